@@ -1,0 +1,26 @@
+"""CPU oracle for paged decode attention over prefix-aliased KV blocks.
+
+TEST INFRASTRUCTURE ONLY.  Everything in this package is a plain, slow,
+by-the-definition CPU implementation used to check the HIP library.  It shares
+no code with the library (no common helpers, constants or tables), imports
+nothing from it, and must never be called from the product path: only the test
+suite, the smoke check and the benchmark's CPU-baseline leg use it.
+
+What pins each function (see the tests that do not need a GPU):
+
+* attention.decode_attention - brute-force scalar loops on tiny inputs; closed
+  forms of softmax attention (one token, equal keys, constant values, a
+  dominating key); a third opinion from a dense fp64 library attention on a
+  contiguous table; invariance under physical block placement and under
+  duplicated histories; exact split-and-merge identity.
+* block_tables.build_block_tables - the aliasing rule is written out directly
+  on token prefixes (no hash); pinned by the structure the paper's sharing
+  patterns imply (shared columns, distinct ids, reference counts) and by a
+  quadratic all-pairs prefix comparison on small batches.
+* hashing.chunk_hashes - count, cumulativity and the prefix-consistency
+  property ("equal at level l iff equal first l*K tokens") follow the paper's
+  worked example and Algorithm 2's structure.  The paper prints no hash values
+  and leaves Hash/InitConst open, so the *values* follow this build's written
+  specification only: parity of hash values is "parity unpinned" beyond two
+  independently written implementations agreeing bit for bit.
+"""
