@@ -1,0 +1,210 @@
+/*
+ * fea - paged decode attention over prefix-aliased KV blocks, for gfx950.
+ *
+ * C ABI of libfea.so.  Plain pointers and sizes only.  Every pointer argument
+ * is marked HOST or DEVICE below.  The library never allocates or frees device
+ * memory: the caller owns q, the KV caches, tables, outputs and the workspace.
+ * The library owns only host bookkeeping behind fea_kv_pool.
+ *
+ * Every call returns a status: FEA_OK (0) or a negative code.  After a failure
+ * fea_last_error() returns a thread-local, human-readable message, and no
+ * output argument has been written (fea_build_block_tables additionally rolls
+ * the pool back to its state before the call).  Nothing throws or aborts.
+ *
+ * Device work is enqueued on the caller's HIP stream and the call returns
+ * without synchronising.  Contents of device buffers are never inspected on
+ * the host.
+ */
+#ifndef FEA_H
+#define FEA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FEA_OK       0
+#define FEA_EINVAL  (-1)   /* bad argument (null pointer, unsupported shape, ...)        */
+#define FEA_ENOMEM  (-2)   /* the KV pool has too few free blocks                        */
+#define FEA_ERANGE  (-3)   /* a caller-provided table or workspace is too small          */
+#define FEA_EHIP    (-4)   /* the HIP runtime reported an error (message has the detail) */
+
+#define FEA_DTYPE_F32   0  /* q, caches, out are float32; arithmetic float32             */
+#define FEA_DTYPE_BF16  1  /* q, caches, out are bfloat16; products/accumulation float32 */
+
+#define FEA_BLOCK_TOKENS 16  /* tokens per KV block (the paper's Section 3 setup; also the
+                                chunk size K of the prefix hashes, Section 4.2)          */
+
+/* flags for fea_attn_params.flags */
+#define FEA_FLAG_REUSE_PLAN 1  /* skip alias detection: the workspace still holds the plan
+                                  of the previous call, and tables/lengths/B/params are
+                                  unchanged since (e.g. the other layers of one step)    */
+
+typedef struct fea_kv_pool fea_kv_pool;
+
+/* Shape of one attention call.  Query head h reads KV head h / (num_q_heads /
+ * num_kv_heads) (grouped-query attention with contiguous groups). */
+typedef struct fea_attn_params {
+    int32_t num_q_heads;
+    int32_t num_kv_heads;   /* must divide num_q_heads                                   */
+    int32_t head_dim;       /* f32: 32, 64, 128 or 256.  bf16: 64, 128 or 256            */
+    int32_t block_size;     /* must be FEA_BLOCK_TOKENS                                  */
+    int32_t dtype;          /* FEA_DTYPE_*                                               */
+    float   scale;          /* softmax scale; 0 means 1/sqrt(head_dim) (Section 2.1)     */
+    int32_t split_blocks;   /* KV blocks per work item; 0 lets the planner choose        */
+    int32_t max_group;      /* 0: group any number of requests that alias a leading run
+                               of blocks; 1: treat every request on its own              */
+    int32_t flags;          /* FEA_FLAG_*                                                */
+    int32_t reserved[3];    /* must be 0                                                 */
+} fea_attn_params;
+
+/* Message of the last failure on this thread ("" if none).  HOST string owned
+ * by the library, valid until the next failing call on the same thread. */
+const char* fea_last_error(void);
+
+/* ------------------------------------------------------------------------
+ * KV block pool (host bookkeeping only).
+ *
+ * The paper's engines keep the KV cache in 16-token blocks and reuse a block
+ * between requests whose token prefixes agree up to and including that block
+ * (Section 2.2, hash-identified block reuse; Section 3, paged KV).  The pool
+ * hands out block ids (indices into dimension 0 of the caller's K/V tensors),
+ * counts references, and remembers which prefix each shared block stores.
+ *
+ * perm_seed == 0: ids are handed out 0, 1, 2, ...  Otherwise the initial free
+ * list is shuffled: s = perm_seed; for k = num_blocks-1 .. 1: s += GAMMA;
+ * j = mix(s) mod (k+1); swap(free[k], free[j])  (mix and GAMMA as documented at
+ * fea_chunk_hashes).  Blocks are taken from the head of the free list; released
+ * blocks are appended at its tail.
+ *
+ * Errors: FEA_EINVAL for num_blocks == 0, block_size != 16 or out == NULL.
+ */
+int32_t fea_kv_alloc(uint32_t num_blocks, uint32_t block_size, uint64_t perm_seed,
+                     fea_kv_pool** out /* HOST */);
+int32_t fea_kv_free(fea_kv_pool* pool);
+
+/* Pool counters.  Any output pointer may be NULL.  refcounts: HOST int32[num_blocks]. */
+int32_t fea_kv_stats(const fea_kv_pool* pool, uint32_t* num_blocks, uint32_t* free_blocks,
+                     uint32_t* hash_collisions, int32_t* refcounts);
+
+/* ------------------------------------------------------------------------
+ * Chunked cumulative prefix hashes of one token sequence (HOST in, HOST out).
+ *
+ * The chunk-parallel formulation of the paper's prefix hash computation
+ * (Appendix "Prefix Hash Computation", Algorithm 2; Section 4.2 "Hash
+ * Vectors"): each chunk of K = 16 tokens is hashed independently into a leaf,
+ * the leaves are chained h_c = Hash(h_{c-1} || leaf_c) from a fixed h_0, and a
+ * trailing partial chunk is hashed too, giving C = ceil(T/16) values with the
+ * property that h_c is equal for two sequences iff their first 16c tokens are.
+ * The paper leaves Hash and h_0 open; this library fixes (mod 2^64):
+ *   mix(x):  x ^= x>>30; x *= 0xBF58476D1CE4E5B9; x ^= x>>27;
+ *            x *= 0x94D049BB133111EB; x ^= x>>31
+ *   GAMMA  = 0x9E3779B97F4A7C15
+ *   leaf   : a = mix(GAMMA ^ n); a = mix(a ^ (uint32)t_j), j = 1..n; n = chunk length
+ *   chain  : h_0 = 0x243F6A8885A308D3; h_c = mix(mix(h_{c-1} + GAMMA) ^ leaf_c)
+ *
+ * hashes must hold ceil(T/16) values.  T == 0 writes nothing.
+ * Errors: FEA_EINVAL for T < 0 or a NULL pointer with T > 0.
+ */
+int32_t fea_chunk_hashes(const int32_t* tokens /* HOST [T] */, int64_t T,
+                         uint64_t* hashes /* HOST [ceil(T/16)] */);
+
+/* ------------------------------------------------------------------------
+ * Block tables for a batch, with prefix aliasing (HOST in, HOST out).
+ *
+ * For request i (tokens[tok_offsets[i] .. tok_offsets[i+1])) and column c the
+ * table entry is the physical block holding tokens [16c, 16c+16) of exactly
+ * that request's prefix.  Two requests get the same block in column c iff c is
+ * a full chunk of both and their first 16(c+1) tokens are equal (Section 4.2:
+ * same hash at level l iff same first l*K tokens; Section 2.2: block reuse when
+ * hash sequences match).  A trailing partial chunk always gets a fresh block of
+ * its own (decode appends into it).  Requests are processed in index order and
+ * columns left to right; a column whose prefix is already stored (by this call
+ * or an earlier one on the same pool) reuses that block and takes a reference,
+ * any other column takes the head of the free list.  Lookup is by (level,
+ * cumulative hash) and every hit is verified against the stored tokens and the
+ * parent block, so a hash collision can never alias different prefixes.
+ *
+ *   block_tables  HOST int32 [B, max_blocks_per_seq], unused columns = -1
+ *   seq_lens      HOST int32 [B]      = tok_offsets[i+1] - tok_offsets[i]
+ *   hashes        HOST uint64, all requests back to back, or NULL
+ *   hash_offsets  HOST int64 [B+1] start of each request's hashes, or NULL
+ *
+ * Errors: FEA_EINVAL (NULL/negative arguments, non-monotone offsets),
+ * FEA_ERANGE (a request needs more than max_blocks_per_seq blocks), FEA_ENOMEM
+ * (pool exhausted).  On any error the pool and all outputs are as before.
+ */
+int32_t fea_build_block_tables(fea_kv_pool* pool,
+                               const int32_t* tokens, const int64_t* tok_offsets, int32_t B,
+                               int32_t max_blocks_per_seq,
+                               int32_t* block_tables, int32_t* seq_lens,
+                               uint64_t* hashes, int64_t* hash_offsets);
+
+/* Drops one reference from each of the nb blocks of a finished request's table
+ * row (HOST).  A block whose count reaches zero forgets its prefix and joins the
+ * tail of the free list - the pool-side counterpart of removing a finished
+ * request (Section 4.2, "Removing a Request from the Active Batch").
+ * Errors: FEA_EINVAL for ids out of range or blocks that hold no reference;
+ * nothing is released in that case. */
+int32_t fea_release(fea_kv_pool* pool, const int32_t* block_table_row /* HOST [nb] */, int32_t nb);
+
+/* Host-side check of a table (for tests and debugging; HOST pointers): every
+ * entry in columns < ceil(seq_lens[i]/16) lies in [0, num_blocks), seq_lens are
+ * non-negative and fit table_stride.  Returns FEA_OK or FEA_EINVAL. */
+int32_t fea_validate_block_tables(const int32_t* block_tables, int32_t table_stride,
+                                  const int32_t* seq_lens, int32_t B, uint32_t num_blocks);
+
+/* ------------------------------------------------------------------------
+ * Decode attention (DEVICE pointers, asynchronous on hip_stream).
+ *
+ * For every request i and query head h, with L = seq_lens[i] cached tokens
+ * found through block_tables[i]:
+ *     out[i,h,:] = sum_t softmax_t( q[i,h,:] . k_t * scale ) v_t
+ * i.e. softmax(Q K^T / sqrt(d)) V for the single decode query of each request
+ * against its whole KV history (Section 2.1; the full-cache sweep per decode
+ * step of Section 1).  seq_lens[i] counts the tokens attended to; the current
+ * token's K/V must already be in the cache.  seq_lens[i] == 0 gives a zero row.
+ *
+ * Layouts (all contiguous):
+ *   q, out        [B, num_q_heads, head_dim]
+ *   k_cache       [num_blocks, num_kv_heads, 16, head_dim]   (v_cache alike)
+ *   block_tables  int32 [B, table_stride]; only columns < ceil(L_i/16) are read
+ *   seq_lens      int32 [B], each <= 16 * table_stride
+ * The result is correct for ANY table whose read entries are valid block ids:
+ * blocks may repeat inside a row and alias between rows at any position.
+ * Requests whose rows start with the same run of block ids are detected on the
+ * device and that run is swept once for all of them.
+ *
+ *   workspace     DEVICE scratch of at least fea_decode_workspace_bytes() bytes,
+ *                 256-byte aligned; contents are overwritten.  Calls that share
+ *                 a workspace must be ordered on one stream.
+ *   hip_stream    a hipStream_t (NULL = the default stream)
+ *
+ * Errors: FEA_EINVAL (NULL pointer, unsupported params, B < 0), FEA_ERANGE
+ * (workspace_bytes too small), FEA_EHIP (launch failure).  B == 0 is a no-op.
+ */
+int32_t fea_decode_workspace_bytes(const fea_attn_params* p, int32_t B, int32_t table_stride,
+                                   size_t* out_bytes /* HOST */);
+
+int32_t fea_decode_attention(const fea_attn_params* p,
+                             const void* q, const void* k_cache, const void* v_cache,
+                             const int32_t* block_tables, int32_t table_stride,
+                             const int32_t* seq_lens, int32_t B,
+                             void* out,
+                             void* workspace, size_t workspace_bytes,
+                             void* hip_stream);
+
+/* Summary of the plan the last fea_decode_attention call left in `workspace`
+ * (synchronises hip_stream; for tests, tuning and the benchmark's reporting).
+ * info: HOST int32[8] = { work items, prefix groups, requests in groups,
+ * blocks per work item, partial rows, shared-run blocks (sum over groups),
+ * kernel variant (0 generic, 1 MFMA), overflow flag }. */
+int32_t fea_decode_plan_info(const void* workspace /* DEVICE */, void* hip_stream,
+                             int32_t* info /* HOST [8] */);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FEA_H */

@@ -1,0 +1,201 @@
+// fea_decode_attention: argument checks, workspace carving and the three launches
+// (plan, KV sweep, merge).  No device memory is allocated here and nothing
+// synchronises except fea_decode_plan_info.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+
+#include "../../include/fea.h"
+#include "fea_internal.h"
+#include "fea_plan.h"
+
+namespace fea {
+
+static size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+static int env_int(const char* name, int dflt) {
+    const char* v = std::getenv(name);
+    if (!v || !*v) return dflt;
+    return std::atoi(v);
+}
+
+static bool is_pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
+
+struct Resolved {
+    int variant;      // 0 generic, 1 MFMA
+    int G, mpt, grouping, split_user;
+    PlanTuning tune;
+    WsLayout lay;
+};
+
+static int32_t check_params(const fea_attn_params* p, const char* who) {
+    if (!p) return fail(FEA_EINVAL, "%s: params is NULL", who);
+    if (p->num_q_heads <= 0 || p->num_kv_heads <= 0 || p->num_q_heads % p->num_kv_heads != 0)
+        return fail(FEA_EINVAL, "%s: num_q_heads=%d must be a positive multiple of num_kv_heads=%d", who, p->num_q_heads, p->num_kv_heads);
+    if (p->block_size != FEA_BLOCK_TOKENS) return fail(FEA_EINVAL, "%s: block_size=%d, only %d is supported", who, p->block_size, FEA_BLOCK_TOKENS);
+    if (p->dtype != FEA_DTYPE_F32 && p->dtype != FEA_DTYPE_BF16) return fail(FEA_EINVAL, "%s: unknown dtype %d", who, p->dtype);
+    const int d = p->head_dim;
+    const bool d_ok = p->dtype == FEA_DTYPE_F32 ? (d == 32 || d == 64 || d == 128 || d == 256) : (d == 64 || d == 128 || d == 256);
+    if (!d_ok) return fail(FEA_EINVAL, "%s: head_dim=%d not supported for this dtype", who, d);
+    if (!(p->scale >= 0.f) || !std::isfinite(p->scale)) return fail(FEA_EINVAL, "%s: scale must be finite and >= 0", who);
+    if (p->split_blocks < 0 || p->max_group < 0) return fail(FEA_EINVAL, "%s: split_blocks and max_group must be >= 0", who);
+    if (p->flags & ~FEA_FLAG_REUSE_PLAN) return fail(FEA_EINVAL, "%s: unknown flag bits 0x%x", who, p->flags);
+    if (p->reserved[0] || p->reserved[1] || p->reserved[2]) return fail(FEA_EINVAL, "%s: reserved fields must be 0", who);
+    return FEA_OK;
+}
+
+static int32_t resolve(const fea_attn_params* p, int32_t B, int32_t stride, Resolved& r, const char* who) {
+    if (B < 0 || stride < 0) return fail(FEA_EINVAL, "%s: negative B or table_stride", who);
+    if ((int64_t)B * p->num_q_heads > 0x3FFFFFFF || (int64_t)stride * kBlock > 0x3FFFFFFF)
+        return fail(FEA_EINVAL, "%s: problem too large (B*Hq or sequence length overflows)", who);
+    r.G = p->num_q_heads / p->num_kv_heads;
+    const bool mfma_ok = p->dtype == FEA_DTYPE_BF16 && p->head_dim == 128 && is_pow2(r.G) && r.G <= 16;
+    r.variant = (mfma_ok && !env_int("FEA_FORCE_GENERIC", 0)) ? 1 : 0;
+    r.mpt = r.G >= kTileRows ? 1 : kTileRows / r.G;
+    r.grouping = p->max_group == 1 ? 0 : 1;
+    r.split_user = p->split_blocks > 0 ? ((p->split_blocks + 1) & ~1) : 0;
+    r.tune.target_items = std::max(64, env_int("FEA_TARGET_ITEMS", 1024));
+    r.tune.min_split = std::max(2, env_int("FEA_MIN_SPLIT", 8));
+    r.tune.min_run = std::max(1, env_int("FEA_MIN_RUN", 2));
+    const int64_t rows = (int64_t)B * p->num_q_heads;
+    const int64_t budget = std::max<int64_t>(16384, (int64_t)env_int("FEA_ROW_BUDGET_MULT", 16) * rows);
+    r.tune.row_budget = (int32_t)std::min<int64_t>(budget, 0x3FFFFFFF);
+
+    int64_t max_items, max_rows;
+    if (r.split_user > 0) {
+        const int64_t per = (stride + r.split_user - 1) / r.split_user;
+        max_items = 2ll * B * p->num_kv_heads * per + 64;
+        max_rows = 2ll * rows * per + 64;
+    } else {
+        max_items = (int64_t)r.tune.target_items + 2ll * B * p->num_kv_heads + 64;
+        max_rows = (int64_t)r.tune.row_budget + 2 * rows + 64;
+    }
+    if (max_items > 0x3FFFFFFF || max_rows > 0x3FFFFFFF) return fail(FEA_EINVAL, "%s: split_blocks too small for this problem size", who);
+    WsLayout& l = r.lay;
+    size_t off = up256(H_WORDS * sizeof(int32_t));
+    l.req = off;      off += up256((size_t)B * sizeof(ReqDesc));
+    l.grp = off;      off += up256((size_t)B * sizeof(GroupDesc));
+    l.members = off;  off += up256((size_t)B * sizeof(int32_t));
+    l.items = off;    off += up256((size_t)max_items * sizeof(Item));
+    l.ml = off;       off += up256((size_t)max_rows * 2 * sizeof(float));
+    l.acc = off;      off += up256((size_t)max_rows * p->head_dim * sizeof(float));
+    l.total = off;
+    l.max_items = (int32_t)max_items;
+    l.max_rows = (int32_t)max_rows;
+    return FEA_OK;
+}
+
+static int cu_count() {
+    static int n = 0;
+    if (n == 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) n = prop.multiProcessorCount;
+        if (n <= 0) n = 256;
+    }
+    return n;
+}
+
+}  // namespace fea
+
+using namespace fea;
+
+extern "C" {
+
+int32_t fea_decode_workspace_bytes(const fea_attn_params* p, int32_t B, int32_t table_stride, size_t* out_bytes) {
+    if (!out_bytes) return fail(FEA_EINVAL, "fea_decode_workspace_bytes: out_bytes is NULL");
+    int32_t rc = check_params(p, "fea_decode_workspace_bytes");
+    if (rc != FEA_OK) return rc;
+    Resolved r;
+    rc = resolve(p, B, table_stride, r, "fea_decode_workspace_bytes");
+    if (rc != FEA_OK) return rc;
+    *out_bytes = r.lay.total;
+    return FEA_OK;
+}
+
+int32_t fea_decode_attention(const fea_attn_params* p, const void* q, const void* k_cache, const void* v_cache,
+                             const int32_t* block_tables, int32_t table_stride, const int32_t* seq_lens, int32_t B,
+                             void* out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    int32_t rc = check_params(p, "fea_decode_attention");
+    if (rc != FEA_OK) return rc;
+    Resolved r;
+    rc = resolve(p, B, table_stride, r, "fea_decode_attention");
+    if (rc != FEA_OK) return rc;
+    if (B == 0) return FEA_OK;
+    if (!q || !k_cache || !v_cache || !block_tables || !seq_lens || !out || !workspace)
+        return fail(FEA_EINVAL, "fea_decode_attention: NULL device pointer");
+    if (((uintptr_t)workspace & 255) != 0) return fail(FEA_EINVAL, "fea_decode_attention: workspace must be 256-byte aligned");
+    if (((uintptr_t)q & 15) || ((uintptr_t)k_cache & 15) || ((uintptr_t)v_cache & 15) || ((uintptr_t)out & 15))
+        return fail(FEA_EINVAL, "fea_decode_attention: q, caches and out must be 16-byte aligned");
+    if (workspace_bytes < r.lay.total)
+        return fail(FEA_ERANGE, "fea_decode_attention: workspace has %zu bytes, %zu needed", workspace_bytes, r.lay.total);
+
+    const float scale = p->scale > 0.f ? p->scale : 1.0f / std::sqrt((float)p->head_dim);
+    if (!(p->flags & FEA_FLAG_REUSE_PLAN)) {
+        PlanArgs pa;
+        std::memset(&pa, 0, sizeof pa);
+        pa.bt = block_tables;
+        pa.seq_lens = seq_lens;
+        pa.ws = static_cast<char*>(workspace);
+        pa.lay = r.lay;
+        pa.tune = r.tune;
+        pa.stride = table_stride;
+        pa.B = B;
+        pa.Hq = p->num_q_heads;
+        pa.Hkv = p->num_kv_heads;
+        pa.G = r.G;
+        pa.mpt = r.mpt;
+        pa.grouping = r.grouping;
+        pa.split_user = r.split_user;
+        pa.variant = r.variant;
+        launch_plan(pa, hip_stream);
+    }
+    SweepArgs sa;
+    std::memset(&sa, 0, sizeof sa);
+    sa.q = q;
+    sa.k_cache = k_cache;
+    sa.v_cache = v_cache;
+    sa.bt = block_tables;
+    sa.out = out;
+    sa.ws = static_cast<char*>(workspace);
+    sa.lay = r.lay;
+    sa.scale_log2 = scale * 1.4426950408889634f;
+    sa.stride = table_stride;
+    sa.B = B;
+    sa.Hq = p->num_q_heads;
+    sa.Hkv = p->num_kv_heads;
+    sa.G = r.G;
+    sa.mpt = r.mpt;
+    if (r.variant == 1) {
+        launch_sweep_mfma(sa, std::max(1, env_int("FEA_SWEEP_GRID", cu_count())), hip_stream);
+    } else {
+        const int grid = std::min(r.lay.max_items, std::max(1, env_int("FEA_SWEEP_GRID", 8 * cu_count())));
+        launch_sweep_generic(sa, p->dtype, p->head_dim, grid, hip_stream);
+    }
+    launch_merge(sa, p->dtype, p->head_dim, hip_stream);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(FEA_EHIP, "fea_decode_attention: launch failed: %s", hipGetErrorString(e));
+    return FEA_OK;
+}
+
+int32_t fea_decode_plan_info(const void* workspace, void* hip_stream, int32_t* info) {
+    if (!workspace || !info) return fail(FEA_EINVAL, "fea_decode_plan_info: NULL pointer");
+    int32_t hdr[H_WORDS];
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    hipError_t e = hipMemcpyAsync(hdr, workspace, sizeof hdr, hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e != hipSuccess) return fail(FEA_EHIP, "fea_decode_plan_info: %s", hipGetErrorString(e));
+    info[0] = hdr[H_ITEMS];
+    info[1] = hdr[H_GROUPS];
+    info[2] = hdr[H_GROUPED];
+    info[3] = hdr[H_SPLIT];
+    info[4] = hdr[H_ROWS];
+    info[5] = hdr[H_SHARED_BLOCKS];
+    info[6] = hdr[H_VARIANT];
+    info[7] = hdr[H_OVERFLOW];
+    return FEA_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,109 @@
+// Device-resident plan of one decode-attention call: which requests alias a
+// leading run of KV blocks, how the KV sweep is cut into work items, and where
+// each item's partial result goes.  Shared by the planner, the sweep kernels and
+// the merge kernel.
+#pragma once
+#include <cstddef>
+#include <cstdint>
+
+namespace fea {
+
+constexpr int kBlock = 16;            // tokens per KV block
+constexpr int kPlanThreads = 1024;    // the planner is one workgroup
+constexpr int kGroupReqMax = 2048;    // requests with index >= this are never grouped
+constexpr int kHashSlots = 4096;      // LDS hash slots for leader finding (2x kGroupReqMax)
+constexpr int kTileRows = 64;         // query rows one MFMA work item carries at most
+
+// header words (int32) at the start of the workspace
+enum Hdr {
+    H_ITEMS = 0,       // number of work items
+    H_QUEUE = 1,       // next item to hand out (zero between calls)
+    H_GROUPS = 2,      // prefix groups found
+    H_GROUPED = 3,     // requests that belong to a group
+    H_SPLIT = 4,       // KV blocks per work item
+    H_ROWS = 5,        // partial rows in use
+    H_SHARED_BLOCKS = 6,
+    H_VARIANT = 7,     // 0 generic, 1 MFMA
+    H_OVERFLOW = 8,    // planner ran out of item/partial capacity (never by construction)
+    H_WORDS = 64
+};
+
+struct ReqDesc {       // one per request
+    int32_t group;     // leader request id of its group, or -1
+    int32_t rank;      // position inside the group
+    int32_t priv_c0;   // first private column (= shared run length, 0 if ungrouped)
+    int32_t priv_nsplits;
+    int32_t priv_pbase;   // first partial row of the private segment
+    int32_t nb;        // ceil(L / 16)
+    int32_t L;
+    int32_t priv_item_base;
+};
+
+struct GroupDesc {     // indexed by leader request id; valid only where members >= 2
+    int32_t leader;
+    int32_t members;
+    int32_t run;       // aliased leading blocks (full blocks of every member)
+    int32_t nsplits;
+    int32_t pbase;     // first partial row of the shared segment
+    int32_t member_off;   // into the member list
+    int32_t tiles;     // row tiles (members are cut into tiles of members_per_tile)
+    int32_t item_base;
+};
+
+struct Item {          // one KV sweep: a row set x one KV head x a column range
+    int32_t kind;      // 0: one request's private columns, 1: a group's shared run
+    int32_t who;       // request id / leader id
+    int32_t g;         // KV head
+    int32_t tile;      // row tile inside the group
+    int32_t c0, c1;    // table columns [c0, c1) of `who`'s row
+    int32_t pbase;     // partial row of the item's first query row
+    int32_t tok_end;   // tokens at positions >= tok_end are not attended to
+};
+
+// Byte offsets of the workspace sections (all multiples of 256).
+struct WsLayout {
+    size_t req, grp, members, items, ml, acc, total;
+    int32_t max_items, max_rows;
+};
+
+// Planner tuning (host constants, overridable through the environment for sweeps).
+struct PlanTuning {
+    int32_t target_items;   // aim for about this many work items
+    int32_t min_split;      // never cut finer than this many blocks
+    int32_t row_budget;     // cap on partial rows beyond 2*B*Hq
+    int32_t min_run;        // shortest aliased run worth sweeping jointly
+};
+
+struct PlanArgs {
+    const int32_t* bt;
+    const int32_t* seq_lens;
+    char* ws;
+    WsLayout lay;
+    PlanTuning tune;
+    int32_t stride, B, Hq, Hkv, G;
+    int32_t mpt;         // members (requests) per row tile
+    int32_t grouping;    // 0: every request on its own
+    int32_t split_user;  // 0: choose
+    int32_t variant;
+};
+
+// Everything the sweep and merge kernels need besides the plan in the workspace.
+struct SweepArgs {
+    const void* q;
+    const void* k_cache;
+    const void* v_cache;
+    const int32_t* bt;
+    void* out;
+    char* ws;
+    WsLayout lay;
+    float scale_log2;    // softmax scale times log2(e): scores live in the base-2 domain
+    int32_t stride, B, Hq, Hkv, G, mpt;
+};
+
+// launchers (defined next to their kernels); stream is a hipStream_t
+void launch_plan(const PlanArgs& a, void* stream);
+void launch_sweep_generic(const SweepArgs& a, int dtype, int head_dim, int grid, void* stream);
+void launch_sweep_mfma(const SweepArgs& a, int grid, void* stream);
+void launch_merge(const SweepArgs& a, int dtype, int head_dim, void* stream);
+
+}  // namespace fea

@@ -1,0 +1,303 @@
+// Generic KV sweep (plain vector ALU) and the merge of partial results.
+//
+// The generic sweep serves float32 caches and every shape the MFMA sweep does not
+// take.  One workgroup per work item; scores of a 256-token piece are staged in
+// LDS, the softmax runs online across pieces (running maximum and sum), and the
+// value accumulation is reduced across the workgroup at the end.  Everything is
+// float32; scores are kept in the base-2 domain (score * scale * log2 e) so that
+// the exponential is a bare v_exp_f32.
+//
+// Computes, for the item's token range R and each query head h of its KV head:
+//   m = max_{t in R} s_t,  l = sum_t 2^(s_t - m),  acc = sum_t 2^(s_t - m) v_t
+// with s_t = (q_h . k_t) * scale * log2(e)  -- the pieces of
+// softmax(q K^T / sqrt(d)) V (Section 2.1) that the merge kernel combines.
+#include <hip/hip_runtime.h>
+
+#include "../../include/fea.h"
+#include "fea_plan.h"
+
+namespace fea {
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+    static constexpr int kPerLoad = 4;   // elements in one 16-byte load
+    __device__ static void load(const float* p, float (&f)[4]) {
+        const float4 v = *reinterpret_cast<const float4*>(p);
+        f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
+    }
+    __device__ static void store(float* p, float v) { *p = v; }
+};
+struct bf16_t { uint16_t bits; };
+template <> struct Elem<bf16_t> {
+    static constexpr int kPerLoad = 8;
+    __device__ static void load(const bf16_t* p, float (&f)[8]) {
+        const uint4 v = *reinterpret_cast<const uint4*>(p);
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            f[2 * k] = __uint_as_float(w[k] << 16);
+            f[2 * k + 1] = __uint_as_float(w[k] & 0xFFFF0000u);
+        }
+    }
+    __device__ static void store(bf16_t* p, float v) {   // round to nearest even
+        uint32_t u = __float_as_uint(v);
+        if ((u & 0x7FFFFFFFu) > 0x7F800000u) { p->bits = 0x7FC0; return; }
+        u += 0x7FFFu + ((u >> 16) & 1u);
+        p->bits = (uint16_t)(u >> 16);
+    }
+};
+
+constexpr int kGenThreads = 256;
+constexpr int kGenWaves = kGenThreads / 64;
+constexpr int kPiece = 256;   // tokens whose scores are staged at once
+constexpr int kHB = 4;        // query heads handled per pass over the KV range
+
+template <typename T, int D>
+__global__ __launch_bounds__(kGenThreads) void sweep_generic_kernel(SweepArgs a) {
+    constexpr int EPL = Elem<T>::kPerLoad;
+    constexpr int LPT = D / EPL;          // lanes that share one token row
+    constexpr int TPW = 64 / LPT;         // token rows per wave-wide load
+    static_assert(LPT >= 1 && LPT <= 64 && (LPT & (LPT - 1)) == 0, "head_dim not supported");
+
+    __shared__ float s_sc[kHB][kPiece];
+    __shared__ float s_alpha[kHB], s_m[kHB], s_l[kHB];
+    __shared__ float s_red[kGenWaves][kHB][D];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c = lane % LPT, r = lane / LPT;
+    const int* hdr = reinterpret_cast<const int*>(a.ws);
+    const Item* items = reinterpret_cast<const Item*>(a.ws + a.lay.items);
+    float2* ml = reinterpret_cast<float2*>(a.ws + a.lay.ml);
+    float* pacc = reinterpret_cast<float*>(a.ws + a.lay.acc);
+    const T* Q = static_cast<const T*>(a.q);
+    const T* K = static_cast<const T*>(a.k_cache);
+    const T* V = static_cast<const T*>(a.v_cache);
+    const int n_items = hdr[H_ITEMS];
+
+    for (int it = blockIdx.x; it < n_items; it += gridDim.x) {
+        const Item item = items[it];
+        const int32_t* row = a.bt + (size_t)item.who * a.stride;
+        const int t_begin = item.c0 * kBlock, t_end = item.tok_end;
+        // query rows of the item: one request, or the members of a group's row tile
+        // (the vector path simply sweeps the shared run once per member)
+        int n_mem = 1;
+        const int* mlist = nullptr;
+        if (item.kind == 1) {
+            const GroupDesc gd = reinterpret_cast<const GroupDesc*>(a.ws + a.lay.grp)[item.who];
+            const int first = item.tile * a.mpt;
+            n_mem = min(a.mpt, gd.members - first);
+            mlist = reinterpret_cast<const int*>(a.ws + a.lay.members) + gd.member_off + first;
+        }
+        for (int mh = 0; mh < n_mem * ((a.G + kHB - 1) / kHB); ++mh) {
+            const int mem = mh / ((a.G + kHB - 1) / kHB);
+            const int hb = (mh % ((a.G + kHB - 1) / kHB)) * kHB;
+            const int qreq = mlist ? mlist[mem] : item.who;
+            const int prow0 = item.pbase + mem * a.G + hb;
+            const int nh = min(kHB, a.G - hb);
+            float qf[kHB][EPL];
+#pragma unroll
+            for (int j = 0; j < kHB; ++j) {
+                if (j < nh) {
+                    Elem<T>::load(Q + ((size_t)qreq * a.Hq + item.g * a.G + hb + j) * D + c * EPL, qf[j]);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < EPL; ++e) qf[j][e] = 0.f;
+                }
+            }
+            float acc[kHB][EPL];
+#pragma unroll
+            for (int j = 0; j < kHB; ++j)
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) acc[j][e] = 0.f;
+            float m_run = -INFINITY, l_run = 0.f;   // meaningful in wave j for head j
+
+            for (int p0 = t_begin; p0 < t_end; p0 += kPiece) {
+                const int np = min(kPiece, t_end - p0);
+                // scores
+                for (int tt = wave * TPW + r; tt < np; tt += kGenWaves * TPW) {
+                    const int t = p0 + tt;
+                    const int blk = row[t / kBlock];
+                    float kf[EPL];
+                    Elem<T>::load(K + (((size_t)blk * a.Hkv + item.g) * kBlock + (t % kBlock)) * D + c * EPL, kf);
+                    float dot[kHB];
+#pragma unroll
+                    for (int j = 0; j < kHB; ++j) {
+                        float s = 0.f;
+#pragma unroll
+                        for (int e = 0; e < EPL; ++e) s = fmaf(qf[j][e], kf[e], s);
+                        dot[j] = s;
+                    }
+#pragma unroll
+                    for (int o = LPT / 2; o >= 1; o >>= 1)
+#pragma unroll
+                        for (int j = 0; j < kHB; ++j) dot[j] += __shfl_xor(dot[j], o);
+                    if (c == 0) {
+#pragma unroll
+                        for (int j = 0; j < kHB; ++j) s_sc[j][tt] = dot[j] * a.scale_log2;
+                    }
+                }
+                __syncthreads();
+                // softmax bookkeeping: wave j owns head j
+                if (wave < kHB) {
+                    const int j = wave;
+                    float mx = -INFINITY;
+                    for (int tt = lane; tt < np; tt += 64) mx = fmaxf(mx, s_sc[j][tt]);
+#pragma unroll
+                    for (int o = 32; o >= 1; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+                    const float m_new = fmaxf(m_run, mx);
+                    float sum = 0.f;
+                    for (int tt = lane; tt < np; tt += 64) {
+                        const float p = exp2f(s_sc[j][tt] - m_new);
+                        s_sc[j][tt] = p;
+                        sum += p;
+                    }
+#pragma unroll
+                    for (int o = 32; o >= 1; o >>= 1) sum += __shfl_xor(sum, o);
+                    const float alpha = exp2f(m_run - m_new);   // 0 on the first piece
+                    l_run = l_run * alpha + sum;
+                    m_run = m_new;
+                    if (lane == 0) { s_alpha[j] = alpha; s_m[j] = m_run; s_l[j] = l_run; }
+                }
+                __syncthreads();
+                // values
+#pragma unroll
+                for (int j = 0; j < kHB; ++j) {
+                    const float al = s_alpha[j];
+#pragma unroll
+                    for (int e = 0; e < EPL; ++e) acc[j][e] *= al;
+                }
+                for (int tt = wave * TPW + r; tt < np; tt += kGenWaves * TPW) {
+                    const int t = p0 + tt;
+                    const int blk = row[t / kBlock];
+                    float vf[EPL];
+                    Elem<T>::load(V + (((size_t)blk * a.Hkv + item.g) * kBlock + (t % kBlock)) * D + c * EPL, vf);
+#pragma unroll
+                    for (int j = 0; j < kHB; ++j) {
+                        const float p = s_sc[j][tt];
+#pragma unroll
+                        for (int e = 0; e < EPL; ++e) acc[j][e] = fmaf(p, vf[e], acc[j][e]);
+                    }
+                }
+                __syncthreads();
+            }
+            // reduce the value sums over the token rows of a wave, then over waves
+#pragma unroll
+            for (int o = LPT; o < 64; o <<= 1)
+#pragma unroll
+                for (int j = 0; j < kHB; ++j)
+#pragma unroll
+                    for (int e = 0; e < EPL; ++e) acc[j][e] += __shfl_xor(acc[j][e], o);
+            if (r == 0) {
+#pragma unroll
+                for (int j = 0; j < kHB; ++j)
+#pragma unroll
+                    for (int e = 0; e < EPL; ++e) s_red[wave][j][c * EPL + e] = acc[j][e];
+            }
+            __syncthreads();
+            for (int x = tid; x < nh * D; x += kGenThreads) {
+                const int j = x / D, e = x % D;
+                float s = 0.f;
+#pragma unroll
+                for (int w = 0; w < kGenWaves; ++w) s += s_red[w][j][e];
+                pacc[(size_t)(prow0 + j) * D + e] = s;
+            }
+            if (tid < nh) ml[prow0 + tid] = make_float2(s_m[tid], s_l[tid]);
+            __syncthreads();
+        }
+    }
+}
+
+// out[i,h,:] = sum_s 2^(m_s - M) acc_s / sum_s 2^(m_s - M) l_s over the partials
+// of row (i,h): the group's shared-run splits followed by the request's own.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void merge_kernel(SweepArgs a) {
+    constexpr int NE = (D + 63) / 64;
+    const int lane = threadIdx.x & 63;
+    const int rowid = blockIdx.x * 4 + (threadIdx.x >> 6);
+    int* hdr = reinterpret_cast<int*>(a.ws);
+    if (blockIdx.x == 0 && threadIdx.x == 0) hdr[H_QUEUE] = 0;   // ready for a plan-reusing call
+    if (rowid >= a.B * a.Hq) return;
+    const int i = rowid / a.Hq, h = rowid % a.Hq;
+    const int g = h / a.G, hh = h % a.G;
+    const ReqDesc rd = reinterpret_cast<const ReqDesc*>(a.ws + a.lay.req)[i];
+    const float2* ml = reinterpret_cast<const float2*>(a.ws + a.lay.ml);
+    const float* pacc = reinterpret_cast<const float*>(a.ws + a.lay.acc);
+    T* out = static_cast<T*>(a.out) + (size_t)rowid * D;
+
+    if (hdr[H_OVERFLOW]) {   // the plan did not fit its buffers: make it loud
+        for (int e = lane; e < D; e += 64) Elem<T>::store(out + e, __uint_as_float(0x7FC00000u));
+        return;
+    }
+    int ns_sh = 0, sh_base = 0, sh_stride = 0;
+    if (rd.group >= 0) {
+        const GroupDesc gd = reinterpret_cast<const GroupDesc*>(a.ws + a.lay.grp)[rd.group];
+        ns_sh = gd.nsplits;
+        sh_stride = a.Hkv * gd.members * a.G;
+        sh_base = gd.pbase + g * gd.members * a.G + rd.rank * a.G + hh;
+    }
+    const int ns_pr = rd.priv_nsplits;
+    const int pr_base = rd.priv_pbase + h;
+    const int ns = ns_sh + ns_pr;
+    auto prow = [&](int s) { return s < ns_sh ? sh_base + s * sh_stride : pr_base + (s - ns_sh) * a.Hq; };
+
+    float M = -INFINITY;
+    for (int s = 0; s < ns; ++s) M = fmaxf(M, ml[prow(s)].x);
+    float num[NE];
+#pragma unroll
+    for (int k = 0; k < NE; ++k) num[k] = 0.f;
+    float den = 0.f;
+    for (int s = 0; s < ns; ++s) {
+        const int pr = prow(s);
+        const float2 v = ml[pr];
+        const float w = exp2f(v.x - M);
+        den = fmaf(w, v.y, den);
+#pragma unroll
+        for (int k = 0; k < NE; ++k) {
+            const int e = lane + 64 * k;
+            if (e < D) num[k] = fmaf(w, pacc[(size_t)pr * D + e], num[k]);
+        }
+    }
+    const float inv = ns > 0 ? 1.f / den : 0.f;
+#pragma unroll
+    for (int k = 0; k < NE; ++k) {
+        const int e = lane + 64 * k;
+        if (e < D) Elem<T>::store(out + e, num[k] * inv);
+    }
+}
+
+template <typename T>
+static void launch_generic_t(const SweepArgs& a, int head_dim, int grid, hipStream_t st) {
+    switch (head_dim) {
+        case 32: hipLaunchKernelGGL((sweep_generic_kernel<T, 32>), dim3(grid), dim3(kGenThreads), 0, st, a); break;
+        case 64: hipLaunchKernelGGL((sweep_generic_kernel<T, 64>), dim3(grid), dim3(kGenThreads), 0, st, a); break;
+        case 128: hipLaunchKernelGGL((sweep_generic_kernel<T, 128>), dim3(grid), dim3(kGenThreads), 0, st, a); break;
+        case 256: hipLaunchKernelGGL((sweep_generic_kernel<T, 256>), dim3(grid), dim3(kGenThreads), 0, st, a); break;
+        default: break;
+    }
+}
+
+void launch_sweep_generic(const SweepArgs& a, int dtype, int head_dim, int grid, void* stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (dtype == FEA_DTYPE_F32) launch_generic_t<float>(a, head_dim, grid, st);
+    else launch_generic_t<bf16_t>(a, head_dim, grid, st);
+}
+
+template <typename T>
+static void launch_merge_t(const SweepArgs& a, int head_dim, hipStream_t st) {
+    const int grid = (a.B * a.Hq + 3) / 4;
+    switch (head_dim) {
+        case 32: hipLaunchKernelGGL((merge_kernel<T, 32>), dim3(grid), dim3(256), 0, st, a); break;
+        case 64: hipLaunchKernelGGL((merge_kernel<T, 64>), dim3(grid), dim3(256), 0, st, a); break;
+        case 128: hipLaunchKernelGGL((merge_kernel<T, 128>), dim3(grid), dim3(256), 0, st, a); break;
+        case 256: hipLaunchKernelGGL((merge_kernel<T, 256>), dim3(grid), dim3(256), 0, st, a); break;
+        default: break;
+    }
+}
+
+void launch_merge(const SweepArgs& a, int dtype, int head_dim, void* stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (dtype == FEA_DTYPE_F32) launch_merge_t<float>(a, head_dim, st);
+    else launch_merge_t<bf16_t>(a, head_dim, st);
+}
+
+}  // namespace fea

@@ -1,0 +1,190 @@
+"""ctypes binding of libfea.so: same names as the C ABI, argument marshalling only."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import numpy as np
+
+FEA_DTYPE_F32 = 0
+FEA_DTYPE_BF16 = 1
+FEA_FLAG_REUSE_PLAN = 1
+_CODES = {-1: "FEA_EINVAL", -2: "FEA_ENOMEM", -3: "FEA_ERANGE", -4: "FEA_EHIP"}
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB: Optional[C.CDLL] = None
+
+
+class FeaError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"{_CODES.get(code, code)}: {message}")
+        self.code = code
+
+
+class AttnParams(C.Structure):
+    _fields_ = [("num_q_heads", C.c_int32), ("num_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("block_size", C.c_int32), ("dtype", C.c_int32), ("scale", C.c_float),
+                ("split_blocks", C.c_int32), ("max_group", C.c_int32), ("flags", C.c_int32),
+                ("reserved", C.c_int32 * 3)]
+
+    def __init__(self, num_q_heads, num_kv_heads, head_dim, dtype, scale=0.0, split_blocks=0,
+                 max_group=0, flags=0, block_size=16):
+        super().__init__(num_q_heads, num_kv_heads, head_dim, block_size, dtype, scale,
+                         split_blocks, max_group, flags)
+
+
+def library_path() -> str:
+    return os.path.join(_HERE, "libfea.so")
+
+
+def load_library() -> C.CDLL:
+    """Loads libfea.so; raises if it has not been built (there is no fallback path)."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = library_path()
+    if not os.path.exists(path):
+        raise ImportError(f"{path} is missing: build it with `python -m paper_2605_06046_amd.build` "
+                          "(or __graft_entry__.build()); there is no CPU fallback")
+    lib = C.CDLL(path)
+    vp, i32, i64, u32, u64 = C.c_void_p, C.c_int32, C.c_int64, C.c_uint32, C.c_uint64
+    sigs = {
+        "fea_last_error": (C.c_char_p, []),
+        "fea_kv_alloc": (i32, [u32, u32, u64, C.POINTER(vp)]),
+        "fea_kv_free": (i32, [vp]),
+        "fea_kv_stats": (i32, [vp, C.POINTER(u32), C.POINTER(u32), C.POINTER(u32), vp]),
+        "fea_chunk_hashes": (i32, [vp, i64, vp]),
+        "fea_build_block_tables": (i32, [vp, vp, vp, i32, i32, vp, vp, vp, vp]),
+        "fea_release": (i32, [vp, vp, i32]),
+        "fea_validate_block_tables": (i32, [vp, i32, vp, i32, u32]),
+        "fea_decode_workspace_bytes": (i32, [C.POINTER(AttnParams), i32, i32, C.POINTER(C.c_size_t)]),
+        "fea_decode_attention": (i32, [C.POINTER(AttnParams), vp, vp, vp, vp, i32, vp, i32, vp, vp, C.c_size_t, vp]),
+        "fea_decode_plan_info": (i32, [vp, vp, vp]),
+    }
+    for name, (res, args) in sigs.items():
+        fn = getattr(lib, name)
+        fn.restype = res
+        fn.argtypes = args
+    _LIB = lib
+    return lib
+
+
+def _check(rc: int) -> None:
+    if rc != 0:
+        raise FeaError(rc, load_library().fea_last_error().decode())
+
+
+def _np_ptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+class KVPool:
+    """Opaque handle of the host-side block pool."""
+
+    def __init__(self, handle):
+        self.handle = handle
+
+    def __del__(self):
+        try:
+            fea_kv_free(self)
+        except Exception:
+            pass
+
+
+def fea_kv_alloc(num_blocks: int, block_size: int = 16, perm_seed: int = 0) -> KVPool:
+    h = C.c_void_p()
+    _check(load_library().fea_kv_alloc(num_blocks, block_size, perm_seed, C.byref(h)))
+    return KVPool(h)
+
+
+def fea_kv_free(pool: KVPool) -> None:
+    if pool.handle:
+        load_library().fea_kv_free(pool.handle)
+        pool.handle = None
+
+
+def fea_kv_stats(pool: KVPool):
+    """(num_blocks, free_blocks, hash_collisions, refcounts[int32])"""
+    lib = load_library()
+    nb, fb, col = C.c_uint32(), C.c_uint32(), C.c_uint32()
+    _check(lib.fea_kv_stats(pool.handle, C.byref(nb), C.byref(fb), C.byref(col), None))
+    rc = np.zeros(nb.value, dtype=np.int32)
+    _check(lib.fea_kv_stats(pool.handle, None, None, None, _np_ptr(rc)))
+    return nb.value, fb.value, col.value, rc
+
+
+def fea_chunk_hashes(tokens: np.ndarray) -> np.ndarray:
+    tokens = np.ascontiguousarray(tokens, dtype=np.int32)
+    out = np.zeros(-(-len(tokens) // 16), dtype=np.uint64)
+    _check(load_library().fea_chunk_hashes(_np_ptr(tokens), len(tokens), _np_ptr(out)))
+    return out
+
+
+def fea_build_block_tables(pool: KVPool, tokens: np.ndarray, tok_offsets: np.ndarray,
+                           max_blocks_per_seq: int, want_hashes: bool = False):
+    """Returns (block_tables[B, max_blocks] int32, seq_lens[B] int32, hashes, hash_offsets)."""
+    tokens = np.ascontiguousarray(tokens, dtype=np.int32)
+    tok_offsets = np.ascontiguousarray(tok_offsets, dtype=np.int64)
+    B = len(tok_offsets) - 1
+    tables = np.full((B, max_blocks_per_seq), -2, dtype=np.int32)
+    lens = np.zeros(B, dtype=np.int32)
+    hashes = hoff = None
+    if want_hashes:
+        total = int(sum(-(-int(t) // 16) for t in np.diff(tok_offsets)))
+        hashes = np.zeros(total, dtype=np.uint64)
+        hoff = np.zeros(B + 1, dtype=np.int64)
+    _check(load_library().fea_build_block_tables(pool.handle, _np_ptr(tokens), _np_ptr(tok_offsets), B,
+                                                 max_blocks_per_seq, _np_ptr(tables), _np_ptr(lens),
+                                                 _np_ptr(hashes), _np_ptr(hoff)))
+    return tables, lens, hashes, hoff
+
+
+def fea_release(pool: KVPool, row: np.ndarray) -> None:
+    row = np.ascontiguousarray(row, dtype=np.int32)
+    _check(load_library().fea_release(pool.handle, _np_ptr(row), len(row)))
+
+
+def fea_validate_block_tables(tables: np.ndarray, seq_lens: np.ndarray, num_blocks: int) -> None:
+    tables = np.ascontiguousarray(tables, dtype=np.int32)
+    seq_lens = np.ascontiguousarray(seq_lens, dtype=np.int32)
+    _check(load_library().fea_validate_block_tables(_np_ptr(tables), tables.shape[1], _np_ptr(seq_lens),
+                                                    tables.shape[0], num_blocks))
+
+
+def fea_decode_workspace_bytes(params: AttnParams, B: int, table_stride: int) -> int:
+    out = C.c_size_t()
+    _check(load_library().fea_decode_workspace_bytes(C.byref(params), B, table_stride, C.byref(out)))
+    return out.value
+
+
+def _dev_ptr(t):
+    return C.c_void_p(t.data_ptr())
+
+
+def fea_decode_attention(params: AttnParams, q, k_cache, v_cache, block_tables, seq_lens, out, workspace,
+                         stream=None) -> None:
+    """All tensor arguments are contiguous torch tensors on the GPU; `stream` is a
+    torch.cuda.Stream (default: the current one).  Asynchronous."""
+    import torch
+    for name, t in (("q", q), ("k_cache", k_cache), ("v_cache", v_cache), ("block_tables", block_tables),
+                    ("seq_lens", seq_lens), ("out", out), ("workspace", workspace)):
+        if not t.is_cuda or not t.is_contiguous():
+            raise ValueError(f"{name} must be a contiguous GPU tensor")
+    if block_tables.dtype != torch.int32 or seq_lens.dtype != torch.int32:
+        raise ValueError("block_tables and seq_lens must be int32")
+    st = stream if stream is not None else torch.cuda.current_stream()
+    _check(load_library().fea_decode_attention(
+        C.byref(params), _dev_ptr(q), _dev_ptr(k_cache), _dev_ptr(v_cache), _dev_ptr(block_tables),
+        block_tables.shape[1], _dev_ptr(seq_lens), q.shape[0], _dev_ptr(out), _dev_ptr(workspace),
+        workspace.numel() * workspace.element_size(), C.c_void_p(st.cuda_stream)))
+
+
+def fea_decode_plan_info(workspace, stream=None) -> dict:
+    import torch
+    st = stream if stream is not None else torch.cuda.current_stream()
+    info = np.zeros(8, dtype=np.int32)
+    _check(load_library().fea_decode_plan_info(_dev_ptr(workspace), C.c_void_p(st.cuda_stream), _np_ptr(info)))
+    keys = ("items", "groups", "grouped_requests", "split_blocks", "partial_rows", "shared_blocks",
+            "variant", "overflow")
+    return dict(zip(keys, (int(x) for x in info)))

@@ -1,0 +1,73 @@
+"""Helpers for the GPU tests: push a drawn workload through libfea and fetch the result."""
+import numpy as np
+
+import workloads as W
+from oracle.attention import decode_attention
+from paper_2605_06046_amd import (AttnParams, FEA_DTYPE_BF16, FEA_DTYPE_F32, fea_build_block_tables,
+                                  fea_decode_attention, fea_decode_plan_info, fea_decode_workspace_bytes,
+                                  fea_kv_alloc)
+
+
+def to_device(x: np.ndarray):
+    import torch
+    if x.dtype == np.uint16:
+        return torch.from_numpy(x.view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(x).cuda()
+
+
+def values(x: np.ndarray) -> np.ndarray:
+    """Exact float32 values of a drawn array (bf16 bits or float32)."""
+    return W.bf16_bits_to_f32(x) if x.dtype == np.uint16 else x
+
+
+def run_hip(q, k_cache, v_cache, bt, lens, num_q_heads, num_kv_heads, head_dim, dtype, **pkw):
+    """q/k/v: numpy (float32 or bf16 bits); bt/lens: numpy int32.  Returns (out float64, plan info)."""
+    import torch
+    params = AttnParams(num_q_heads, num_kv_heads, head_dim,
+                        FEA_DTYPE_BF16 if dtype == "bf16" else FEA_DTYPE_F32, **pkw)
+    B, stride = bt.shape
+    dq, dk, dv = to_device(q), to_device(k_cache), to_device(v_cache)
+    dbt = torch.from_numpy(np.ascontiguousarray(bt, dtype=np.int32)).cuda()
+    dl = torch.from_numpy(np.ascontiguousarray(lens, dtype=np.int32)).cuda()
+    out = torch.full_like(dq, float("nan"))
+    ws = torch.empty(max(256, fea_decode_workspace_bytes(params, B, stride)), dtype=torch.uint8, device="cuda")
+    fea_decode_attention(params, dq, dk, dv, dbt, dl, out, ws)
+    info = fea_decode_plan_info(ws) if B > 0 else {}
+    torch.cuda.synchronize()
+    return out.float().cpu().numpy().astype(np.float64), info
+
+
+def library_tables(wl):
+    pool = fea_kv_alloc(wl.num_blocks, 16, wl.perm_seed)
+    bt, lens, _, _ = fea_build_block_tables(pool, wl.tokens, wl.tok_offsets, wl.max_blocks_per_seq)
+    return bt, lens
+
+
+def run_workload(wl, poison=True, **pkw):
+    """Library tables -> poison dead slots -> HIP attention.  Returns (out, bt, lens, info)."""
+    bt, lens = library_tables(wl)
+    if poison:
+        W.poison_dead_slots(wl, bt, lens)
+    s = wl.spec
+    out, info = run_hip(wl.q, wl.k_cache, wl.v_cache, bt, lens, s.num_q_heads, s.num_kv_heads, s.head_dim,
+                        s.dtype, **pkw)
+    return out, bt, lens, info
+
+
+def oracle_for(wl, bt, lens, requests=None):
+    return decode_attention(values(wl.q), values(wl.k_cache), values(wl.v_cache), bt, lens, requests=requests)
+
+
+TOL = {"f32": (1e-5, 1e-5), "bf16": (2e-2, 3e-3)}     # (max-abs, relative L2)
+
+
+def assert_close(got, want, dtype, rows=None, what=""):
+    if rows is not None:
+        got, want = got[rows], want[rows]
+    assert np.isfinite(got).all(), f"{what}: non-finite output"
+    max_abs, rel = TOL[dtype]
+    err = np.abs(got - want).max()
+    rl2 = np.linalg.norm(got - want) / max(np.linalg.norm(want), 1e-30)
+    assert err <= max_abs, f"{what}: max-abs {err:.3e} > {max_abs}"
+    assert rl2 <= rel, f"{what}: rel-L2 {rl2:.3e} > {rel}"
+    return err, rl2

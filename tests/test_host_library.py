@@ -1,0 +1,174 @@
+"""Host side of libfea.so against the oracle, bit for bit (no GPU needed)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import workloads as W
+from oracle.block_tables import build_block_tables, free_list
+from oracle.hashing import chunk_hashes
+from paper_2605_06046_amd import (AttnParams, FEA_DTYPE_BF16, FEA_DTYPE_F32, FeaError, fea_build_block_tables,
+                                  fea_chunk_hashes, fea_decode_workspace_bytes, fea_kv_alloc, fea_kv_stats,
+                                  fea_release, fea_validate_block_tables, library_path, load_library)
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "fea.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = set(re.findall(r"\b(fea_[a-z_]+)\s*\(", header))
+    assert {"fea_kv_alloc", "fea_build_block_tables", "fea_decode_attention"} <= names
+    lib = ctypes.CDLL(library_path())
+    for n in sorted(names):
+        assert hasattr(lib, n), n
+
+
+@pytest.mark.parametrize("T", [0, 1, 15, 16, 17, 63, 64, 65, 80, 1000, 4673])
+def test_chunk_hashes_match_oracle(T):
+    rng = np.random.default_rng(T)
+    toks = rng.integers(-3, 32000, size=T, dtype=np.int32)
+    got = fea_chunk_hashes(toks)
+    assert got.tolist() == chunk_hashes(toks)
+
+
+def _seqs(wl):
+    return [wl.request_tokens(i) for i in range(wl.spec.batch)]
+
+
+@pytest.mark.parametrize("name", ["c1", "c2", "c3", "c4", "c5"])
+def test_block_tables_and_hashes_match_oracle_on_the_configs(name):
+    wl = W.generate(W.CONFIGS[name], with_kv=False)
+    pool = fea_kv_alloc(wl.num_blocks, 16, wl.perm_seed)
+    bt, lens, hs, hoff = fea_build_block_tables(pool, wl.tokens, wl.tok_offsets, wl.max_blocks_per_seq, True)
+    obt, olens, orc = build_block_tables(_seqs(wl), wl.num_blocks, wl.perm_seed, wl.max_blocks_per_seq)
+    assert np.array_equal(bt, obt) and np.array_equal(lens, olens)
+    nb, free, collisions, rc = fea_kv_stats(pool)
+    assert np.array_equal(rc, orc) and collisions == 0 and free == nb - (orc > 0).sum()
+    fea_validate_block_tables(bt, lens, wl.num_blocks)
+    # hashes of a few requests, oracle-recomputed from scratch
+    for i in sorted({0, 1, wl.spec.batch // 2, wl.spec.batch - 1}):
+        assert hs[hoff[i]:hoff[i + 1]].tolist() == chunk_hashes(wl.request_tokens(i))
+
+
+def _adversarial_batch(seed):
+    rng = np.random.default_rng(seed)
+    stems = [rng.integers(0, 4, size=int(rng.integers(0, 90)), dtype=np.int32) for _ in range(3)]
+    seqs = []
+    for _ in range(12):
+        stem = stems[int(rng.integers(0, 3))]
+        cut = int(rng.integers(0, len(stem) + 1))
+        tail = rng.integers(0, 4, size=int(rng.integers(0, 40)), dtype=np.int32)
+        s = np.concatenate([stem[:cut], tail])
+        seqs.append(s if len(s) else np.array([1], dtype=np.int32))
+    seqs.append(seqs[3].copy())
+    seqs.append(np.zeros(0, dtype=np.int32))       # an empty request
+    return seqs
+
+
+@pytest.mark.parametrize("seed", range(8))
+@pytest.mark.parametrize("perm", [0, 77])
+def test_block_tables_match_oracle_on_adversarial_batches(seed, perm):
+    seqs = _adversarial_batch(seed)
+    offs = np.zeros(len(seqs) + 1, dtype=np.int64)
+    offs[1:] = np.cumsum([len(s) for s in seqs])
+    toks = np.concatenate(seqs).astype(np.int32)
+    pool = fea_kv_alloc(200, 16, perm)
+    bt, lens, hs, hoff = fea_build_block_tables(pool, toks, offs, 9, True)
+    obt, olens, orc = build_block_tables(seqs, 200, perm, 9)
+    assert np.array_equal(bt, obt) and np.array_equal(lens, olens)
+    assert np.array_equal(fea_kv_stats(pool)[3], orc)
+    for i, s in enumerate(seqs):
+        assert hs[hoff[i]:hoff[i + 1]].tolist() == chunk_hashes(s)
+
+
+def test_second_batch_on_same_pool_aliases_the_first():
+    rng = np.random.default_rng(0)
+    pre = rng.integers(0, 32000, size=64, dtype=np.int32)
+    a = np.concatenate([pre, rng.integers(0, 32000, size=10, dtype=np.int32)])
+    b = np.concatenate([pre, rng.integers(0, 32000, size=20, dtype=np.int32)])
+    pool = fea_kv_alloc(32)
+    bt1, _, _, _ = fea_build_block_tables(pool, a, np.array([0, len(a)]), 8)
+    bt2, _, _, _ = fea_build_block_tables(pool, b, np.array([0, len(b)]), 8)
+    assert bt1[0, :4].tolist() == bt2[0, :4].tolist() == [0, 1, 2, 3]
+    assert bt1[0, 4] == 4 and bt2[0, 4:6].tolist() == [5, 6]
+    # both at once on a fresh pool gives the same tables as the oracle
+    obt, _, _ = build_block_tables([a, b], 32)
+    assert np.array_equal(np.vstack([bt1[0], bt2[0]])[:, :6], obt[:, :6])
+
+
+def test_release_returns_blocks_and_forgets_prefixes():
+    rng = np.random.default_rng(1)
+    a = rng.integers(0, 32000, size=40, dtype=np.int32)
+    pool = fea_kv_alloc(8)
+    offs = np.array([0, 40, 80])
+    bt, _, _, _ = fea_build_block_tables(pool, np.concatenate([a, a]), offs, 3)
+    assert bt.tolist() == [[0, 1, 2], [0, 1, 3]]
+    _, free, _, rc = fea_kv_stats(pool)
+    assert rc.tolist() == [2, 2, 1, 1, 0, 0, 0, 0] and free == 4
+    fea_release(pool, bt[0])
+    assert fea_kv_stats(pool)[3].tolist() == [1, 1, 0, 1, 0, 0, 0, 0] and fea_kv_stats(pool)[1] == 5
+    fea_release(pool, bt[1])
+    assert fea_kv_stats(pool)[1] == 8
+    with pytest.raises(FeaError):
+        fea_release(pool, bt[1])                      # nothing left to release
+    with pytest.raises(FeaError):
+        fea_release(pool, np.array([99], dtype=np.int32))
+    # freed blocks rejoin at the tail; the old prefix is forgotten
+    bt3, _, _, _ = fea_build_block_tables(pool, a, np.array([0, 40]), 3)
+    assert bt3[0].tolist() == [4, 5, 6]
+
+
+def test_pool_exhaustion_rolls_back_everything():
+    rng = np.random.default_rng(2)
+    a = rng.integers(0, 32000, size=48, dtype=np.int32)
+    b = rng.integers(0, 32000, size=100, dtype=np.int32)
+    pool = fea_kv_alloc(6, 16, 5)
+    bt0, _, _, _ = fea_build_block_tables(pool, a, np.array([0, 48]), 7)
+    before = fea_kv_stats(pool)
+    toks = np.concatenate([a, b])
+    with pytest.raises(FeaError) as ei:
+        fea_build_block_tables(pool, toks, np.array([0, 48, 148]), 7)
+    assert ei.value.code == -2
+    after = fea_kv_stats(pool)
+    assert before[:3] == after[:3] and np.array_equal(before[3], after[3])
+    # the pool still works and hands out the same next blocks as if nothing happened
+    c = rng.integers(0, 32000, size=20, dtype=np.int32)
+    bt1, _, _, _ = fea_build_block_tables(pool, c, np.array([0, 20]), 7)
+    assert bt1[0, :2].tolist() == free_list(6, 5)[3:5]
+    # the aliased prefix survived the rollback
+    bt2, _, _, _ = fea_build_block_tables(pool, a[:32], np.array([0, 32]), 7)
+    assert bt2[0, :2].tolist() == bt0[0, :2].tolist()
+
+
+def test_argument_errors():
+    pool = fea_kv_alloc(4)
+    toks = np.arange(40, dtype=np.int32)
+    with pytest.raises(FeaError) as ei:
+        fea_build_block_tables(pool, toks, np.array([0, 40]), 2)      # needs 3 columns
+    assert ei.value.code == -3
+    with pytest.raises(FeaError):
+        fea_build_block_tables(pool, toks, np.array([0, 40, 30]), 4)  # offsets go backwards
+    with pytest.raises(FeaError):
+        fea_kv_alloc(0)
+    with pytest.raises(FeaError):
+        fea_kv_alloc(8, 32)
+    bad = np.array([[0, 7]], dtype=np.int32)
+    with pytest.raises(FeaError):
+        fea_validate_block_tables(bad, np.array([20], dtype=np.int32), 4)
+    fea_validate_block_tables(bad, np.array([16], dtype=np.int32), 4)   # column 1 is not read
+
+
+def test_workspace_size_and_param_checks():
+    p = AttnParams(32, 8, 128, FEA_DTYPE_BF16)
+    n = fea_decode_workspace_bytes(p, 64, 320)
+    assert n % 256 == 0 and 0 < n < 1 << 30
+    assert fea_decode_workspace_bytes(p, 128, 320) > n
+    assert fea_decode_workspace_bytes(AttnParams(8, 2, 64, FEA_DTYPE_F32), 4, 20) > 0
+    for bad in (AttnParams(32, 5, 128, FEA_DTYPE_BF16), AttnParams(32, 8, 100, FEA_DTYPE_BF16),
+                AttnParams(32, 8, 128, 7), AttnParams(32, 8, 128, FEA_DTYPE_BF16, block_size=32),
+                AttnParams(32, 8, 128, FEA_DTYPE_BF16, scale=-1.0), AttnParams(32, 8, 32, FEA_DTYPE_BF16)):
+        with pytest.raises(FeaError):
+            fea_decode_workspace_bytes(bad, 4, 20)

@@ -99,6 +99,8 @@ def scaled(spec: Spec, batch_div: int = 1, len_div: int = 1, name: Optional[str]
     lo2, hi2 = max(1, lo // len_div), max(1, hi // len_div)
     if lo2 == hi2 and lo != hi:
         hi2 = lo2 + BLOCK + 3
+    elif lo2 == hi2 and lo2 % BLOCK == 0:
+        lo2 = hi2 = lo2 + 5
     return replace(spec, name=name or f"{spec.name}_small", groups=groups, suffix=(lo2, hi2))
 
 
