@@ -1,0 +1,331 @@
+#!/usr/bin/env python3
+"""Benchmark of paged decode attention over prefix-aliased KV on one MI355X.
+
+One step = one fea_decode_attention call (alias detection + KV sweep + merge)
+for a whole batch: every request produces one token's attention output.  Tables,
+q and the KV pool are resident in HBM before the timed region.  The KV pool is
+replicated so that consecutive steps touch different memory and the 256 MB
+memory-side cache cannot serve them ("cold", the headline); a warm figure on a
+single replica is reported next to it.
+
+Prints ONE JSON line on stdout.  --suite additionally measures all five batch
+shapes and the homogeneous-vs-heterogeneous comparisons and writes them to
+gpurun_out/suite.jsonl.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes as C
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import workloads as W  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+class Case:
+    """One batch on the device: tables from the library, q and a replicated KV pool."""
+
+    def __init__(self, spec, replicas_bytes=1 << 30, seed_shift=0, tokens=None, max_group=0, label=None):
+        import torch
+        import paper_2605_06046_amd as fea
+        self.fea, self.torch, self.spec = fea, torch, spec
+        self.label = label or spec.name
+        wl = W.generate(spec, with_kv=False) if tokens is None else tokens
+        self.wl = wl
+        t0 = time.perf_counter()
+        pool = fea.fea_kv_alloc(wl.num_blocks, 16, wl.perm_seed)
+        bt, lens, _, _ = fea.fea_build_block_tables(pool, wl.tokens, wl.tok_offsets, wl.max_blocks_per_seq)
+        self.table_build_s = time.perf_counter() - t0
+        self.bt, self.lens = bt, lens
+        self.B = bt.shape[0]
+        live = np.unique(bt[bt >= 0])
+        self.unique_blocks = int(len(live))
+        self.logical_blocks = int((bt >= 0).sum())
+        es = 2 if spec.dtype == "bf16" else 4
+        self.block_bytes = 16 * 2 * spec.num_kv_heads * spec.head_dim * es      # K and V of one block
+        self.unique_bytes = self.unique_blocks * self.block_bytes
+        self.logical_bytes = self.logical_blocks * self.block_bytes
+        pool_bytes = wl.num_blocks * self.block_bytes
+        self.R = max(1, min(8, -(-replicas_bytes // max(self.unique_bytes, 1)))) if pool_bytes < (2 << 30) else 1
+        dt = torch.bfloat16 if spec.dtype == "bf16" else torch.float32
+        g = torch.Generator(device="cuda")
+        g.manual_seed(spec.seed + seed_shift)
+        shape = (self.R, wl.num_blocks, spec.num_kv_heads, 16, spec.head_dim)
+        self.k = torch.empty(shape, dtype=dt, device="cuda")
+        self.v = torch.empty(shape, dtype=dt, device="cuda")
+        for r in range(self.R):                      # chunked: randn makes float32 first
+            for cache in (self.k, self.v):
+                for b0 in range(0, wl.num_blocks, 8192):
+                    b1 = min(wl.num_blocks, b0 + 8192)
+                    cache[r, b0:b1] = torch.randn((b1 - b0,) + shape[2:], generator=g, device="cuda",
+                                                  dtype=torch.float32).to(dt)
+        q = wl.q
+        self.q = (torch.from_numpy(q.view(np.int16)).cuda().view(torch.bfloat16) if q.dtype == np.uint16
+                  else torch.from_numpy(q).cuda())
+        self.dbt = torch.from_numpy(bt).cuda()
+        self.dl = torch.from_numpy(lens).cuda()
+        self.out = torch.empty_like(self.q)
+        self.params = fea.AttnParams(spec.num_q_heads, spec.num_kv_heads, spec.head_dim,
+                                     fea.FEA_DTYPE_BF16 if spec.dtype == "bf16" else fea.FEA_DTYPE_F32,
+                                     max_group=max_group)
+        nbytes = fea.fea_decode_workspace_bytes(self.params, self.B, bt.shape[1])
+        self.ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        # argument lists prepared once: the timed loop only makes the foreign call
+        lib = fea.load_library()
+        self._fn = lib.fea_decode_attention
+        vp = C.c_void_p
+        self._args = [
+            (C.byref(self.params), vp(self.q.data_ptr()), vp(self.k[r].data_ptr()), vp(self.v[r].data_ptr()),
+             vp(self.dbt.data_ptr()), bt.shape[1], vp(self.dl.data_ptr()), self.B, vp(self.out.data_ptr()),
+             vp(self.ws.data_ptr()), nbytes)
+            for r in range(self.R)]
+
+    def step(self, r, stream_ptr):
+        rc = self._fn(*self._args[r], stream_ptr)
+        if rc != 0:
+            raise RuntimeError(self.fea.load_library().fea_last_error().decode())
+
+    def time_steps(self, steps, warmup, cold=True, graph=False):
+        """Mean milliseconds per step over `steps` back-to-back calls."""
+        torch = self.torch
+        R = self.R if cold else 1
+        stream = torch.cuda.current_stream()
+        sp = C.c_void_p(stream.cuda_stream)
+        for s in range(warmup):
+            self.step(s % R, sp)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        if graph:
+            side = torch.cuda.Stream()
+            gr = torch.cuda.CUDAGraph()
+            with torch.cuda.stream(side):
+                spg = C.c_void_p(side.cuda_stream)
+                for s in range(R):
+                    self.step(s, spg)
+                side.synchronize()
+                with torch.cuda.graph(gr, stream=side):
+                    for s in range(R):
+                        self.step(s, spg)
+            reps = max(1, steps // R)
+            gr.replay()
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(reps):
+                gr.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / (reps * R)
+        e0.record()
+        for s in range(steps):
+            self.step(s % R, sp)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / steps
+
+    def kernel_times(self, steps, cold=True):
+        """Average (plan, sweep, merge) durations in ms from HIP events around each launch."""
+        torch, fea = self.torch, self.fea
+        R = self.R if cold else 1
+        sp = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+        fea.fea_profile_enable(True)
+        acc = np.zeros(3)
+        try:
+            for s in range(steps):
+                self.step(s % R, sp)
+                acc += np.array(fea.fea_profile_last())
+        finally:
+            fea.fea_profile_enable(False)
+        return acc / steps
+
+    def measure(self, steps, warmup, graph=False):
+        ms_cold = self.time_steps(steps, warmup, cold=True, graph=graph)
+        ms_warm = self.time_steps(steps, warmup, cold=False, graph=graph)
+        kt = self.kernel_times(min(steps, 50))
+        info = self.fea.fea_decode_plan_info(self.ws)
+        return {
+            "workload": self.label, "B": self.B, "ms_per_step": ms_cold, "ms_per_step_warm": ms_warm,
+            "tokens_per_s": self.B / (ms_cold * 1e-3), "tokens_per_s_warm": self.B / (ms_warm * 1e-3),
+            "unique_kv_bytes": self.unique_bytes, "logical_kv_bytes": self.logical_bytes,
+            "unique_kv_gbs": self.unique_bytes / (ms_cold * 1e-3) / 1e9,
+            "unique_kv_gbs_warm": self.unique_bytes / (ms_warm * 1e-3) / 1e9,
+            "logical_kv_gbs": self.logical_bytes / (ms_cold * 1e-3) / 1e9,
+            "frac_hbm_peak_step": self.unique_bytes / (ms_cold * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "kernel_us": {"plan": kt[0] * 1e3, "sweep": kt[1] * 1e3, "merge": kt[2] * 1e3},
+            "sweep_gbs": self.unique_bytes / (kt[1] * 1e-3) / 1e9,
+            "replicas": self.R, "plan": info, "table_build_ms": self.table_build_s * 1e3,
+            "table_build_tokens_per_s": len(self.wl.tokens) / self.table_build_s,
+        }
+
+
+def cpu_baseline(case, budget_s=20.0):
+    """The float64 oracle, as it stands, on the host cores: whole requests of the
+    same batch until about `budget_s` seconds of work are done."""
+    from oracle.attention import decode_attention
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    torch = case.torch
+    q = case.q.float().cpu().numpy()
+    k = case.k[0].float().cpu().numpy()
+    v = case.v[0].float().cpu().numpy()
+    decode_attention(q, k, v, case.bt, case.lens, requests=[0])          # warm
+    done, t0 = 0, time.perf_counter()
+    while done < case.B and time.perf_counter() - t0 < budget_s:
+        decode_attention(q, k, v, case.bt, case.lens, requests=[done])
+        done += 1
+    dt = time.perf_counter() - t0
+    return {"value": done / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"first {done} of {case.B} requests of {case.label} (all heads, full history), {dt:.1f} s wall"}
+
+
+def traffic_from_profile(workload):
+    """HBM bytes per sweep launch from the committed counter summary, if it is current."""
+    path = os.path.join(ROOT, "profiles", f"sweep_mfma_{workload}_pmc.json")
+    try:
+        d = json.load(open(path))
+        return d.get("traffic_bytes_per_launch") if d.get("kernel_rev") == kernel_rev() else None
+    except Exception:
+        return None
+
+
+def kernel_rev():
+    import hashlib
+    h = hashlib.sha256()
+    for f in ("fea_sweep_mfma.hip", "fea_planner.hip", "fea_plan.h"):
+        h.update(open(os.path.join(ROOT, "paper_2605_06046_amd", "csrc", f), "rb").read())
+    return h.hexdigest()[:12]
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--workload", default="c2", choices=sorted(W.CONFIGS))
+    ap.add_argument("--graph", action="store_true", help="replay the steps from a captured HIP graph")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--suite", action="store_true", help="also run all shapes and the homogeneity comparisons")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible")
+        sys.exit(2)
+    import paper_2605_06046_amd as fea
+    fea.load_library()
+
+    spec = W.CONFIGS[args.workload]
+    case = Case(spec)
+    m = case.measure(args.steps, args.warmup, graph=args.graph)
+    log(json.dumps(m))
+    sweep_s = m["kernel_us"]["sweep"] * 1e-6
+    achieved = case.unique_bytes / sweep_s / 1e9
+    line = {
+        "metric": "decode-attn tokens/s (unique-KV HBM GB/s vs peak in roofline)",
+        "value": m["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": m["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if spec.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: B={case.B}, Hq={spec.num_q_heads}, Hkv={spec.num_kv_heads}, "
+                               f"d={spec.head_dim}, block 16, groups={[list(g) for g in spec.groups[:2]]}"
+                               f"{'...' if len(spec.groups) > 2 else ''}, suffix U{list(spec.suffix)}",
+                   "mode": "graph" if args.graph else "eager", "kv_replicas_rotated": case.R,
+                   "unique_kv_MB": case.unique_bytes / 1e6, "logical_kv_MB": case.logical_bytes / 1e6},
+        "unique_kv_gbs": m["unique_kv_gbs"], "frac_hbm_peak_whole_step": m["frac_hbm_peak_step"],
+        "warm": {"tokens_per_s": m["tokens_per_s_warm"], "unique_kv_gbs": m["unique_kv_gbs_warm"]},
+        "kernel_us": m["kernel_us"], "plan": m["plan"],
+        "host_table_build": {"ms": m["table_build_ms"], "tokens_per_s": m["table_build_tokens_per_s"]},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic_from_profile(args.workload),
+                     "kernel": "sweep_mfma_kernel" if m["plan"]["variant"] == 1 else "sweep_generic_kernel",
+                     "bytes_per_launch": case.unique_bytes},
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(case)
+    else:
+        line["cpu_baseline"] = None
+
+    if args.suite:
+        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+        with open(os.path.join(ROOT, "gpurun_out", "suite.jsonl"), "w") as f:
+            f.write(json.dumps(m) + "\n")
+            del case
+            torch.cuda.empty_cache()
+            for res in run_suite(args):
+                f.write(json.dumps(res) + "\n")
+                f.flush()
+                log(json.dumps(res))
+    print(json.dumps(line), flush=True)
+
+
+def run_suite(args):
+    """All shapes, plus: H2 homogeneous vs mixed batch of equal size and logical KV,
+    H3 shared vs unshared batch of equal lengths, H1 one mixed launch vs eight
+    homogeneous launches over the same KV."""
+    import dataclasses
+    import torch
+    steps, warm = max(50, args.steps // 4), max(10, args.warmup // 2)
+    for name in ("c1", "c3", "c4", "c5"):
+        c = Case(W.CONFIGS[name])
+        yield c.measure(steps if name != "c5" else 40, warm if name != "c5" else 5, graph=args.graph)
+        del c
+        torch.cuda.empty_cache()
+    base = W.CONFIGS["c3"]
+    # H2: 32 requests of one group vs 32 requests drawn 4 from each of the 8 groups
+    homo = dataclasses.replace(base, name="H2_homogeneous", groups=((32, 4096),), interleave=False)
+    mixed = dataclasses.replace(base, name="H2_mixed", groups=tuple((4, 4096) for _ in range(8)))
+    for sp in (homo, mixed):
+        c = Case(sp, label=sp.name)
+        yield c.measure(steps, warm, graph=args.graph)
+        del c
+        torch.cuda.empty_cache()
+    # H3: c2 against the same lengths with nothing shared
+    c2 = W.CONFIGS["c2"]
+    wl = W.generate(c2, with_kv=False)
+    rng = np.random.default_rng(7)
+    toks = wl.tokens.copy()
+    for i in range(c2.batch):                     # re-draw every prefix: same lengths, no common tokens
+        toks[wl.tok_offsets[i]:wl.tok_offsets[i] + 4096] = rng.integers(0, W.VOCAB, size=4096, dtype=np.int32)
+    wl_unshared = dataclasses.replace(wl, tokens=toks, num_blocks=int(sum(-(-int(L) // 16) for L in wl.seq_lens)))
+    c = Case(dataclasses.replace(c2, name="H3_unshared"), tokens=wl_unshared, label="H3_unshared")
+    yield c.measure(steps, warm, graph=args.graph)
+    del c
+    torch.cuda.empty_cache()
+    # grouping switched off on the shared batch: the paper's own mechanism (cache locality only)
+    c = Case(c2, max_group=1, label="c2_grouping_off")
+    yield c.measure(steps, warm, graph=args.graph)
+    del c
+    torch.cuda.empty_cache()
+    # H1: the 8 groups of c3 as 8 homogeneous launches of 32 (time summed) vs the one mixed launch above
+    total_ms, total_ms_warm, B = 0.0, 0.0, 0
+    for gi in range(8):
+        sp = dataclasses.replace(base, name=f"H1_group{gi}", index=30 + gi, groups=((32, 4096),), interleave=False)
+        c = Case(sp, replicas_bytes=1 << 30, label=sp.name)
+        m = c.measure(steps, warm, graph=args.graph)
+        total_ms += m["ms_per_step"]
+        total_ms_warm += m["ms_per_step_warm"]
+        B += c.B
+        del c
+        torch.cuda.empty_cache()
+    yield {"workload": "H1_eight_homogeneous_launches_of_32", "B": B, "ms_per_step": total_ms,
+           "ms_per_step_warm": total_ms_warm, "tokens_per_s": B / (total_ms * 1e-3)}
+
+
+if __name__ == "__main__":
+    main()

@@ -204,6 +204,17 @@ int32_t fea_decode_attention(const fea_attn_params* p,
 int32_t fea_decode_plan_info(const void* workspace /* DEVICE */, void* hip_stream,
                              int32_t* info /* HOST [8] */);
 
+/* Per-kernel timing for measurement runs.  While enabled, fea_decode_attention
+ * records library-owned HIP events on the caller's stream before and after each
+ * of its three launches (alias detection, KV sweep, merge).  fea_profile_last
+ * waits for the most recent call to finish and returns the three durations in
+ * milliseconds (HOST float[3]); with FEA_FLAG_REUSE_PLAN the first is ~0.
+ * Process-wide, not thread-safe; leave it off in production.
+ * Errors: FEA_EHIP if events cannot be created or read; FEA_EINVAL for NULL or
+ * when profiling was never enabled. */
+int32_t fea_profile_enable(int32_t on);
+int32_t fea_profile_last(float* ms);
+
 #ifdef __cplusplus
 }
 #endif

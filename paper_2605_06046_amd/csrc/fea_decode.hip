@@ -77,7 +77,7 @@ static int32_t resolve(const fea_attn_params* p, int32_t B, int32_t stride, Reso
     size_t off = up256(H_WORDS * sizeof(int32_t));
     l.req = off;      off += up256((size_t)B * sizeof(ReqDesc));
     l.grp = off;      off += up256((size_t)B * sizeof(GroupDesc));
-    l.members = off;  off += up256((size_t)B * sizeof(int32_t));
+    l.members = off;  off += up256((size_t)2 * B * sizeof(int32_t));   // group lists, then the identity list
     l.items = off;    off += up256((size_t)max_items * sizeof(Item));
     l.ml = off;       off += up256((size_t)max_rows * 2 * sizeof(float));
     l.acc = off;      off += up256((size_t)max_rows * p->head_dim * sizeof(float));
@@ -86,6 +86,10 @@ static int32_t resolve(const fea_attn_params* p, int32_t B, int32_t stride, Reso
     l.max_rows = (int32_t)max_rows;
     return FEA_OK;
 }
+
+// Optional per-kernel timing: four library-owned events around the three launches.
+static bool g_prof_on = false;
+static hipEvent_t g_ev[4] = {nullptr, nullptr, nullptr, nullptr};
 
 static int cu_count() {
     static int n = 0;
@@ -150,8 +154,12 @@ int32_t fea_decode_attention(const fea_attn_params* p, const void* q, const void
         pa.grouping = r.grouping;
         pa.split_user = r.split_user;
         pa.variant = r.variant;
+        if (g_prof_on) hipEventRecord(g_ev[0], static_cast<hipStream_t>(hip_stream));
         launch_plan(pa, hip_stream);
+    } else if (g_prof_on) {
+        hipEventRecord(g_ev[0], static_cast<hipStream_t>(hip_stream));
     }
+    if (g_prof_on) hipEventRecord(g_ev[1], static_cast<hipStream_t>(hip_stream));
     SweepArgs sa;
     std::memset(&sa, 0, sizeof sa);
     sa.q = q;
@@ -169,14 +177,36 @@ int32_t fea_decode_attention(const fea_attn_params* p, const void* q, const void
     sa.G = r.G;
     sa.mpt = r.mpt;
     if (r.variant == 1) {
-        launch_sweep_mfma(sa, std::max(1, env_int("FEA_SWEEP_GRID", cu_count())), hip_stream);
+        launch_sweep_mfma(sa, std::max(1, env_int("FEA_SWEEP_GRID", 4 * cu_count())), hip_stream);   // one wave per SIMD
     } else {
         const int grid = std::min(r.lay.max_items, std::max(1, env_int("FEA_SWEEP_GRID", 8 * cu_count())));
         launch_sweep_generic(sa, p->dtype, p->head_dim, grid, hip_stream);
     }
+    if (g_prof_on) hipEventRecord(g_ev[2], static_cast<hipStream_t>(hip_stream));
     launch_merge(sa, p->dtype, p->head_dim, hip_stream);
+    if (g_prof_on) hipEventRecord(g_ev[3], static_cast<hipStream_t>(hip_stream));
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(FEA_EHIP, "fea_decode_attention: launch failed: %s", hipGetErrorString(e));
+    return FEA_OK;
+}
+
+int32_t fea_profile_enable(int32_t on) {
+    if (on && !g_ev[0]) {
+        for (auto& ev : g_ev) {
+            const hipError_t e = hipEventCreate(&ev);
+            if (e != hipSuccess) return fail(FEA_EHIP, "fea_profile_enable: %s", hipGetErrorString(e));
+        }
+    }
+    g_prof_on = on != 0;
+    return FEA_OK;
+}
+
+int32_t fea_profile_last(float* ms) {
+    if (!ms) return fail(FEA_EINVAL, "fea_profile_last: ms is NULL");
+    if (!g_ev[0]) return fail(FEA_EINVAL, "fea_profile_last: profiling was never enabled");
+    hipError_t e = hipEventSynchronize(g_ev[3]);
+    for (int k = 0; k < 3 && e == hipSuccess; ++k) e = hipEventElapsedTime(&ms[k], g_ev[k], g_ev[k + 1]);
+    if (e != hipSuccess) return fail(FEA_EHIP, "fea_profile_last: %s", hipGetErrorString(e));
     return FEA_OK;
 }
 

@@ -12,7 +12,7 @@ constexpr int kBlock = 16;            // tokens per KV block
 constexpr int kPlanThreads = 1024;    // the planner is one workgroup
 constexpr int kGroupReqMax = 2048;    // requests with index >= this are never grouped
 constexpr int kHashSlots = 4096;      // LDS hash slots for leader finding (2x kGroupReqMax)
-constexpr int kTileRows = 64;         // query rows one MFMA work item carries at most
+constexpr int kTileRows = 32;         // query rows one MFMA work item carries at most
 
 // header words (int32) at the start of the workspace
 enum Hdr {
@@ -50,14 +50,16 @@ struct GroupDesc {     // indexed by leader request id; valid only where members
     int32_t item_base;
 };
 
-struct Item {          // one KV sweep: a row set x one KV head x a column range
-    int32_t kind;      // 0: one request's private columns, 1: a group's shared run
-    int32_t who;       // request id / leader id
+struct Item {          // one KV sweep: a row set x one KV head x a column range (48 bytes)
+    int32_t who;       // request whose table row is read (the group's leader for a shared run)
     int32_t g;         // KV head
-    int32_t tile;      // row tile inside the group
+    int32_t nrows;     // query rows: (requests in the row set) x (group heads)
+    int32_t mlist_off; // the row set's request ids start at members[mlist_off]
     int32_t c0, c1;    // table columns [c0, c1) of `who`'s row
     int32_t pbase;     // partial row of the item's first query row
     int32_t tok_end;   // tokens at positions >= tok_end are not attended to
+    int32_t kind;      // 0: one request's private columns, 1: a group's shared run
+    int32_t pad[3];
 };
 
 // Byte offsets of the workspace sections (all multiples of 256).

@@ -80,18 +80,12 @@ __global__ __launch_bounds__(kGenThreads) void sweep_generic_kernel(SweepArgs a)
         const int t_begin = item.c0 * kBlock, t_end = item.tok_end;
         // query rows of the item: one request, or the members of a group's row tile
         // (the vector path simply sweeps the shared run once per member)
-        int n_mem = 1;
-        const int* mlist = nullptr;
-        if (item.kind == 1) {
-            const GroupDesc gd = reinterpret_cast<const GroupDesc*>(a.ws + a.lay.grp)[item.who];
-            const int first = item.tile * a.mpt;
-            n_mem = min(a.mpt, gd.members - first);
-            mlist = reinterpret_cast<const int*>(a.ws + a.lay.members) + gd.member_off + first;
-        }
+        const int n_mem = item.nrows / a.G;
+        const int* mlist = reinterpret_cast<const int*>(a.ws + a.lay.members) + item.mlist_off;
         for (int mh = 0; mh < n_mem * ((a.G + kHB - 1) / kHB); ++mh) {
             const int mem = mh / ((a.G + kHB - 1) / kHB);
             const int hb = (mh % ((a.G + kHB - 1) / kHB)) * kHB;
-            const int qreq = mlist ? mlist[mem] : item.who;
+            const int qreq = mlist[mem];
             const int prow0 = item.pbase + mem * a.G + hb;
             const int nh = min(kHB, a.G - hb);
             float qf[kHB][EPL];

@@ -35,7 +35,8 @@ class AttnParams(C.Structure):
 
 
 def library_path() -> str:
-    return os.path.join(_HERE, "libfea.so")
+    """The in-tree build; FEA_LIBRARY names another build of the same library (development aid)."""
+    return os.environ.get("FEA_LIBRARY") or os.path.join(_HERE, "libfea.so")
 
 
 def load_library() -> C.CDLL:
@@ -61,6 +62,8 @@ def load_library() -> C.CDLL:
         "fea_decode_workspace_bytes": (i32, [C.POINTER(AttnParams), i32, i32, C.POINTER(C.c_size_t)]),
         "fea_decode_attention": (i32, [C.POINTER(AttnParams), vp, vp, vp, vp, i32, vp, i32, vp, vp, C.c_size_t, vp]),
         "fea_decode_plan_info": (i32, [vp, vp, vp]),
+        "fea_profile_enable": (i32, [i32]),
+        "fea_profile_last": (i32, [vp]),
     }
     for name, (res, args) in sigs.items():
         fn = getattr(lib, name)
@@ -188,3 +191,14 @@ def fea_decode_plan_info(workspace, stream=None) -> dict:
     keys = ("items", "groups", "grouped_requests", "split_blocks", "partial_rows", "shared_blocks",
             "variant", "overflow")
     return dict(zip(keys, (int(x) for x in info)))
+
+
+def fea_profile_enable(on: bool) -> None:
+    _check(load_library().fea_profile_enable(1 if on else 0))
+
+
+def fea_profile_last():
+    """(plan_ms, sweep_ms, merge_ms) of the most recent fea_decode_attention call."""
+    ms = np.zeros(3, dtype=np.float32)
+    _check(load_library().fea_profile_last(_np_ptr(ms)))
+    return float(ms[0]), float(ms[1]), float(ms[2])
