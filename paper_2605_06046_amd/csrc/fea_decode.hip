@@ -25,10 +25,25 @@ static bool is_pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
 
 struct Resolved {
     int variant;      // 0 generic, 1 MFMA
-    int G, mpt, grouping, split_user;
+    int G, mpt, grouping, split_user, grid;
     PlanTuning tune;
     WsLayout lay;
 };
+
+// Optional per-kernel timing: four library-owned events around the three launches.
+static bool g_prof_on = false;
+static hipEvent_t g_ev[4] = {nullptr, nullptr, nullptr, nullptr};
+
+static int cu_count() {
+    static int n = 0;
+    if (n == 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) n = prop.multiProcessorCount;
+        if (n <= 0) n = 256;
+    }
+    return n;
+}
 
 static int32_t check_params(const fea_attn_params* p, const char* who) {
     if (!p) return fail(FEA_EINVAL, "%s: params is NULL", who);
@@ -56,21 +71,24 @@ static int32_t resolve(const fea_attn_params* p, int32_t B, int32_t stride, Reso
     r.mpt = r.G >= kTileRows ? 1 : kTileRows / r.G;
     r.grouping = p->max_group == 1 ? 0 : 1;
     r.split_user = p->split_blocks > 0 ? ((p->split_blocks + 1) & ~1) : 0;
-    r.tune.target_items = std::max(64, env_int("FEA_TARGET_ITEMS", 1024));
-    r.tune.min_split = std::max(2, env_int("FEA_MIN_SPLIT", 8));
+    // the sweep grid the plan is cut for: one single-wave workgroup per SIMD on the
+    // matrix-core path, a few workgroups per CU on the generic path
+    r.grid = std::max(1, env_int("FEA_SWEEP_GRID", (r.variant == 1 ? 4 : 8) * cu_count()));
+    r.tune.n_waves = r.grid;
+    r.tune.min_piece = std::max(1, env_int("FEA_MIN_PIECE", 4));
     r.tune.min_run = std::max(1, env_int("FEA_MIN_RUN", 2));
+    r.tune.pad = 0;
     const int64_t rows = (int64_t)B * p->num_q_heads;
-    const int64_t budget = std::max<int64_t>(16384, (int64_t)env_int("FEA_ROW_BUDGET_MULT", 16) * rows);
-    r.tune.row_budget = (int32_t)std::min<int64_t>(budget, 0x3FFFFFFF);
-
+    const int64_t segs = 2ll * B * p->num_kv_heads;          // private segments + at most as many shared ones
+    const int64_t rows_per_item = std::max(kTileRows, r.mpt * r.G);
     int64_t max_items, max_rows;
     if (r.split_user > 0) {
-        const int64_t per = (stride + r.split_user - 1) / r.split_user;
-        max_items = 2ll * B * p->num_kv_heads * per + 64;
-        max_rows = 2ll * rows * per + 64;
+        const int64_t per = ((stride + 1) / 2 + r.split_user / 2 - 1) / (r.split_user / 2) + 1;   // pieces per segment
+        max_items = segs * per + 64;
+        max_rows = 2 * rows * per + 64;
     } else {
-        max_items = (int64_t)r.tune.target_items + 2ll * B * p->num_kv_heads + 64;
-        max_rows = (int64_t)r.tune.row_budget + 2 * rows + 64;
+        max_items = segs + 3ll * r.grid + 64;                // pieces of shared runs + cuts of the private stream
+        max_rows = 2 * rows + (int64_t)r.grid * (rows_per_item + 2 * r.G) + 64;
     }
     if (max_items > 0x3FFFFFFF || max_rows > 0x3FFFFFFF) return fail(FEA_EINVAL, "%s: split_blocks too small for this problem size", who);
     WsLayout& l = r.lay;
@@ -78,6 +96,8 @@ static int32_t resolve(const fea_attn_params* p, int32_t B, int32_t stride, Reso
     l.req = off;      off += up256((size_t)B * sizeof(ReqDesc));
     l.grp = off;      off += up256((size_t)B * sizeof(GroupDesc));
     l.members = off;  off += up256((size_t)2 * B * sizeof(int32_t));   // group lists, then the identity list
+    l.segs = off;     off += up256((size_t)segs * sizeof(SegDesc));
+    l.wave_first = off; off += up256((size_t)(max_items + 2) * sizeof(int32_t));
     l.items = off;    off += up256((size_t)max_items * sizeof(Item));
     l.ml = off;       off += up256((size_t)max_rows * 2 * sizeof(float));
     l.acc = off;      off += up256((size_t)max_rows * p->head_dim * sizeof(float));
@@ -85,21 +105,6 @@ static int32_t resolve(const fea_attn_params* p, int32_t B, int32_t stride, Reso
     l.max_items = (int32_t)max_items;
     l.max_rows = (int32_t)max_rows;
     return FEA_OK;
-}
-
-// Optional per-kernel timing: four library-owned events around the three launches.
-static bool g_prof_on = false;
-static hipEvent_t g_ev[4] = {nullptr, nullptr, nullptr, nullptr};
-
-static int cu_count() {
-    static int n = 0;
-    if (n == 0) {
-        int dev = 0;
-        hipDeviceProp_t prop;
-        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) n = prop.multiProcessorCount;
-        if (n <= 0) n = 256;
-    }
-    return n;
 }
 
 }  // namespace fea
@@ -176,12 +181,8 @@ int32_t fea_decode_attention(const fea_attn_params* p, const void* q, const void
     sa.Hkv = p->num_kv_heads;
     sa.G = r.G;
     sa.mpt = r.mpt;
-    if (r.variant == 1) {
-        launch_sweep_mfma(sa, std::max(1, env_int("FEA_SWEEP_GRID", 4 * cu_count())), hip_stream);   // one wave per SIMD
-    } else {
-        const int grid = std::min(r.lay.max_items, std::max(1, env_int("FEA_SWEEP_GRID", 8 * cu_count())));
-        launch_sweep_generic(sa, p->dtype, p->head_dim, grid, hip_stream);
-    }
+    if (r.variant == 1) launch_sweep_mfma(sa, r.grid, hip_stream);
+    else launch_sweep_generic(sa, p->dtype, p->head_dim, r.grid, hip_stream);
     if (g_prof_on) hipEventRecord(g_ev[2], static_cast<hipStream_t>(hip_stream));
     launch_merge(sa, p->dtype, p->head_dim, hip_stream);
     if (g_prof_on) hipEventRecord(g_ev[3], static_cast<hipStream_t>(hip_stream));

@@ -12,19 +12,20 @@ constexpr int kBlock = 16;            // tokens per KV block
 constexpr int kPlanThreads = 1024;    // the planner is one workgroup
 constexpr int kGroupReqMax = 2048;    // requests with index >= this are never grouped
 constexpr int kHashSlots = 4096;      // LDS hash slots for leader finding (2x kGroupReqMax)
-constexpr int kTileRows = 32;         // query rows one MFMA work item carries at most
+constexpr int kTileRows = 64;         // query rows one MFMA work item carries at most
 
 // header words (int32) at the start of the workspace
 enum Hdr {
     H_ITEMS = 0,       // number of work items
-    H_QUEUE = 1,       // next item to hand out (zero between calls)
+    H_QUEUE = 1,       // unused (kept zero)
     H_GROUPS = 2,      // prefix groups found
     H_GROUPED = 3,     // requests that belong to a group
-    H_SPLIT = 4,       // KV blocks per work item
+    H_SPLIT = 4,       // KV blocks per wave (balanced mode) or per item (fixed split)
     H_ROWS = 5,        // partial rows in use
     H_SHARED_BLOCKS = 6,
     H_VARIANT = 7,     // 0 generic, 1 MFMA
     H_OVERFLOW = 8,    // planner ran out of item/partial capacity (never by construction)
+    H_WAVES = 9,       // sweep waves that received work
     H_WORDS = 64
 };
 
@@ -32,25 +33,31 @@ struct ReqDesc {       // one per request
     int32_t group;     // leader request id of its group, or -1
     int32_t rank;      // position inside the group
     int32_t priv_c0;   // first private column (= shared run length, 0 if ungrouped)
-    int32_t priv_nsplits;
-    int32_t priv_pbase;   // first partial row of the private segment
     int32_t nb;        // ceil(L / 16)
     int32_t L;
-    int32_t priv_item_base;
+    int32_t pad[3];
 };
 
 struct GroupDesc {     // indexed by leader request id; valid only where members >= 2
     int32_t leader;
     int32_t members;
     int32_t run;       // aliased leading blocks (full blocks of every member)
-    int32_t nsplits;
-    int32_t pbase;     // first partial row of the shared segment
     int32_t member_off;   // into the member list
     int32_t tiles;     // row tiles (members are cut into tiles of members_per_tile)
-    int32_t item_base;
+    int32_t seg_base;  // its segments are segs[B*Hkv + seg_base + g*tiles + tile]
+    int32_t pad[2];
 };
 
-struct Item {          // one KV sweep: a row set x one KV head x a column range (48 bytes)
+// A segment is one row set x one KV head x a whole column range (a request's
+// private columns, or a group row tile's shared run).  It is swept in `npieces`
+// consecutive pieces; piece p's partial for the segment's row r is partial row
+// pbase + p * rows + r.
+struct SegDesc {
+    int32_t pbase;
+    int32_t npieces;
+};
+
+struct Item {          // one KV sweep: a row set x one KV head x a column range (64 bytes)
     int32_t who;       // request whose table row is read (the group's leader for a shared run)
     int32_t g;         // KV head
     int32_t nrows;     // query rows: (requests in the row set) x (group heads)
@@ -58,22 +65,25 @@ struct Item {          // one KV sweep: a row set x one KV head x a column range
     int32_t c0, c1;    // table columns [c0, c1) of `who`'s row
     int32_t pbase;     // partial row of the item's first query row
     int32_t tok_end;   // tokens at positions >= tok_end are not attended to
+    int32_t fb[4];     // block ids of columns c0 .. c0+3 (clamped to c1-1): lets a sweep start
+                       // fetching before it has read the table row itself
     int32_t kind;      // 0: one request's private columns, 1: a group's shared run
     int32_t pad[3];
 };
+static_assert(sizeof(Item) == 64, "Item is read as four 16-byte words");
 
 // Byte offsets of the workspace sections (all multiples of 256).
 struct WsLayout {
-    size_t req, grp, members, items, ml, acc, total;
+    size_t req, grp, members, segs, wave_first, items, ml, acc, total;
     int32_t max_items, max_rows;
 };
 
 // Planner tuning (host constants, overridable through the environment for sweeps).
 struct PlanTuning {
-    int32_t target_items;   // aim for about this many work items
-    int32_t min_split;      // never cut finer than this many blocks
-    int32_t row_budget;     // cap on partial rows beyond 2*B*Hq
+    int32_t n_waves;        // sweep waves the work is cut for (the sweep kernel's grid)
+    int32_t min_piece;      // a wave gets at least this many 32-token tiles (fewer waves get work instead)
     int32_t min_run;        // shortest aliased run worth sweeping jointly
+    int32_t pad;
 };
 
 struct PlanArgs {

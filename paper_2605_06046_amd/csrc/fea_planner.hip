@@ -7,6 +7,12 @@
 // on their own.  A group is only a way to save KV reads: membership requires
 // nothing but equal block ids over the run and full blocks for every member, so
 // the result is the same attention whatever the tables look like.
+//
+// The sweeps are then laid end to end as one stream of 32-token tiles (shared
+// runs first) and the stream is cut into equal shares, one per sweep wave, so
+// that every wave moves the same number of KV bytes; a cut inside a segment just
+// adds one partial result to it.  With an explicit split size the segments are
+// cut every `split` blocks instead and the pieces dealt out in equal numbers.
 #include <hip/hip_runtime.h>
 
 #include <climits>
@@ -18,7 +24,7 @@ namespace fea {
 __device__ __forceinline__ int cdiv(int a, int b) { return (a + b - 1) / b; }
 
 // Integer division by a run-time divisor without the ~40-instruction expansion:
-// exact for 0 <= x < 2^24 and 1 <= d (block and request counts are far below that).
+// exact for 0 <= x < 2^24 and 1 <= d (row and request counts are far below that).
 struct FastDiv {
     int d;
     float rcp;
@@ -31,6 +37,20 @@ struct FastDiv {
         return q;
     }
     __device__ __forceinline__ int cdiv(int x) const { return div(x + d - 1); }
+};
+
+// The same through double precision: exact for 0 <= x < 2^31 (tile positions).
+struct WideDiv {
+    int d;
+    double rcp;
+    __device__ explicit WideDiv(int dd) : d(dd), rcp(1.0 / (double)dd) {}
+    __device__ __forceinline__ int div(int x) const {
+        int q = (int)((double)x * rcp);
+        const long long r = (long long)x - (long long)q * d;
+        if (r >= d) ++q;
+        if (r < 0) --q;
+        return q;
+    }
 };
 
 // Exclusive prefix sum of one int per thread over the 1024-thread block.
@@ -62,42 +82,74 @@ __device__ int block_scan_excl(int v, int* s_tmp, int& total) {
     return base + x - v;
 }
 
-__device__ long long block_sum_ll(long long v, long long* s_tmp) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+__device__ int wave_scan_excl(int v, int lane, int& total) {
+    int x = v;
 #pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o);
-    if (lane == 0) s_tmp[wave] = v;
-    __syncthreads();
-    long long t = 0;
-#pragma unroll
-    for (int w = 0; w < kPlanThreads / 64; ++w) t += s_tmp[w];
-    __syncthreads();
-    return t;
+    for (int o = 1; o < 64; o <<= 1) {
+        const int y = __shfl_up(x, o);
+        if (lane >= o) x += y;
+    }
+    total = __shfl(x, 63);
+    return x - v;
 }
 
 __device__ __forceinline__ uint32_t slot_of(int key) { return ((uint32_t)key * 2654435761u) >> 20; }  // 12 bits
 
-__device__ __forceinline__ void write_item(Item* it, int kind, int who, int g, int nrows, int mlist_off, int c0, int c1,
-                                           int pbase, int tok_end) {
+__device__ __forceinline__ void write_item(Item* it, const int32_t* table_row, int kind, int who, int g, int nrows,
+                                           int mlist_off, int c0, int c1, int pbase, int tok_end) {
+    const int last = c1 - 1;
+    const int f0 = table_row[c0], f1 = table_row[min(c0 + 1, last)];
+    const int f2 = table_row[min(c0 + 2, last)], f3 = table_row[min(c0 + 3, last)];
     int4* p = reinterpret_cast<int4*>(it);
     p[0] = make_int4(who, g, nrows, mlist_off);
     p[1] = make_int4(c0, c1, pbase, tok_end);
-    p[2] = make_int4(kind, 0, 0, 0);
+    p[2] = make_int4(f0, f1, f2, f3);
+    p[3] = make_int4(kind, 0, 0, 0);
 }
+
+// How a segment of `tiles` tiles that starts at stream position S is cut.
+struct Cutter {
+    int fixed;        // > 0: cut every `fixed` tiles from the segment start; 0: cut at multiples of q in the stream
+    WideDiv by_q;
+    FastDiv by_fixed;
+    __device__ Cutter(int fixed_tiles, int q) : fixed(fixed_tiles), by_q(max(q, 1)), by_fixed(max(fixed_tiles, 1)) {}
+    __device__ __forceinline__ int pieces(int S, int tiles) const {
+        if (tiles <= 0) return 0;
+        if (fixed > 0) return by_fixed.cdiv(tiles);
+        return 1 + by_q.div(S + tiles - 1) - by_q.div(S);
+    }
+    // tile range [jb, je) of piece p; k0 = by_q.div(S)
+    __device__ __forceinline__ void range(int S, int tiles, int k0, int p, int& jb, int& je) const {
+        if (fixed > 0) {
+            jb = p * fixed;
+            je = min(tiles, jb + fixed);
+        } else {
+            jb = p == 0 ? 0 : (k0 + p) * by_q.d - S;
+            je = min(tiles, (k0 + p + 1) * by_q.d - S);
+        }
+    }
+};
+
+constexpr int kGroupMax = kGroupReqMax / 2;   // a group has at least two members
 
 __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
     static_assert(kHashSlots == 4096, "slot_of() yields 12 bits");
     __shared__ union {
-        struct { int keys[kHashSlots]; int vals[kHashSlots]; } h;
-        struct { int run[kGroupReqMax]; int cnt[kGroupReqMax]; int moff[kGroupReqMax]; } c;
+        struct { int keys[kHashSlots]; int vals[kHashSlots]; } h;                     // leader finding only
+        struct { int run[kGroupReqMax]; int cnt[kGroupReqMax]; int moff[kGroupReqMax];
+                 int gseg[kGroupMax]; } c;                                            // afterwards
     } u;
     __shared__ short s_lead[kGroupReqMax];      // request ids fit 16 bits (kGroupReqMax <= 32767)
-    __shared__ int s_lcp[kGroupReqMax];
     __shared__ int s_len[kGroupReqMax];
-    __shared__ unsigned short s_flw[kGroupReqMax];   // followers: grouped requests that are not their group's leader
+    __shared__ union {
+        int lcp[kGroupReqMax];                                  // until the group runs are known
+        struct { int npc[kGroupMax]; int ibase[kGroupMax]; int rbase[kGroupMax]; } g;   // then the cut of each group
+    } v;
+    __shared__ union {
+        unsigned short flw[kGroupReqMax];       // followers (grouped, not leader), for the run detection
+        unsigned short glist[kGroupMax];        // then the list of viable leaders
+    } w;
     __shared__ int s_tmp[64];
-    __shared__ long long s_tmpll[kPlanThreads / 64];
-    __shared__ int s_glist[kGroupReqMax / 2];   // viable leaders (a group has >= 2 members)
     __shared__ int s_ngroups, s_ngrouped, s_shared_blocks, s_nflw;
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -106,9 +158,11 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
     ReqDesc* req = reinterpret_cast<ReqDesc*>(a.ws + a.lay.req);
     GroupDesc* grp = reinterpret_cast<GroupDesc*>(a.ws + a.lay.grp);
     int* members = reinterpret_cast<int*>(a.ws + a.lay.members);
+    SegDesc* segs = reinterpret_cast<SegDesc*>(a.ws + a.lay.segs);
+    int* wave_first = reinterpret_cast<int*>(a.ws + a.lay.wave_first);
     Item* items = reinterpret_cast<Item*>(a.ws + a.lay.items);
 
-    const int B = a.B;
+    const int B = a.B, Hkv = a.Hkv;
     const int nG = a.grouping ? min(B, kGroupReqMax) : 0;
     const int maxL = a.stride * kBlock;
     auto clampL = [&](int L) { return max(0, min(L, maxL)); };
@@ -151,13 +205,13 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
                 while (u.h.keys[s] != key) s = (s + 1) & (kHashSlots - 1);
                 lead = u.h.vals[s];
                 lcp = min(s_len[i], s_len[lead]) / kBlock;
-                if (lead != i) s_flw[atomicAdd(&s_nflw, 1)] = (unsigned short)i;
+                if (lead != i) w.flw[atomicAdd(&s_nflw, 1)] = (unsigned short)i;
             }
             s_lead[i] = (short)lead;
-            s_lcp[i] = lcp;
+            v.lcp[i] = lcp;
         }
     }
-    __syncthreads();   // the hash table is dead from here on; its memory becomes run/cnt/moff
+    __syncthreads();   // the hash table is dead from here on; its memory becomes run/cnt/moff/...
     for (int i = tid; i < nG; i += kPlanThreads) { u.c.run[i] = INT_MAX; u.c.cnt[i] = 0; u.c.moff[i] = 0; }
 
     // ---- longest common run of block ids with the leader's row.  All (follower,
@@ -180,10 +234,10 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
                 who[q] = -1;
                 if (e < total) {
                     const int f = by_epr.div(e);
-                    const int i = s_flw[f];
+                    const int i = w.flw[f];
                     const int lead = s_lead[i];
                     const int c = (e - f * epr) * cpe;
-                    const int cp = min(s_len[i], s_len[lead]) / kBlock;   // the starting value of s_lcp[i]
+                    const int cp = min(s_len[i], s_len[lead]) / kBlock;   // the starting value of lcp[i]
                     if (c < cp) {
                         who[q] = i; col[q] = c; cap[q] = cp;
                         const int32_t* ri = a.bt + (size_t)i * a.stride + c;
@@ -206,7 +260,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
                     if (xs[q].z != ys[q].z) first = col[q] + 2;
                     if (xs[q].y != ys[q].y) first = col[q] + 1;
                     if (xs[q].x != ys[q].x) first = col[q];
-                    if (first < cap[q]) atomicMin(&s_lcp[who[q]], first);
+                    if (first < cap[q]) atomicMin(&v.lcp[who[q]], first);
                 }
             }
         }
@@ -222,16 +276,16 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
         if (i < nG) {
             const int lead = s_lead[i];
             if (lead >= 0) {
-                atomicMin(&u.c.run[lead], s_lcp[i]);
+                atomicMin(&u.c.run[lead], v.lcp[i]);
                 my_rank[k] = atomicAdd(&u.c.cnt[lead], 1);
             }
         }
     }
-    __syncthreads();
+    __syncthreads();   // lcp[] and flw[] are dead from here on
     auto viable = [&](int i) { return s_lead[i] == i && u.c.cnt[i] >= 2 && u.c.run[i] >= a.tune.min_run; };
     const FastDiv by_mpt(a.mpt);
 
-    // ---- member-list offsets (exclusive scan over leaders)
+    // ---- member-list offsets (exclusive scan over leaders) and the list of groups
     {
         const int per = (nG + kPlanThreads - 1) / kPlanThreads;   // 0, 1 or 2
         const int i0 = tid * per, i1 = min(nG, i0 + per);
@@ -244,166 +298,219 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
             if (viable(i)) {
                 u.c.moff[i] = base;
                 base += u.c.cnt[i];
-                const int gi = atomicAdd(&s_ngroups, 1);
-                s_glist[gi] = i;
+                w.glist[atomicAdd(&s_ngroups, 1)] = (unsigned short)i;
                 atomicAdd(&s_shared_blocks, u.c.run[i]);
             }
         if (tid == 0) s_ngrouped = total;
     }
     __syncthreads();
+    const int n_groups = s_ngroups;
 
-    // ---- totals that fix the split size; member lists (grouped part, then identity)
-    long long w_local = 0, rb_local = 0;
+    // ---- cost model.  A 32-token tile costs a wave more the more query rows ride on
+    // it; weights in quarter units of a one-row-tile sweep.  Shared runs are cut into
+    // equal pieces per segment, one piece per wave (a "share"); the private columns of
+    // all requests form one stream of tiles that is cut into equal shares for the
+    // remaining waves.  Both kinds of share are sized to the same cost.
+    auto tile_weight = [&](int rows) { return rows <= 16 ? 4 : (rows <= 32 ? 5 : 6); };
+    auto run_of = [&](int i) {   // shared columns of request i (0 if ungrouped)
+        if (i >= nG) return 0;
+        const int lead = s_lead[i];
+        return (lead >= 0 && viable(lead)) ? u.c.run[lead] : 0;
+    };
+    auto len_of = [&](int i) { return i < nG ? s_len[i] : clampL(a.seq_lens[i]); };
+    auto priv_tiles = [&](int i) { return ((((len_of(i) + kBlock - 1) / kBlock) - run_of(i)) + 1) >> 1; };   // per KV head
+
+    // private stream: request i owns Hkv * priv_tiles(i) consecutive tiles, KV head by KV head
+    const int per = (B + kPlanThreads - 1) / kPlanThreads;
+    const int r0 = tid * per, r1 = min(B, r0 + per);
+    int lt = 0;
+    for (int i = r0; i < r1; ++i) lt += Hkv * priv_tiles(i);
+    int T_pr;
+    const int tbase = block_scan_excl(lt, s_tmp, T_pr);
+    // shared side, serial over the (few) groups: units of cost, then the cut of each group
+    __shared__ int s_plan[8];
+    if (tid == 0) {
+        long long U = 4ll * T_pr;
+        int T_sh = 0;
+        for (int gi = 0; gi < n_groups; ++gi) {
+            const int ld = w.glist[gi];
+            const int tiles_r = by_mpt.cdiv(u.c.cnt[ld]), T_seg = (u.c.run[ld] + 1) >> 1;
+            const int wgt = tile_weight(min(a.mpt, u.c.cnt[ld]) * a.G);
+            U += (long long)Hkv * tiles_r * T_seg * wgt;
+            T_sh += Hkv * tiles_r * T_seg;
+        }
+        int fixed_tiles = 0, q = 1, n_sh = 0;
+        if (a.split_user > 0) fixed_tiles = a.split_user >> 1;   // split_user is even
+        const long long total_tiles = (long long)T_pr + T_sh;
+        const int n_act = (int)max(1ll, min((long long)a.tune.n_waves, total_tiles / max(a.tune.min_piece, 1)));
+        const long long Q = max(4ll, (U + n_act - 1) / n_act);   // cost per share
+        int seg_acc = 0;
+        for (int gi = 0; gi < n_groups; ++gi) {
+            const int ld = w.glist[gi];
+            const int tiles_r = by_mpt.cdiv(u.c.cnt[ld]), T_seg = (u.c.run[ld] + 1) >> 1;
+            const int wgt = tile_weight(min(a.mpt, u.c.cnt[ld]) * a.G);
+            const int want = fixed_tiles > 0 ? fixed_tiles : (int)max(1ll, Q / wgt);   // tiles per piece
+            const int n_pc = (T_seg + want - 1) / want;
+            v.g.npc[gi] = n_pc;
+            v.g.ibase[gi] = n_sh;                       // its items are shares n_sh ..
+            u.c.gseg[gi] = seg_acc;
+            n_sh += Hkv * tiles_r * n_pc;
+            seg_acc += Hkv * tiles_r;
+        }
+        if (fixed_tiles == 0) {
+            // private shares: the waves left over, but never fewer than the stream needs at a share's cost
+            const long long n_pr = max((long long)(n_act - n_sh), (4ll * T_pr + Q - 1) / Q);
+            q = (int)max(1ll, (T_pr + max(n_pr, 1ll) - 1) / max(n_pr, 1ll));
+        }
+        s_plan[0] = fixed_tiles;
+        s_plan[1] = q;
+        s_plan[2] = n_sh;
+    }
+    __syncthreads();
+    const int fixed_tiles = s_plan[0], q = s_plan[1], n_sh = s_plan[2];
+    const Cutter cut(fixed_tiles, q);
+
+    // partial-row bases of the groups (serial again: few groups) - items are counted in n_sh
+    if (tid == 0) {
+        int rb = 0;
+        for (int gi = 0; gi < n_groups; ++gi) {
+            v.g.rbase[gi] = rb;
+            rb += Hkv * v.g.npc[gi] * u.c.cnt[w.glist[gi]] * a.G;
+        }
+        s_plan[3] = rb;
+    }
+    // ---- item and partial-row counts of the requests, scanned in stream order
+    int li = 0;
+    {
+        int tb = tbase;
+        for (int i = r0; i < r1; ++i) {
+            const int T_seg = priv_tiles(i);
+            for (int g = 0; g < Hkv; ++g) li += cut.pieces(tb + g * T_seg, T_seg);
+            tb += Hkv * T_seg;
+        }
+    }
+    int priv_items;
+    const int ibase = n_sh + block_scan_excl(li, s_tmp, priv_items);   // (the scan's barriers publish s_plan[3])
+    const int rows_sh = s_plan[3];
+    const int total_items = n_sh + priv_items, total_rows = rows_sh + priv_items * a.G;
+    const bool overflow = total_items > a.lay.max_items || total_rows > a.lay.max_rows;
+
+    // shares: a shared piece each, then the cuts of the private stream; with a fixed
+    // split all items are dealt out in equal numbers instead
+    const int n_shares = overflow ? 0 : (fixed_tiles > 0 ? min(a.tune.n_waves, total_items) : n_sh + (T_pr + q - 1) / q);
+    for (int x = tid; x <= a.lay.max_items; x += kPlanThreads) {
+        int first = overflow ? 0 : total_items;
+        if (!overflow) {
+            if (fixed_tiles > 0) { if (x < n_shares) first = (int)(((long long)x * total_items) / n_shares); }
+            else if (x <= n_sh) first = x;
+        }
+        if (x <= n_shares || x == a.lay.max_items) wave_first[x] = first;
+    }
+    __syncthreads();   // defaults of wave_first[] are in place before pieces overwrite their entries
+
+    // ---- descriptors and items of the requests
+    {
+        int tb = tbase, idx = ibase;
+        for (int i = r0; i < r1; ++i) {
+            const int L = len_of(i), nb = (L + kBlock - 1) / kBlock, c0 = run_of(i);
+            const int T_seg = priv_tiles(i);
+            ReqDesc rd;
+            rd.group = c0 > 0 ? (int)s_lead[i] : -1;
+            rd.rank = 0;
+            rd.priv_c0 = c0;
+            rd.nb = nb;
+            rd.L = L;
+            rd.pad[0] = rd.pad[1] = rd.pad[2] = 0;
+            req[i] = rd;
+            const int32_t* trow = a.bt + (size_t)i * a.stride;
+            for (int g = 0; g < Hkv; ++g) {
+                const int S = tb + g * T_seg;
+                const int np = overflow ? 0 : cut.pieces(S, T_seg);
+                SegDesc sd;
+                sd.pbase = rows_sh + (idx - n_sh) * a.G;
+                sd.npieces = np;
+                segs[(size_t)i * Hkv + g] = sd;
+                const int k0 = cut.by_q.div(S);
+                for (int p = 0; p < np; ++p) {
+                    int jb, je;
+                    cut.range(S, T_seg, k0, p, jb, je);
+                    const int cs = c0 + 2 * jb, ce = min(nb, c0 + 2 * je);
+                    write_item(&items[idx], trow, 0, i, g, a.G, B + i, cs, ce, rows_sh + (idx - n_sh) * a.G,
+                               min(L, ce * kBlock));
+                    if (fixed_tiles == 0 && (p > 0 || S == k0 * q)) wave_first[n_sh + k0 + p] = idx;
+                    ++idx;
+                }
+            }
+            tb += Hkv * T_seg;
+        }
+    }
+    // ranks live with the thread that drew them; member lists (grouped part, then identity)
+    __syncthreads();
     for (int k = 0, i = tid; i < B; i += kPlanThreads, ++k) {
-        const int nb = ((i < nG ? s_len[i] : clampL(a.seq_lens[i])) + kBlock - 1) / kBlock;
-        int run_i = 0;
         if (i < nG) {
             const int lead = s_lead[i];
             if (lead >= 0 && viable(lead)) {
-                run_i = u.c.run[lead];
+                req[i].rank = my_rank[k];
                 members[u.c.moff[lead] + my_rank[k]] = i;
             }
-            if (viable(i)) w_local += (long long)u.c.run[i] * a.Hkv * by_mpt.cdiv(u.c.cnt[i]);
         }
         members[B + i] = i;
-        w_local += (long long)(nb - run_i) * a.Hkv;
-        rb_local += (long long)nb * a.Hq;
     }
-    const long long W = block_sum_ll(w_local, s_tmpll);
-    const long long RB = block_sum_ll(rb_local, s_tmpll);
-    int split = a.split_user;
-    if (split <= 0) {
-        long long s = a.tune.min_split;
-        s = max(s, (W + a.tune.target_items - 1) / a.tune.target_items);
-        s = max(s, (RB + a.tune.row_budget - 1) / a.tune.row_budget);
-        split = (int)min(s, (long long)INT_MAX / 64);
-    }
-    split = (split + 1) & ~1;   // sweeps advance two blocks at a time
-    const FastDiv by_split(split);
-
-    // ---- per-segment item and partial-row counts, scanned: groups first, then requests
-    const int N = nG + B;
-    const int per = (N + kPlanThreads - 1) / kPlanThreads;
-    const int e0 = tid * per, e1 = min(N, e0 + per);
-    auto seg_counts = [&](int e, int& n_items, int& n_rows, int& nsplits, int& c0, int& L) {
-        n_items = n_rows = nsplits = c0 = L = 0;
-        if (e < nG) {
-            if (viable(e)) {
-                nsplits = by_split.cdiv(u.c.run[e]);
-                n_items = a.Hkv * by_mpt.cdiv(u.c.cnt[e]) * nsplits;
-                n_rows = nsplits * u.c.cnt[e] * a.Hq;
-            }
-        } else {
-            const int i = e - nG;
-            L = i < nG ? s_len[i] : clampL(a.seq_lens[i]);
-            if (i < nG) {
-                const int lead = s_lead[i];
-                if (lead >= 0 && viable(lead)) c0 = u.c.run[lead];
-            }
-            nsplits = by_split.cdiv((L + kBlock - 1) / kBlock - c0);
-            n_items = a.Hkv * nsplits;
-            n_rows = nsplits * a.Hq;
-        }
-    };
-    int li = 0, lr = 0;
-    for (int e = e0; e < e1; ++e) {
-        int ni, nr, ns, c0, L;
-        seg_counts(e, ni, nr, ns, c0, L);
-        li += ni;
-        lr += nr;
-    }
-    int total_items, total_rows;
-    int ibase = block_scan_excl(li, s_tmp, total_items);
-    int rbase = block_scan_excl(lr, s_tmp, total_rows);
-    const bool overflow = total_items > a.lay.max_items || total_rows > a.lay.max_rows;
-
-    for (int e = e0; e < e1; ++e) {
-        int ni, nr, ns, c0, L;
-        seg_counts(e, ni, nr, ns, c0, L);
-        if (e < nG) {
-            const bool ok = viable(e);
-            GroupDesc gd;
-            gd.leader = e;
-            gd.members = ok ? u.c.cnt[e] : 0;
-            gd.run = ok ? u.c.run[e] : 0;
-            gd.nsplits = ns;
-            gd.pbase = rbase;
-            gd.member_off = u.c.moff[e];
-            gd.tiles = ok ? by_mpt.cdiv(u.c.cnt[e]) : 0;
-            gd.item_base = ibase;
-            grp[e] = gd;
-        } else {
-            const int i = e - nG;
-            const int nb = (L + kBlock - 1) / kBlock;
-            ReqDesc rd;
-            rd.group = -1;
-            rd.rank = 0;
-            if (i < nG) {
-                const int lead = s_lead[i];
-                if (lead >= 0 && viable(lead)) rd.group = lead;
-            }
-            rd.priv_c0 = c0;
-            rd.priv_nsplits = ns;
-            rd.priv_pbase = rbase;
-            rd.nb = nb;
-            rd.L = L;
-            rd.priv_item_base = ibase;
-            req[i] = rd;
-            if (!overflow) {
-                // private items of one request: KV head fastest, so that a request's
-                // heads (which read the same blocks' other head slices) run together
-                Item* dst = items + ibase;
-                for (int s = 0; s < ns; ++s) {
-                    const int cs = c0 + s * split, ce = min(nb, cs + split);
-                    for (int g = 0; g < a.Hkv; ++g)
-                        write_item(dst++, 0, i, g, a.G, B + i, cs, ce, rbase + s * a.Hq + g * a.G, min(L, ce * kBlock));
-                }
-            }
-        }
-        ibase += ni;
-        rbase += nr;
-    }
-    __syncthreads();
-    // ranks live with the thread that drew them
-#pragma unroll
-    for (int k = 0; k < kGroupReqMax / kPlanThreads; ++k) {
-        const int i = tid + k * kPlanThreads;
-        if (i < nG) {
-            const int lead = s_lead[i];
-            if (lead >= 0 && viable(lead)) req[i].rank = my_rank[k];
-        }
-    }
-    // shared items: one wave per group, row tile fastest so that the tiles of one
-    // (split, KV head), which read the same KV bytes, are handed out back to back
+    // ---- descriptors and items of the groups: one wave per group, lanes over its items.
+    // Order: KV head, piece, row tile - the row tiles of one piece read the same KV bytes
+    // and sit on neighbouring shares, which the sweep maps to one XCD.
     if (!overflow) {
-        for (int gi = wave; gi < s_ngroups; gi += kPlanThreads / 64) {
-            const int e = s_glist[gi];
-            const int members_g = u.c.cnt[e], run_g = u.c.run[e];
-            const int tiles = by_mpt.cdiv(members_g), nsplits = by_split.cdiv(run_g);
-            const GroupDesc gd = grp[e];   // for pbase / item_base (written above, visible after the barrier)
-            const FastDiv by_tiles(tiles), by_hkv(a.Hkv);
-            const int n = a.Hkv * tiles * nsplits;
+        for (int gi = wave; gi < n_groups; gi += kPlanThreads / 64) {
+            const int ld = w.glist[gi];
+            const int cnt = u.c.cnt[ld], run = u.c.run[ld];
+            const int tiles_r = by_mpt.cdiv(cnt), T_seg = (run + 1) >> 1;
+            const int n_pc = v.g.npc[gi];
+            const int ps = fixed_tiles > 0 ? fixed_tiles : (T_seg + n_pc - 1) / n_pc;   // tiles per piece
+            if (lane == 0) {
+                GroupDesc gd;
+                gd.leader = ld;
+                gd.members = cnt;
+                gd.run = run;
+                gd.member_off = u.c.moff[ld];
+                gd.tiles = tiles_r;
+                gd.seg_base = u.c.gseg[gi];
+                gd.pad[0] = gd.pad[1] = 0;
+                grp[ld] = gd;
+            }
+            const int32_t* trow = a.bt + (size_t)ld * a.stride;
+            const FastDiv by_tr(tiles_r), by_pc(n_pc);
+            const int n = Hkv * n_pc * tiles_r;
+            const int full_rows = a.mpt * a.G, last_rows = (cnt - (tiles_r - 1) * a.mpt) * a.G;
+            // partial rows of segment (g, tau): pieces p = 0 .. n_pc-1, rows(tau) each; segments in (g, tau) order
+            const int rows_per_head = cnt * a.G;
             for (int k = lane; k < n; k += 64) {
-                const int rest = by_tiles.div(k), tau = k - rest * tiles;
-                const int s = by_hkv.div(rest), g = rest - s * a.Hkv;
-                const int cs = s * split, ce = min(run_g, cs + split);
-                const int first = tau * a.mpt;
-                const int pb = gd.pbase + (s * a.Hkv + g) * members_g * a.G + first * a.G;
-                write_item(&items[gd.item_base + k], 1, e, g, min(a.mpt, members_g - first) * a.G, gd.member_off + first,
-                           cs, ce, pb, ce * kBlock);
+                const int rest = by_tr.div(k), tau = k - rest * tiles_r;
+                const int g = by_pc.div(rest), pc = rest - g * n_pc;
+                const int rows = tau == tiles_r - 1 ? last_rows : full_rows;
+                const int seg_pbase = v.g.rbase[gi] + n_pc * (g * rows_per_head + tau * full_rows);
+                const int cs = 2 * pc * ps, ce = min(run, 2 * (pc + 1) * ps);
+                write_item(&items[v.g.ibase[gi] + k], trow, 1, ld, g, rows, u.c.moff[ld] + tau * a.mpt, cs, ce,
+                           seg_pbase + pc * rows, ce * kBlock);
+                if (pc == 0) {
+                    SegDesc sd;
+                    sd.pbase = seg_pbase;
+                    sd.npieces = n_pc;
+                    segs[(size_t)B * Hkv + u.c.gseg[gi] + g * tiles_r + tau] = sd;
+                }
             }
         }
     }
     if (tid == 0) {
         hdr[H_ITEMS] = overflow ? 0 : total_items;
         hdr[H_QUEUE] = 0;
-        hdr[H_GROUPS] = s_ngroups;
+        hdr[H_GROUPS] = n_groups;
         hdr[H_GROUPED] = s_ngrouped;
-        hdr[H_SPLIT] = split;
+        hdr[H_SPLIT] = fixed_tiles > 0 ? 2 * fixed_tiles : 2 * q;
         hdr[H_ROWS] = total_rows;
         hdr[H_SHARED_BLOCKS] = s_shared_blocks;
         hdr[H_VARIANT] = a.variant;
         hdr[H_OVERFLOW] = overflow ? 1 : 0;
+        hdr[H_WAVES] = n_shares;
     }
 }
 

@@ -222,17 +222,23 @@ __global__ __launch_bounds__(256) void merge_kernel(SweepArgs a) {
         for (int e = lane; e < D; e += 64) Elem<T>::store(out + e, __uint_as_float(0x7FC00000u));
         return;
     }
+    // partials of the row: the pieces of its group's shared-run segment, then the
+    // pieces of its own private segment
+    const SegDesc* segs = reinterpret_cast<const SegDesc*>(a.ws + a.lay.segs);
     int ns_sh = 0, sh_base = 0, sh_stride = 0;
     if (rd.group >= 0) {
         const GroupDesc gd = reinterpret_cast<const GroupDesc*>(a.ws + a.lay.grp)[rd.group];
-        ns_sh = gd.nsplits;
-        sh_stride = a.Hkv * gd.members * a.G;
-        sh_base = gd.pbase + g * gd.members * a.G + rd.rank * a.G + hh;
+        const int tau = rd.rank / a.mpt;
+        const SegDesc sd = segs[(size_t)a.B * a.Hkv + gd.seg_base + g * gd.tiles + tau];
+        ns_sh = sd.npieces;
+        sh_stride = min(a.mpt, gd.members - tau * a.mpt) * a.G;
+        sh_base = sd.pbase + (rd.rank - tau * a.mpt) * a.G + hh;
     }
-    const int ns_pr = rd.priv_nsplits;
-    const int pr_base = rd.priv_pbase + h;
+    const SegDesc pd = segs[(size_t)i * a.Hkv + g];
+    const int ns_pr = pd.npieces;
+    const int pr_base = pd.pbase + hh;
     const int ns = ns_sh + ns_pr;
-    auto prow = [&](int s) { return s < ns_sh ? sh_base + s * sh_stride : pr_base + (s - ns_sh) * a.Hq; };
+    auto prow = [&](int s) { return s < ns_sh ? sh_base + s * sh_stride : pr_base + (s - ns_sh) * a.G; };
 
     float M = -INFINITY;
     for (int s = 0; s < ns; ++s) M = fmaxf(M, ml[prow(s)].x);

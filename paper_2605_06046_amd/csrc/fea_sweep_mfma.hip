@@ -1,8 +1,9 @@
 // KV sweep on the matrix cores: bf16 caches, head_dim 128, query group size a
 // power of two up to 16.
 //
-// Persistent single-wave workgroups pull work items from a queue in the
-// workspace.  An item is a set of up to 32 query rows (one request's query group,
+// One single-wave workgroup per SIMD; the planner has cut the stream of 32-token
+// tiles into equal shares, and wave w sweeps the consecutive work items of share w.
+// An item is a set of up to 64 query rows (one request's query group,
 // or a row tile of a prefix group: members x group heads stacked) x one KV head x
 // a range of table columns; the wave sweeps the range with an online softmax and
 // writes one partial (m, l, acc[128]) per query row.
@@ -21,7 +22,9 @@
 // lane loads that write straight into LDS (global_load_lds_dwordx4), so data in
 // flight costs no registers: two 16 KB stages per wave, and the fetch of tile
 // t+2 is issued as soon as tile t has been read out of its stage, which keeps
-// two tiles in flight while a tile is being computed.  Each load covers four
+// two tiles in flight while a tile is being computed - across item boundaries too:
+// an item's descriptor carries its first four block ids, so the last tiles of one
+// item overlap with the first fetches of the next.  Each load covers four
 // whole 256-byte token rows; inside a row the sixteen 16-byte chunks are placed
 // XOR-swizzled by the row number, which makes the "lane = token" reads of the K
 // operand bank-conflict free without padding (the DMA path cannot pad).  V needs
@@ -36,6 +39,8 @@
 // base-2 domain.  Products are bf16 x bf16 accumulated in float32; the softmax
 // weights are rounded to bf16 for the second product, the sums stay float32.
 #include <hip/hip_runtime.h>
+
+#include <cstdlib>
 
 #include "fea_plan.h"
 
@@ -56,15 +61,42 @@ __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast
 __device__ __forceinline__ u32x4 ld16(const void* p) { return *reinterpret_cast<const u32x4*>(p); }
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// 64 lanes x 16 bytes from global memory straight into LDS: lane l's bytes land at
-// lds_addr + 16 l (lds_addr is wave-uniform and goes through M0).
-__device__ __forceinline__ void dma16(const char* base, uint32_t lane_off, uint32_t lds_addr) {
-    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1"
+// Wave-uniform values that must sit in scalar registers (folded away by the compiler
+// where it already knows them to be uniform).
+// (The builtin returns a signed int: the halves go through uint32_t so that the low
+// word is zero-extended, not sign-extended, when the pointer is put back together.)
+__device__ __forceinline__ uint32_t sgpr(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
+__device__ __forceinline__ const char* sgpr(const void* p) {
+    const uint64_t v = reinterpret_cast<uint64_t>(p);
+    const uint64_t lo = sgpr((uint32_t)v), hi = sgpr((uint32_t)(v >> 32));
+    return reinterpret_cast<const char*>(lo | (hi << 32));
+}
+
+// Four wave-wide loads of 64 x 16 bytes from global memory straight into LDS: load
+// i reads base + off_i (per lane) and lane l's bytes land at lds_i + 16 l.  The LDS
+// addresses are wave-uniform and go through M0.  The scalar operands may have been
+// produced by a vector instruction (v_readfirstlane) just before; the hardware
+// wants five wait states between such a write and a memory instruction that reads
+// the register, and the compiler cannot see into this block, hence the s_nop.
+__device__ __forceinline__ void dma16x4(const char* base, uint32_t off0, uint32_t off1, uint32_t off2, uint32_t off3,
+                                        uint32_t lds0, uint32_t lds1, uint32_t lds2, uint32_t lds3) {
+    asm volatile(
+        "s_nop 4\n\t"
+        "s_mov_b32 m0, %5\n\tglobal_load_lds_dwordx4 %0, %4\n\t"
+        "s_mov_b32 m0, %6\n\tglobal_load_lds_dwordx4 %1, %4\n\t"
+        "s_mov_b32 m0, %7\n\tglobal_load_lds_dwordx4 %2, %4\n\t"
+        "s_mov_b32 m0, %8\n\tglobal_load_lds_dwordx4 %3, %4"
+        :: "v"(off0), "v"(off1), "v"(off2), "v"(off3), "s"(base), "s"(lds0), "s"(lds1), "s"(lds2), "s"(lds3)
+        : "memory", "m0");
+}
+// One load of 4 bytes per lane (block ids of 64 table columns), same conventions.
+__device__ __forceinline__ void dma4(const void* base, uint32_t lane_off, uint32_t lds_addr) {
+    asm volatile("s_nop 4\n\ts_mov_b32 m0, %2\n\tglobal_load_lds_dword %0, %1"
                  :: "v"(lane_off), "s"(base), "s"(lds_addr) : "memory", "m0");
 }
 // acc *= f for an accumulator tuple that lives in the accumulation registers.  Done
 // by hand so that the register allocator keeps the big O accumulators there (a
-// plain C++ multiply would pull all 128 of them into the vector register file and
+// plain C++ multiply would pull all of them into the vector register file and
 // make every tile pay for copies).  Only the rare "raise the reference" path runs
 // this; the leading s_nop covers the matrix-core write -> read distance even if a
 // product into the same tuple were the immediately preceding instruction.
@@ -83,11 +115,6 @@ __device__ __forceinline__ void scale_acc(f32x4& acc, float f) {
         : "v"(f));
     acc[0] = a0; acc[1] = a1; acc[2] = a2; acc[3] = a3;
 }
-// Same for 4 bytes per lane (block ids of 64 table columns).
-__device__ __forceinline__ void dma4(const void* base, uint32_t lane_off, uint32_t lds_addr) {
-    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dword %0, %1"
-                 :: "v"(lane_off), "s"(base), "s"(lds_addr) : "memory", "m0");
-}
 template <int N> __device__ __forceinline__ void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory"); }
 __device__ __forceinline__ void wait_lgkmcnt0() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 
@@ -103,28 +130,36 @@ struct Lanes {
 __device__ __forceinline__ void fetch_tile(const SweepArgs& a, int g, int b0, int b1, uint32_t stage, const Lanes& L) {
     const size_t o0 = ((size_t)b0 * a.Hkv + g) * kBlkBytes;
     const size_t o1 = ((size_t)b1 * a.Hkv + g) * kBlkBytes;
-    const char* k0 = static_cast<const char*>(a.k_cache) + o0;
-    const char* k1 = static_cast<const char*>(a.k_cache) + o1;
-    const char* v0 = static_cast<const char*>(a.v_cache) + o0;
-    const char* v1 = static_cast<const char*>(a.v_cache) + o1;
+    const char* k0 = sgpr(static_cast<const char*>(a.k_cache) + o0);
+    const char* k1 = sgpr(static_cast<const char*>(a.k_cache) + o1);
+    const char* v0 = sgpr(static_cast<const char*>(a.v_cache) + o0);
+    const char* v1 = sgpr(static_cast<const char*>(a.v_cache) + o1);
+    stage = sgpr(stage);
+    const char* bases[4] = {k0, k1, v0, v1};
 #pragma unroll
-    for (int i = 0; i < 4; ++i) dma16(k0, L.dma_off[i], stage + i * 1024);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) dma16(k1, L.dma_off[i], stage + kBlkBytes + i * 1024);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) dma16(v0, L.dma_off[i], stage + 2 * kBlkBytes + i * 1024);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) dma16(v1, L.dma_off[i], stage + 3 * kBlkBytes + i * 1024);
+    for (int x = 0; x < 4; ++x) {
+        const uint32_t l = stage + x * kBlkBytes;
+        dma16x4(bases[x], L.dma_off[0], L.dma_off[1], L.dma_off[2], L.dma_off[3], l, l + 1024, l + 2048, l + 3072);
+    }
 }
 
+// Tile stream of one wave.  `phase` is the stage the current item's tile 0 uses,
+// `iss` counts the tiles issued so far, numbered from the current item's tile 0
+// (so it can already be 1 or 2 when the item starts: its predecessor fetched them).
+struct Stream {
+    int phase;
+    int iss;
+};
+
 template <int NT>
-__device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item, int log2G, char* s_stage,
-                                           const int* s_cols, uint32_t lds_base, uint32_t cols_base, const Lanes& L,
-                                           int lane) {
+__device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item, const Item& next, bool has_next,
+                                           int log2G, char* s_stage, const int* s_cols, uint32_t lds_base,
+                                           uint32_t cols_base, const Lanes& L, int lane, Stream& sm) {
     const int n = L.n, kg = L.kg;
     const uint16_t* Q = static_cast<const uint16_t*>(a.q);
     const int* mlist = reinterpret_cast<const int*>(a.ws + a.lay.members) + item.mlist_off;
     const int ntiles = (item.c1 - item.c0 + 1) >> 1;
+    const int next_pre = has_next ? min(2, (next.c1 - next.c0 + 1) >> 1) : 0;   // tiles of the next item we may fetch
 
     // Block ids of the item's columns travel through LDS as well, 64 columns per
     // window, two windows: the compiler then sees no pending vector-memory load
@@ -132,18 +167,39 @@ __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item,
     const int32_t* trow = a.bt + (size_t)item.who * a.stride;
     const int last_col = item.c1 - 1;
     auto fetch_cols = [&](int win) {   // clamped: never reads a dead table entry
-        dma4(trow, (uint32_t)min(item.c0 + 64 * win + lane, last_col) * 4u, cols_base + (win & 1) * 256);
+        dma4(sgpr(trow), (uint32_t)min(item.c0 + 64 * win + lane, last_col) * 4u, sgpr(cols_base + (win & 1) * 256));
     };
-    // block ids of tile t; must be called with t = 0, 1, 2, ... in order
-    auto tile_blocks = [&](int t, int& b0, int& b1) {
-        const int w = t & 31, win = t >> 5;
-        if (w == 0 && t > 0) fetch_cols(win + 1);   // window `win` was fetched 32 tiles ago
-        const int* sc = s_cols + (win & 1) * 64 + 2 * w;
-        b0 = __builtin_amdgcn_readfirstlane(sc[0]);
-        b1 = __builtin_amdgcn_readfirstlane(sc[1]);
+    // Issue stream tile `idx` (own tile idx, or tile idx - ntiles of the next item) if it
+    // is the next one due and exists; own tiles must be asked for in increasing order.
+    auto issue = [&](int idx) {
+        if (idx != sm.iss) return;
+        int b0, b1;
+        int g = item.g;
+        if (idx < ntiles) {
+            if (idx < 2) {
+                b0 = idx == 0 ? item.fb[0] : item.fb[2];
+                b1 = idx == 0 ? item.fb[1] : item.fb[3];
+            } else {
+                const int w = idx & 31, win = idx >> 5;
+                if (w == 0) fetch_cols(win + 1);   // window `win` itself was fetched 32 tiles ago
+                const int* sc = s_cols + (win & 1) * 64 + 2 * w;
+                b0 = __builtin_amdgcn_readfirstlane(sc[0]);
+                b1 = __builtin_amdgcn_readfirstlane(sc[1]);
+            }
+        } else {
+            const int j = idx - ntiles;
+            if (j >= next_pre) return;
+            b0 = j == 0 ? next.fb[0] : next.fb[2];
+            b1 = j == 0 ? next.fb[1] : next.fb[3];
+            g = next.g;
+        }
+        fetch_tile(a, g, b0, b1, lds_base + ((sm.phase + idx) & 1) * kStageBytes, L);
+        sm.iss = idx + 1;
     };
     fetch_cols(0);
     fetch_cols(1);
+    issue(0);
+    issue(1);
 
     // B operand of the first product: Q^T, lane (n, kg) holds q[row n][32 ks + 8 kg .. +8]
     bf16x8 qB[NT][4];
@@ -162,20 +218,12 @@ __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item,
         }
     }
     // Everything the compiler knows to be in flight is consumed here, before the
-    // tile loop (this also covers the two column windows).
+    // tile loop (this also covers the two column windows and the first tiles).
     wait_vmcnt<0>();
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) asm volatile("" : "+v"(qB[nt][ks]));
-
-    int b0, b1;
-    tile_blocks(0, b0, b1);
-    fetch_tile(a, item.g, b0, b1, lds_base, L);
-    if (ntiles > 1) {
-        tile_blocks(1, b0, b1);
-        fetch_tile(a, item.g, b0, b1, lds_base + kStageBytes, L);
-    }
 
     // The softmax denominator is accumulated by the matrix core as well: a V^T row
     // of ones turns the second product into sum_t p_t, taken over the same bf16-
@@ -194,9 +242,9 @@ __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item,
     }
 
     for (int t = 0; t < ntiles; ++t) {
-        const char* st = s_stage + (t & 1) * kStageBytes;
-        // tile t has landed once at most the 16 loads of tile t+1 are outstanding
-        if (t + 1 < ntiles) wait_vmcnt<16>(); else wait_vmcnt<0>();
+        const char* st = s_stage + ((sm.phase + t) & 1) * kStageBytes;
+        // tile t has landed once at most the 16 loads of stream tile t+1 are outstanding
+        if (sm.iss > t + 1) wait_vmcnt<16>(); else wait_vmcnt<0>();
         bf16x8 kA[2][4];
         u32x4 vr[8];
 #pragma unroll
@@ -205,11 +253,9 @@ __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item,
             for (int ks = 0; ks < 4; ++ks) kA[mt][ks] = as_bf16x8(ld16(st + mt * kBlkBytes + L.k_off[ks]));
 #pragma unroll
         for (int j = 0; j < 8; ++j) vr[j] = ld16(st + (2 + (j >> 2)) * kBlkBytes + L.v_off[j & 3]);
-        wait_lgkmcnt0();   // the stage is read out: refill it with tile t+2
-        if (t + 2 < ntiles) {
-            tile_blocks(t + 2, b0, b1);
-            fetch_tile(a, item.g, b0, b1, lds_base + (t & 1) * kStageBytes, L);
-        }
+        wait_lgkmcnt0();   // the stage is read out: refill it with stream tile t+2
+        issue(t + 1);      // (only due if the look-ahead into the next item stopped short)
+        issue(t + 2);
 
         const int tile_pos = (item.c0 + 2 * t) * kBlock;          // position of the tile's first token
         const bool ragged = tile_pos + kTileTok > item.tok_end;   // wave-uniform
@@ -307,9 +353,11 @@ __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item,
             if (kg == 0) ml[item.pbase + row] = make_float2(m_run[nt], l);
         }
     }
+    sm.phase = (sm.phase + ntiles) & 1;
+    sm.iss -= ntiles;
 }
 
-__global__ __launch_bounds__(64) void sweep_mfma_kernel(SweepArgs a, int log2G) {
+__global__ __launch_bounds__(64) void sweep_mfma_kernel(SweepArgs a, int log2G, int xcd_aware) {
     __shared__ __attribute__((aligned(1024))) char s_stage[kStages * kStageBytes];
     __shared__ __attribute__((aligned(256))) int s_cols[2 * 64];
     const int lane = threadIdx.x;
@@ -333,22 +381,67 @@ __global__ __launch_bounds__(64) void sweep_mfma_kernel(SweepArgs a, int log2G) 
         L.v_off[i] = vrow * 256 + ((L.n ^ vrow) & 15) * 16;    // chunk n of that row
     }
 
-    auto next_item = [&]() {
-        int it = 0;
-        if (lane == 0) it = atomicAdd(&hdr[H_QUEUE], 1);
-        return __builtin_amdgcn_readfirstlane(it);
+    // Descriptors are fetched as four 16-byte words and made wave-uniform (scalar
+    // registers) before use; the fetch of the descriptor after next is left in
+    // flight across a whole item.
+    struct Raw { int4 w[4]; };
+    auto load_raw = [&](int it) {
+        Raw r;
+        const int4* p = reinterpret_cast<const int4*>(items + min(it, n_items - 1));
+#pragma unroll
+        for (int k = 0; k < 4; ++k) r.w[k] = p[k];
+        return r;
     };
-    for (int it = next_item(); it < n_items; it = next_item()) {
-        const Item item = items[it];
-        if (item.nrows <= 16) sweep_item<1>(a, item, log2G, s_stage, s_cols, lds_base, cols_base, L, lane);
-        else sweep_item<2>(a, item, log2G, s_stage, s_cols, lds_base, cols_base, L, lane);
+    auto uniform = [&](const Raw& r) {
+        auto u = [](int v) { return __builtin_amdgcn_readfirstlane(v); };
+        Item x;
+        x.who = u(r.w[0].x); x.g = u(r.w[0].y); x.nrows = u(r.w[0].z); x.mlist_off = u(r.w[0].w);
+        x.c0 = u(r.w[1].x); x.c1 = u(r.w[1].y); x.pbase = u(r.w[1].z); x.tok_end = u(r.w[1].w);
+        x.fb[0] = u(r.w[2].x); x.fb[1] = u(r.w[2].y); x.fb[2] = u(r.w[2].z); x.fb[3] = u(r.w[2].w);
+        x.kind = u(r.w[3].x);
+        return x;
+    };
+
+    // Which shares this wave sweeps: share, share + grid, ...  Workgroups are dealt
+    // round-robin to the 8 XCDs (workgroup id mod 8), each with its own L2, while
+    // consecutive shares of a shared run are its row tiles over the same KV bytes.
+    // Put every 8 consecutive shares on one XCD so that those bytes are fetched into
+    // one L2 once.  (Pure performance: any permutation is correct.)
+    int share = blockIdx.x;
+    if (xcd_aware && (gridDim.x & 63) == 0) {
+        const int x = blockIdx.x & 7, k = blockIdx.x >> 3;
+        share = 8 * ((k >> 3) * 8 + x) + (k & 7);
+    }
+    const int n_shares = hdr[H_WAVES];
+    const int* wave_first = reinterpret_cast<const int*>(a.ws + a.lay.wave_first);
+    for (; share < n_shares; share += gridDim.x) {
+        int it = __builtin_amdgcn_readfirstlane(wave_first[share]);
+        const int it_end = min(n_items, __builtin_amdgcn_readfirstlane(wave_first[share + 1]));
+        if (it >= it_end) continue;
+        Stream sm;
+        sm.phase = 0;
+        sm.iss = 0;
+        Item item = uniform(load_raw(it));
+        Raw next_raw = load_raw(it + 1);
+        for (;;) {
+            const bool has_next = it + 1 < it_end;
+            const Item next = uniform(next_raw);
+            next_raw = load_raw(it + 2);
+            if (item.nrows <= 16) sweep_item<1>(a, item, next, has_next, log2G, s_stage, s_cols, lds_base, cols_base, L, lane, sm);
+            else if (item.nrows <= 32) sweep_item<2>(a, item, next, has_next, log2G, s_stage, s_cols, lds_base, cols_base, L, lane, sm);
+            else sweep_item<4>(a, item, next, has_next, log2G, s_stage, s_cols, lds_base, cols_base, L, lane, sm);
+            if (!has_next) break;
+            ++it;
+            item = next;
+        }
     }
 }
 
 void launch_sweep_mfma(const SweepArgs& a, int grid, void* stream) {
     int log2G = 0;
     while ((1 << log2G) < a.G) ++log2G;
-    hipLaunchKernelGGL(sweep_mfma_kernel, dim3(grid), dim3(64), 0, static_cast<hipStream_t>(stream), a, log2G);
+    static const int xcd_aware = [] { const char* v = std::getenv("FEA_XCD_AWARE"); return v && *v ? std::atoi(v) : 1; }();
+    hipLaunchKernelGGL(sweep_mfma_kernel, dim3(grid), dim3(64), 0, static_cast<hipStream_t>(stream), a, log2G, xcd_aware);
 }
 
 }  // namespace fea
