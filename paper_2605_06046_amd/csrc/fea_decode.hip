@@ -95,7 +95,7 @@ static int32_t resolve(const fea_attn_params* p, int32_t B, int32_t stride, Reso
     size_t off = up256(H_WORDS * sizeof(int32_t));
     l.req = off;      off += up256((size_t)B * sizeof(ReqDesc));
     l.grp = off;      off += up256((size_t)B * sizeof(GroupDesc));
-    l.members = off;  off += up256((size_t)2 * B * sizeof(int32_t));   // group lists, then the identity list
+    l.members = off;  off += up256((size_t)B * sizeof(int32_t));       // member lists of the groups
     l.segs = off;     off += up256((size_t)segs * sizeof(SegDesc));
     l.wave_first = off; off += up256((size_t)(max_items + 2) * sizeof(int32_t));
     l.items = off;    off += up256((size_t)max_items * sizeof(Item));

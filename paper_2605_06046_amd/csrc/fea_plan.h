@@ -29,13 +29,15 @@ enum Hdr {
     H_WORDS = 64
 };
 
-struct ReqDesc {       // one per request
-    int32_t group;     // leader request id of its group, or -1
-    int32_t rank;      // position inside the group
-    int32_t priv_c0;   // first private column (= shared run length, 0 if ungrouped)
+struct ReqDesc {       // one per request: where the merge finds the partials of its shared run
+    int32_t ns_sh;     // pieces of the group's shared run (0 if ungrouped)
+    int32_t sh_base0;  // partial row of (KV head 0, piece 0, this request's first query head)
+    int32_t sh_gstride;   // partial rows between KV heads
+    int32_t sh_pstride;   // partial rows between pieces (= rows of the request's row tile)
     int32_t nb;        // ceil(L / 16)
     int32_t L;
-    int32_t pad[3];
+    int32_t group;     // leader request id of its group, or -1
+    int32_t priv_c0;   // first private column (= shared run length, 0 if ungrouped)
 };
 
 struct GroupDesc {     // indexed by leader request id; valid only where members >= 2
@@ -57,20 +59,16 @@ struct SegDesc {
     int32_t npieces;
 };
 
-struct Item {          // one KV sweep: a row set x one KV head x a column range (64 bytes)
+struct Item {          // one KV sweep: a row set x one KV head x a column range (32 bytes)
     int32_t who;       // request whose table row is read (the group's leader for a shared run)
     int32_t g;         // KV head
     int32_t nrows;     // query rows: (requests in the row set) x (group heads)
-    int32_t mlist_off; // the row set's request ids start at members[mlist_off]
+    int32_t mlist_off; // the row set's request ids start at members[mlist_off]; -1: just `who`
     int32_t c0, c1;    // table columns [c0, c1) of `who`'s row
     int32_t pbase;     // partial row of the item's first query row
     int32_t tok_end;   // tokens at positions >= tok_end are not attended to
-    int32_t fb[4];     // block ids of columns c0 .. c0+3 (clamped to c1-1): lets a sweep start
-                       // fetching before it has read the table row itself
-    int32_t kind;      // 0: one request's private columns, 1: a group's shared run
-    int32_t pad[3];
 };
-static_assert(sizeof(Item) == 64, "Item is read as four 16-byte words");
+static_assert(sizeof(Item) == 32, "Item is read as two 16-byte words");
 
 // Byte offsets of the workspace sections (all multiples of 256).
 struct WsLayout {

@@ -95,16 +95,11 @@ __device__ int wave_scan_excl(int v, int lane, int& total) {
 
 __device__ __forceinline__ uint32_t slot_of(int key) { return ((uint32_t)key * 2654435761u) >> 20; }  // 12 bits
 
-__device__ __forceinline__ void write_item(Item* it, const int32_t* table_row, int kind, int who, int g, int nrows,
-                                           int mlist_off, int c0, int c1, int pbase, int tok_end) {
-    const int last = c1 - 1;
-    const int f0 = table_row[c0], f1 = table_row[min(c0 + 1, last)];
-    const int f2 = table_row[min(c0 + 2, last)], f3 = table_row[min(c0 + 3, last)];
+__device__ __forceinline__ void write_item(Item* it, int who, int g, int nrows, int mlist_off, int c0, int c1,
+                                           int pbase, int tok_end) {
     int4* p = reinterpret_cast<int4*>(it);
     p[0] = make_int4(who, g, nrows, mlist_off);
     p[1] = make_int4(c0, c1, pbase, tok_end);
-    p[2] = make_int4(f0, f1, f2, f3);
-    p[3] = make_int4(kind, 0, 0, 0);
 }
 
 // How a segment of `tiles` tiles that starts at stream position S is cut.
@@ -343,24 +338,32 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
         if (a.split_user > 0) fixed_tiles = a.split_user >> 1;   // split_user is even
         const long long total_tiles = (long long)T_pr + T_sh;
         const int n_act = (int)max(1ll, min((long long)a.tune.n_waves, total_tiles / max(a.tune.min_piece, 1)));
-        const long long Q = max(4ll, (U + n_act - 1) / n_act);   // cost per share
-        int seg_acc = 0;
-        for (int gi = 0; gi < n_groups; ++gi) {
-            const int ld = w.glist[gi];
-            const int tiles_r = by_mpt.cdiv(u.c.cnt[ld]), T_seg = (u.c.run[ld] + 1) >> 1;
-            const int wgt = tile_weight(min(a.mpt, u.c.cnt[ld]) * a.G);
-            const int want = fixed_tiles > 0 ? fixed_tiles : (int)max(1ll, Q / wgt);   // tiles per piece
-            const int n_pc = (T_seg + want - 1) / want;
-            v.g.npc[gi] = n_pc;
-            v.g.ibase[gi] = n_sh;                       // its items are shares n_sh ..
-            u.c.gseg[gi] = seg_acc;
-            n_sh += Hkv * tiles_r * n_pc;
-            seg_acc += Hkv * tiles_r;
-        }
-        if (fixed_tiles == 0) {
-            // private shares: the waves left over, but never fewer than the stream needs at a share's cost
-            const long long n_pr = max((long long)(n_act - n_sh), (4ll * T_pr + Q - 1) / Q);
-            q = (int)max(1ll, (T_pr + max(n_pr, 1ll) - 1) / max(n_pr, 1ll));
+        // Cost per share: start from an even split and grow it until shared pieces plus
+        // private shares fit the waves (rounding pieces up to whole tiles and whole
+        // segments can push the count over; a wave with two shares would be the tail).
+        long long Q = max(4ll, (U + n_act - 1) / n_act);
+        for (int round = 0; round < 4; ++round) {
+            n_sh = 0;
+            int seg_acc = 0;
+            for (int gi = 0; gi < n_groups; ++gi) {
+                const int ld = w.glist[gi];
+                const int tiles_r = by_mpt.cdiv(u.c.cnt[ld]), T_seg = (u.c.run[ld] + 1) >> 1;
+                const int wgt = tile_weight(min(a.mpt, u.c.cnt[ld]) * a.G);
+                const int want = fixed_tiles > 0 ? fixed_tiles : (int)max(1ll, Q / wgt);   // tiles per piece
+                const int n_pc = (T_seg + want - 1) / want;
+                v.g.npc[gi] = n_pc;
+                v.g.ibase[gi] = n_sh;                       // its items are shares n_sh ..
+                u.c.gseg[gi] = seg_acc;
+                n_sh += Hkv * tiles_r * n_pc;
+                seg_acc += Hkv * tiles_r;
+            }
+            if (fixed_tiles > 0) break;
+            // private shares at the same cost
+            const long long n_pr = max(1ll, (4ll * T_pr + Q - 1) / Q);
+            q = (int)max(1ll, (T_pr + n_pr - 1) / n_pr);
+            const long long shares = n_sh + (T_pr + q - 1) / q;
+            if (shares <= n_act) break;
+            Q = (Q * shares + n_act - 1) / n_act + 1;
         }
         s_plan[0] = fixed_tiles;
         s_plan[1] = q;
@@ -415,14 +418,12 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
             const int L = len_of(i), nb = (L + kBlock - 1) / kBlock, c0 = run_of(i);
             const int T_seg = priv_tiles(i);
             ReqDesc rd;
-            rd.group = c0 > 0 ? (int)s_lead[i] : -1;
-            rd.rank = 0;
-            rd.priv_c0 = c0;
+            rd.ns_sh = rd.sh_base0 = rd.sh_gstride = rd.sh_pstride = 0;   // a group fills these in below
             rd.nb = nb;
             rd.L = L;
-            rd.pad[0] = rd.pad[1] = rd.pad[2] = 0;
+            rd.group = c0 > 0 ? (int)s_lead[i] : -1;
+            rd.priv_c0 = c0;
             req[i] = rd;
-            const int32_t* trow = a.bt + (size_t)i * a.stride;
             for (int g = 0; g < Hkv; ++g) {
                 const int S = tb + g * T_seg;
                 const int np = overflow ? 0 : cut.pieces(S, T_seg);
@@ -435,8 +436,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
                     int jb, je;
                     cut.range(S, T_seg, k0, p, jb, je);
                     const int cs = c0 + 2 * jb, ce = min(nb, c0 + 2 * je);
-                    write_item(&items[idx], trow, 0, i, g, a.G, B + i, cs, ce, rows_sh + (idx - n_sh) * a.G,
-                               min(L, ce * kBlock));
+                    write_item(&items[idx], i, g, a.G, -1, cs, ce, rows_sh + (idx - n_sh) * a.G, min(L, ce * kBlock));
                     if (fixed_tiles == 0 && (p > 0 || S == k0 * q)) wave_first[n_sh + k0 + p] = idx;
                     ++idx;
                 }
@@ -444,18 +444,12 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
             tb += Hkv * T_seg;
         }
     }
-    // ranks live with the thread that drew them; member lists (grouped part, then identity)
-    __syncthreads();
-    for (int k = 0, i = tid; i < B; i += kPlanThreads, ++k) {
-        if (i < nG) {
-            const int lead = s_lead[i];
-            if (lead >= 0 && viable(lead)) {
-                req[i].rank = my_rank[k];
-                members[u.c.moff[lead] + my_rank[k]] = i;
-            }
-        }
-        members[B + i] = i;
+    // member lists of the groups (the rank lives with the thread that drew it)
+    for (int k = 0, i = tid; i < nG; i += kPlanThreads, ++k) {
+        const int lead = s_lead[i];
+        if (lead >= 0 && viable(lead)) members[u.c.moff[lead] + my_rank[k]] = i;
     }
+    __syncthreads();   // request descriptors and member lists are written: groups may amend them
     // ---- descriptors and items of the groups: one wave per group, lanes over its items.
     // Order: KV head, piece, row tile - the row tiles of one piece read the same KV bytes
     // and sit on neighbouring shares, which the sweep maps to one XCD.
@@ -477,7 +471,6 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
                 gd.pad[0] = gd.pad[1] = 0;
                 grp[ld] = gd;
             }
-            const int32_t* trow = a.bt + (size_t)ld * a.stride;
             const FastDiv by_tr(tiles_r), by_pc(n_pc);
             const int n = Hkv * n_pc * tiles_r;
             const int full_rows = a.mpt * a.G, last_rows = (cnt - (tiles_r - 1) * a.mpt) * a.G;
@@ -489,7 +482,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
                 const int rows = tau == tiles_r - 1 ? last_rows : full_rows;
                 const int seg_pbase = v.g.rbase[gi] + n_pc * (g * rows_per_head + tau * full_rows);
                 const int cs = 2 * pc * ps, ce = min(run, 2 * (pc + 1) * ps);
-                write_item(&items[v.g.ibase[gi] + k], trow, 1, ld, g, rows, u.c.moff[ld] + tau * a.mpt, cs, ce,
+                write_item(&items[v.g.ibase[gi] + k], ld, g, rows, u.c.moff[ld] + tau * a.mpt, cs, ce,
                            seg_pbase + pc * rows, ce * kBlock);
                 if (pc == 0) {
                     SegDesc sd;
@@ -497,6 +490,18 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
                     sd.npieces = n_pc;
                     segs[(size_t)B * Hkv + u.c.gseg[gi] + g * tiles_r + tau] = sd;
                 }
+            }
+            // where each member finds the partials of the shared run (rank r = position in the member list)
+            const FastDiv by_m(a.mpt);
+            for (int r = lane; r < cnt; r += 64) {
+                const int i = members[u.c.moff[ld] + r];
+                const int tau = by_m.div(r);
+                int4 shared;
+                shared.x = n_pc;
+                shared.y = v.g.rbase[gi] + n_pc * tau * full_rows + (r - tau * a.mpt) * a.G;
+                shared.z = n_pc * rows_per_head;
+                shared.w = tau == tiles_r - 1 ? last_rows : full_rows;
+                *reinterpret_cast<int4*>(&req[i]) = shared;
             }
         }
     }

@@ -85,7 +85,7 @@ __global__ __launch_bounds__(kGenThreads) void sweep_generic_kernel(SweepArgs a)
         for (int mh = 0; mh < n_mem * ((a.G + kHB - 1) / kHB); ++mh) {
             const int mem = mh / ((a.G + kHB - 1) / kHB);
             const int hb = (mh % ((a.G + kHB - 1) / kHB)) * kHB;
-            const int qreq = mlist[mem];
+            const int qreq = item.mlist_off < 0 ? item.who : mlist[mem];
             const int prow0 = item.pbase + mem * a.G + hb;
             const int nh = min(kHB, a.G - hb);
             float qf[kHB][EPL];
@@ -202,66 +202,85 @@ __global__ __launch_bounds__(kGenThreads) void sweep_generic_kernel(SweepArgs a)
 }
 
 // out[i,h,:] = sum_s 2^(m_s - M) acc_s / sum_s 2^(m_s - M) l_s over the partials
-// of row (i,h): the group's shared-run splits followed by the request's own.
+// of row (i,h): the pieces of its group's shared run, then the pieces of the
+// request's own columns.  One wave per row; the wave is cut into SLOTS groups of
+// D/8 lanes, each group takes every SLOTS-th partial (8 floats per lane, so that a
+// group reads a whole 4*D-byte partial row in one go and several rows are in
+// flight), and the groups are folded together at the end.
 template <typename T, int D>
 __global__ __launch_bounds__(256) void merge_kernel(SweepArgs a) {
-    constexpr int NE = (D + 63) / 64;
+    constexpr int LPR = D / 8;           // lanes per partial row
+    constexpr int SLOTS = 64 / LPR;
     const int lane = threadIdx.x & 63;
     const int rowid = blockIdx.x * 4 + (threadIdx.x >> 6);
     int* hdr = reinterpret_cast<int*>(a.ws);
-    if (blockIdx.x == 0 && threadIdx.x == 0) hdr[H_QUEUE] = 0;   // ready for a plan-reusing call
     if (rowid >= a.B * a.Hq) return;
-    const int i = rowid / a.Hq, h = rowid % a.Hq;
-    const int g = h / a.G, hh = h % a.G;
+    const int i = rowid / a.Hq, h = rowid - i * a.Hq;
+    const int g = h / a.G, hh = h - g * a.G;
     const ReqDesc rd = reinterpret_cast<const ReqDesc*>(a.ws + a.lay.req)[i];
+    const SegDesc pd = reinterpret_cast<const SegDesc*>(a.ws + a.lay.segs)[(size_t)i * a.Hkv + g];
     const float2* ml = reinterpret_cast<const float2*>(a.ws + a.lay.ml);
     const float* pacc = reinterpret_cast<const float*>(a.ws + a.lay.acc);
     T* out = static_cast<T*>(a.out) + (size_t)rowid * D;
+    const int c = lane % LPR, slot = lane / LPR;
 
     if (hdr[H_OVERFLOW]) {   // the plan did not fit its buffers: make it loud
         for (int e = lane; e < D; e += 64) Elem<T>::store(out + e, __uint_as_float(0x7FC00000u));
         return;
     }
-    // partials of the row: the pieces of its group's shared-run segment, then the
-    // pieces of its own private segment
-    const SegDesc* segs = reinterpret_cast<const SegDesc*>(a.ws + a.lay.segs);
-    int ns_sh = 0, sh_base = 0, sh_stride = 0;
-    if (rd.group >= 0) {
-        const GroupDesc gd = reinterpret_cast<const GroupDesc*>(a.ws + a.lay.grp)[rd.group];
-        const int tau = rd.rank / a.mpt;
-        const SegDesc sd = segs[(size_t)a.B * a.Hkv + gd.seg_base + g * gd.tiles + tau];
-        ns_sh = sd.npieces;
-        sh_stride = min(a.mpt, gd.members - tau * a.mpt) * a.G;
-        sh_base = sd.pbase + (rd.rank - tau * a.mpt) * a.G + hh;
-    }
-    const SegDesc pd = segs[(size_t)i * a.Hkv + g];
-    const int ns_pr = pd.npieces;
-    const int pr_base = pd.pbase + hh;
-    const int ns = ns_sh + ns_pr;
-    auto prow = [&](int s) { return s < ns_sh ? sh_base + s * sh_stride : pr_base + (s - ns_sh) * a.G; };
+    const int ns_sh = rd.ns_sh, ns = ns_sh + pd.npieces;
+    const int sh_base = rd.sh_base0 + g * rd.sh_gstride + hh, pr_base = pd.pbase + hh;
+    auto prow = [&](int s) { return s < ns_sh ? sh_base + s * rd.sh_pstride : pr_base + (s - ns_sh) * a.G; };
 
+    // reference exponent: the largest m over all partials (lanes over partials)
     float M = -INFINITY;
-    for (int s = 0; s < ns; ++s) M = fmaxf(M, ml[prow(s)].x);
-    float num[NE];
+    for (int s = lane; s < ns; s += 64) M = fmaxf(M, ml[prow(s)].x);
 #pragma unroll
-    for (int k = 0; k < NE; ++k) num[k] = 0.f;
+    for (int o = 32; o >= 1; o >>= 1) M = fmaxf(M, __shfl_xor(M, o));
+
+    float num[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) num[k] = 0.f;
     float den = 0.f;
-    for (int s = 0; s < ns; ++s) {
-        const int pr = prow(s);
-        const float2 v = ml[pr];
-        const float w = exp2f(v.x - M);
-        den = fmaf(w, v.y, den);
+    for (int s0 = 0; s0 < ns; s0 += 2 * SLOTS) {   // two partial rows per lane group in flight
+        float4 x[2][2];
+        float2 v[2];
+        bool on[2];
 #pragma unroll
-        for (int k = 0; k < NE; ++k) {
-            const int e = lane + 64 * k;
-            if (e < D) num[k] = fmaf(w, pacc[(size_t)pr * D + e], num[k]);
+        for (int q = 0; q < 2; ++q) {
+            const int s = s0 + q * SLOTS + slot;
+            on[q] = s < ns;
+            if (on[q]) {
+                const int pr = prow(s);
+                v[q] = ml[pr];
+                const float4* src = reinterpret_cast<const float4*>(pacc + (size_t)pr * D + c * 8);
+                x[q][0] = src[0];
+                x[q][1] = src[1];
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            if (on[q]) {
+                const float w = exp2f(v[q].x - M);
+                den = fmaf(w, v[q].y, den);
+                num[0] = fmaf(w, x[q][0].x, num[0]); num[1] = fmaf(w, x[q][0].y, num[1]);
+                num[2] = fmaf(w, x[q][0].z, num[2]); num[3] = fmaf(w, x[q][0].w, num[3]);
+                num[4] = fmaf(w, x[q][1].x, num[4]); num[5] = fmaf(w, x[q][1].y, num[5]);
+                num[6] = fmaf(w, x[q][1].z, num[6]); num[7] = fmaf(w, x[q][1].w, num[7]);
+            }
         }
     }
-    const float inv = ns > 0 ? 1.f / den : 0.f;
+    // fold the lane groups (fixed order: deterministic)
 #pragma unroll
-    for (int k = 0; k < NE; ++k) {
-        const int e = lane + 64 * k;
-        if (e < D) Elem<T>::store(out + e, num[k] * inv);
+    for (int o = LPR; o < 64; o <<= 1) {
+        den += __shfl_xor(den, o);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) num[k] += __shfl_xor(num[k], o);
+    }
+    if (slot == 0) {
+        const float inv = ns > 0 ? 1.f / den : 0.f;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) Elem<T>::store(out + c * 8 + k, num[k] * inv);
     }
 }
 

@@ -23,8 +23,9 @@
 // flight costs no registers: two 16 KB stages per wave, and the fetch of tile
 // t+2 is issued as soon as tile t has been read out of its stage, which keeps
 // two tiles in flight while a tile is being computed - across item boundaries too:
-// an item's descriptor carries its first four block ids, so the last tiles of one
-// item overlap with the first fetches of the next.  Each load covers four
+// the block ids of the next item's first columns are fetched while the current
+// item runs, so its last tiles overlap with the first fetches of the next.  Each
+// load covers four
 // whole 256-byte token rows; inside a row the sixteen 16-byte chunks are placed
 // XOR-swizzled by the row number, which makes the "lane = token" reads of the K
 // operand bank-conflict free without padding (the DMA path cannot pad).  V needs
@@ -149,6 +150,11 @@ __device__ __forceinline__ void fetch_tile(const SweepArgs& a, int g, int b0, in
 struct Stream {
     int phase;
     int iss;
+    // Block ids travel through three 64-column windows in LDS: even and odd windows of
+    // the current item, and the first window of the next item (which becomes the even
+    // window when the items switch).
+    int cb0, cb1, cbn;
+    bool cols_ready;   // the current item's first window was fetched while its predecessor ran
 };
 
 template <int NT>
@@ -162,44 +168,43 @@ __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item,
     const int next_pre = has_next ? min(2, (next.c1 - next.c0 + 1) >> 1) : 0;   // tiles of the next item we may fetch
 
     // Block ids of the item's columns travel through LDS as well, 64 columns per
-    // window, two windows: the compiler then sees no pending vector-memory load
-    // inside the tile loop (it would drain the whole prefetch queue for it).
+    // window: the compiler then sees no pending vector-memory load inside the tile
+    // loop (it would drain the whole prefetch queue for it).
     const int32_t* trow = a.bt + (size_t)item.who * a.stride;
-    const int last_col = item.c1 - 1;
-    auto fetch_cols = [&](int win) {   // clamped: never reads a dead table entry
-        dma4(sgpr(trow), (uint32_t)min(item.c0 + 64 * win + lane, last_col) * 4u, sgpr(cols_base + (win & 1) * 256));
+    const int32_t* nrow = a.bt + (size_t)next.who * a.stride;
+    auto fetch_cols = [&](const int32_t* row, int c0, int c1, int win, int buf) {   // clamped: never reads a dead entry
+        dma4(sgpr(row), (uint32_t)min(c0 + 64 * win + lane, c1 - 1) * 4u, sgpr(cols_base + buf * 256));
     };
+    auto buf_of = [&](int win) { return (win & 1) ? sm.cb1 : sm.cb0; };
     // Issue stream tile `idx` (own tile idx, or tile idx - ntiles of the next item) if it
     // is the next one due and exists; own tiles must be asked for in increasing order.
     auto issue = [&](int idx) {
         if (idx != sm.iss) return;
-        int b0, b1;
+        const int* sc;
         int g = item.g;
         if (idx < ntiles) {
-            if (idx < 2) {
-                b0 = idx == 0 ? item.fb[0] : item.fb[2];
-                b1 = idx == 0 ? item.fb[1] : item.fb[3];
-            } else {
-                const int w = idx & 31, win = idx >> 5;
-                if (w == 0) fetch_cols(win + 1);   // window `win` itself was fetched 32 tiles ago
-                const int* sc = s_cols + (win & 1) * 64 + 2 * w;
-                b0 = __builtin_amdgcn_readfirstlane(sc[0]);
-                b1 = __builtin_amdgcn_readfirstlane(sc[1]);
-            }
+            const int w = idx & 31, win = idx >> 5;
+            if (w == 0 && idx > 0) fetch_cols(trow, item.c0, item.c1, win + 1, buf_of(win + 1));   // `win` came 32 tiles ago
+            sc = s_cols + buf_of(win) * 64 + 2 * w;
         } else {
             const int j = idx - ntiles;
             if (j >= next_pre) return;
-            b0 = j == 0 ? next.fb[0] : next.fb[2];
-            b1 = j == 0 ? next.fb[1] : next.fb[3];
+            sc = s_cols + sm.cbn * 64 + 2 * j;
             g = next.g;
         }
+        const int b0 = __builtin_amdgcn_readfirstlane(sc[0]);
+        const int b1 = __builtin_amdgcn_readfirstlane(sc[1]);
         fetch_tile(a, g, b0, b1, lds_base + ((sm.phase + idx) & 1) * kStageBytes, L);
         sm.iss = idx + 1;
     };
-    fetch_cols(0);
-    fetch_cols(1);
+    if (!sm.cols_ready) fetch_cols(trow, item.c0, item.c1, 0, sm.cb0);
+    fetch_cols(trow, item.c0, item.c1, 1, sm.cb1);
+    if (has_next) fetch_cols(nrow, next.c0, next.c1, 0, sm.cbn);
+    if (!sm.cols_ready) wait_vmcnt<0>();   // start of a share: the block ids must be there before tiles can be asked for
+    // Own tiles only at this point: the next item's column window has just been asked
+    // for and is not readable before the drain below.
     issue(0);
-    issue(1);
+    if (ntiles > 1) issue(1);
 
     // B operand of the first product: Q^T, lane (n, kg) holds q[row n][32 ks + 8 kg .. +8]
     bf16x8 qB[NT][4];
@@ -208,7 +213,7 @@ __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item,
         const int row = nt * 16 + n;
         const bool ok = row < item.nrows;
         const int mem = row >> log2G, hh = row & ((1 << log2G) - 1);
-        const int req = ok ? mlist[mem] : 0;
+        const int req = ok ? (item.mlist_off < 0 ? item.who : mlist[mem]) : 0;
         const uint16_t* qp = Q + ((size_t)req * a.Hq + item.g * a.G + hh) * kD + kg * 8;
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
@@ -245,17 +250,23 @@ __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item,
         const char* st = s_stage + ((sm.phase + t) & 1) * kStageBytes;
         // tile t has landed once at most the 16 loads of stream tile t+1 are outstanding
         if (sm.iss > t + 1) wait_vmcnt<16>(); else wait_vmcnt<0>();
+        // Read the tile out of its stage and hand the stage back.  With 16 or 32 query
+        // rows everything is read up front so that the refill starts at once; with 64
+        // rows registers are short, so V is read after the first product (that
+        // instantiation computes long enough per tile for the later refill not to matter).
         bf16x8 kA[2][4];
         u32x4 vr[8];
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
+        for (int mt = 0; mt < (NT < 4 ? 2 : 1); ++mt)
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) kA[mt][ks] = as_bf16x8(ld16(st + mt * kBlkBytes + L.k_off[ks]));
+        if constexpr (NT < 4) {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) vr[j] = ld16(st + (2 + (j >> 2)) * kBlkBytes + L.v_off[j & 3]);
-        wait_lgkmcnt0();   // the stage is read out: refill it with stream tile t+2
-        issue(t + 1);      // (only due if the look-ahead into the next item stopped short)
-        issue(t + 2);
+            for (int j = 0; j < 8; ++j) vr[j] = ld16(st + (2 + (j >> 2)) * kBlkBytes + L.v_off[j & 3]);
+            wait_lgkmcnt0();   // the stage is read out: refill it with stream tile t+2
+            issue(t + 1);      // (only due if the look-ahead into the next item stopped short)
+            issue(t + 2);
+        }
 
         const int tile_pos = (item.c0 + 2 * t) * kBlock;          // position of the tile's first token
         const bool ragged = tile_pos + kTileTok > item.tok_end;   // wave-uniform
@@ -265,12 +276,26 @@ __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item,
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) sacc[nt][0] = sacc[nt][1] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
+        for (int mt = 0; mt < 2; ++mt) {
+            if constexpr (NT == 4) {
+                if (mt == 1) {
+#pragma unroll
+                    for (int ks = 0; ks < 4; ++ks) kA[1][ks] = as_bf16x8(ld16(st + kBlkBytes + L.k_off[ks]));
+                }
+            }
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt)
                     sacc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kA[mt][ks], qB[nt][ks], sacc[nt][mt], 0, 0, 0);
+        }
+        if constexpr (NT == 4) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) vr[j] = ld16(st + (2 + (j >> 2)) * kBlkBytes + L.v_off[j & 3]);
+            wait_lgkmcnt0();
+            issue(t + 1);
+            issue(t + 2);
+        }
 
         // ---- V: zero rows past the end (they may hold anything), then 8x8 transposes of 16-bit values
         if (ragged) {
@@ -355,11 +380,16 @@ __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item,
     }
     sm.phase = (sm.phase + ntiles) & 1;
     sm.iss -= ntiles;
+    const int old0 = sm.cb0;
+    sm.cb0 = sm.cbn;   // the next item's first window is already there
+    sm.cbn = sm.cb1;
+    sm.cb1 = old0;
+    sm.cols_ready = has_next;
 }
 
 __global__ __launch_bounds__(64) void sweep_mfma_kernel(SweepArgs a, int log2G, int xcd_aware) {
     __shared__ __attribute__((aligned(1024))) char s_stage[kStages * kStageBytes];
-    __shared__ __attribute__((aligned(256))) int s_cols[2 * 64];
+    __shared__ __attribute__((aligned(256))) int s_cols[3 * 64];
     const int lane = threadIdx.x;
     int* hdr = reinterpret_cast<int*>(a.ws);
     const Item* items = reinterpret_cast<const Item*>(a.ws + a.lay.items);
@@ -381,15 +411,15 @@ __global__ __launch_bounds__(64) void sweep_mfma_kernel(SweepArgs a, int log2G, 
         L.v_off[i] = vrow * 256 + ((L.n ^ vrow) & 15) * 16;    // chunk n of that row
     }
 
-    // Descriptors are fetched as four 16-byte words and made wave-uniform (scalar
+    // Descriptors are fetched as two 16-byte words and made wave-uniform (scalar
     // registers) before use; the fetch of the descriptor after next is left in
     // flight across a whole item.
-    struct Raw { int4 w[4]; };
+    struct Raw { int4 w[2]; };
     auto load_raw = [&](int it) {
         Raw r;
         const int4* p = reinterpret_cast<const int4*>(items + min(it, n_items - 1));
 #pragma unroll
-        for (int k = 0; k < 4; ++k) r.w[k] = p[k];
+        for (int k = 0; k < 2; ++k) r.w[k] = p[k];
         return r;
     };
     auto uniform = [&](const Raw& r) {
@@ -397,8 +427,6 @@ __global__ __launch_bounds__(64) void sweep_mfma_kernel(SweepArgs a, int log2G, 
         Item x;
         x.who = u(r.w[0].x); x.g = u(r.w[0].y); x.nrows = u(r.w[0].z); x.mlist_off = u(r.w[0].w);
         x.c0 = u(r.w[1].x); x.c1 = u(r.w[1].y); x.pbase = u(r.w[1].z); x.tok_end = u(r.w[1].w);
-        x.fb[0] = u(r.w[2].x); x.fb[1] = u(r.w[2].y); x.fb[2] = u(r.w[2].z); x.fb[3] = u(r.w[2].w);
-        x.kind = u(r.w[3].x);
         return x;
     };
 
@@ -421,6 +449,8 @@ __global__ __launch_bounds__(64) void sweep_mfma_kernel(SweepArgs a, int log2G, 
         Stream sm;
         sm.phase = 0;
         sm.iss = 0;
+        sm.cb0 = 0; sm.cb1 = 1; sm.cbn = 2;
+        sm.cols_ready = false;
         Item item = uniform(load_raw(it));
         Raw next_raw = load_raw(it + 1);
         for (;;) {

@@ -44,6 +44,13 @@ def load_library() -> C.CDLL:
     global _LIB
     if _LIB is not None:
         return _LIB
+    # PyTorch ships its own HIP runtime.  Whichever copy is mapped first serves the whole
+    # process, and device work only lines up with the caller's tensors and streams if
+    # it is PyTorch's: bring it in before libfea.so resolves its libamdhip64 dependency.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     path = library_path()
     if not os.path.exists(path):
         raise ImportError(f"{path} is missing: build it with `python -m paper_2605_06046_amd.build` "
