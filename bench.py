@@ -150,6 +150,31 @@ class Case:
             fea.fea_profile_enable(False)
         return acc / steps
 
+    def time_model_step(self, layers=32, reps=10):
+        """Mean ms per attention call when one plan serves `layers` calls (the layers of
+        one decode step share tables and lengths): 1 planning call + layers-1 reusing calls."""
+        torch, fea = self.torch, self.fea
+        sp = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+        reuse = fea.AttnParams(self.spec.num_q_heads, self.spec.num_kv_heads, self.spec.head_dim,
+                               self.params.dtype, max_group=self.params.max_group, flags=fea.FEA_FLAG_REUSE_PLAN)
+        args_reuse = [(C.byref(reuse),) + a[1:] for a in self._args]
+
+        def one_step(base):
+            self.step(base % self.R, sp)
+            for l in range(1, layers):
+                rc = self._fn(*args_reuse[(base + l) % self.R], sp)
+                if rc != 0:
+                    raise RuntimeError(fea.load_library().fea_last_error().decode())
+        one_step(0)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for r in range(reps):
+            one_step(r)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / (reps * layers)
+
     def measure(self, steps, warmup, graph=False):
         ms_cold = self.time_steps(steps, warmup, cold=True, graph=graph)
         ms_warm = self.time_steps(steps, warmup, cold=False, graph=graph)
@@ -165,12 +190,13 @@ class Case:
             "frac_hbm_peak_step": self.unique_bytes / (ms_cold * 1e-3) / 1e9 / HBM_PEAK_GBS,
             "kernel_us": {"plan": kt[0] * 1e3, "sweep": kt[1] * 1e3, "merge": kt[2] * 1e3},
             "sweep_gbs": self.unique_bytes / (kt[1] * 1e-3) / 1e9,
+            "ms_per_call_plan_shared_by_32_layers": self.time_model_step(),
             "replicas": self.R, "plan": info, "table_build_ms": self.table_build_s * 1e3,
             "table_build_tokens_per_s": len(self.wl.tokens) / self.table_build_s,
         }
 
 
-def cpu_baseline(case, budget_s=20.0):
+def cpu_baseline(case, budget_s=12.0):
     """The float64 oracle, as it stands, on the host cores: whole requests of the
     same batch until about `budget_s` seconds of work are done."""
     from oracle.attention import decode_attention
@@ -185,12 +211,13 @@ def cpu_baseline(case, budget_s=20.0):
     v = case.v[0].float().cpu().numpy()
     decode_attention(q, k, v, case.bt, case.lens, requests=[0])          # warm
     done, t0 = 0, time.perf_counter()
-    while done < case.B and time.perf_counter() - t0 < budget_s:
-        decode_attention(q, k, v, case.bt, case.lens, requests=[done])
+    while time.perf_counter() - t0 < budget_s:
+        decode_attention(q, k, v, case.bt, case.lens, requests=[done % case.B])
         done += 1
     dt = time.perf_counter() - t0
     return {"value": done / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"first {done} of {case.B} requests of {case.label} (all heads, full history), {dt:.1f} s wall"}
+            "sample": f"{done} request-steps cycling over the {case.B} requests of {case.label} "
+                      f"(all heads, full history each), {dt:.1f} s wall"}
 
 
 def traffic_from_profile(workload):
@@ -220,6 +247,8 @@ def main():
     ap.add_argument("--graph", action="store_true", help="replay the steps from a captured HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--suite", action="store_true", help="also run all shapes and the homogeneity comparisons")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="first run a plain 1 GiB device-to-device copy three times (known traffic, for counter runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
@@ -231,6 +260,13 @@ def main():
     import paper_2605_06046_amd as fea
     fea.load_library()
 
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     spec = W.CONFIGS[args.workload]
     case = Case(spec)
     m = case.measure(args.steps, args.warmup, graph=args.graph)
@@ -250,6 +286,8 @@ def main():
         "unique_kv_gbs": m["unique_kv_gbs"], "frac_hbm_peak_whole_step": m["frac_hbm_peak_step"],
         "warm": {"tokens_per_s": m["tokens_per_s_warm"], "unique_kv_gbs": m["unique_kv_gbs_warm"]},
         "kernel_us": m["kernel_us"], "plan": m["plan"],
+        "plan_shared_by_32_layers": {"ms_per_call": m["ms_per_call_plan_shared_by_32_layers"],
+                                     "tokens_per_s": case.B / (m["ms_per_call_plan_shared_by_32_layers"] * 1e-3)},
         "host_table_build": {"ms": m["table_build_ms"], "tokens_per_s": m["table_build_tokens_per_s"]},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic_from_profile(args.workload),

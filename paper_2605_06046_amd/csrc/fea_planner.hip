@@ -102,29 +102,6 @@ __device__ __forceinline__ void write_item(Item* it, int who, int g, int nrows, 
     p[1] = make_int4(c0, c1, pbase, tok_end);
 }
 
-// How a segment of `tiles` tiles that starts at stream position S is cut.
-struct Cutter {
-    int fixed;        // > 0: cut every `fixed` tiles from the segment start; 0: cut at multiples of q in the stream
-    WideDiv by_q;
-    FastDiv by_fixed;
-    __device__ Cutter(int fixed_tiles, int q) : fixed(fixed_tiles), by_q(max(q, 1)), by_fixed(max(fixed_tiles, 1)) {}
-    __device__ __forceinline__ int pieces(int S, int tiles) const {
-        if (tiles <= 0) return 0;
-        if (fixed > 0) return by_fixed.cdiv(tiles);
-        return 1 + by_q.div(S + tiles - 1) - by_q.div(S);
-    }
-    // tile range [jb, je) of piece p; k0 = by_q.div(S)
-    __device__ __forceinline__ void range(int S, int tiles, int k0, int p, int& jb, int& je) const {
-        if (fixed > 0) {
-            jb = p * fixed;
-            je = min(tiles, jb + fixed);
-        } else {
-            jb = p == 0 ? 0 : (k0 + p) * by_q.d - S;
-            je = min(tiles, (k0 + p + 1) * by_q.d - S);
-        }
-    }
-};
-
 constexpr int kGroupMax = kGroupReqMax / 2;   // a group has at least two members
 
 __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
@@ -210,7 +187,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
     for (int i = tid; i < nG; i += kPlanThreads) { u.c.run[i] = INT_MAX; u.c.cnt[i] = 0; u.c.moff[i] = 0; }
 
     // ---- longest common run of block ids with the leader's row.  All (follower,
-    // column group) pairs are spread flat over the threads, four at a time so that
+    // column group) pairs are spread flat over the threads, eight at a time so that
     // their loads are in flight together; a mismatch lowers the follower's run with
     // an LDS atomic.
     {
@@ -220,11 +197,12 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
         const int epr = cdiv(a.stride, cpe);               // elements per row
         const FastDiv by_epr(max(epr, 1));
         const int total = nflw * epr;
-        for (int e0 = tid; e0 < total; e0 += 4 * kPlanThreads) {
-            int4 xs[4], ys[4];
-            int who[4], col[4], cap[4];
+        constexpr int kBatch = 8;
+        for (int e0 = tid; e0 < total; e0 += kBatch * kPlanThreads) {
+            int4 xs[kBatch], ys[kBatch];
+            int who[kBatch], col[kBatch], cap[kBatch];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
+            for (int q = 0; q < kBatch; ++q) {
                 const int e = e0 + q * kPlanThreads;
                 who[q] = -1;
                 if (e < total) {
@@ -248,7 +226,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
                 }
             }
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
+            for (int q = 0; q < kBatch; ++q) {
                 if (who[q] >= 0) {
                     int first = INT_MAX;
                     if (xs[q].w != ys[q].w) first = col[q] + 3;
@@ -315,86 +293,130 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
     auto len_of = [&](int i) { return i < nG ? s_len[i] : clampL(a.seq_lens[i]); };
     auto priv_tiles = [&](int i) { return ((((len_of(i) + kBlock - 1) / kBlock) - run_of(i)) + 1) >> 1; };   // per KV head
 
-    // private stream: request i owns Hkv * priv_tiles(i) consecutive tiles, KV head by KV head
-    const int per = (B + kPlanThreads - 1) / kPlanThreads;
-    const int r0 = tid * per, r1 = min(B, r0 + per);
+    // private stream: request i owns Hkv * priv_tiles(i) consecutive tiles, KV head by KV
+    // head.  Its segments (request, KV head) are the entries the threads share out, so
+    // that a batch of few requests still spreads over many lanes.
+    const int NE = B * Hkv;
+    const int per = (NE + kPlanThreads - 1) / kPlanThreads;
+    const int e0 = tid * per, e1 = min(NE, e0 + per);
+    const FastDiv by_hkv(Hkv);
     int lt = 0;
-    for (int i = r0; i < r1; ++i) lt += Hkv * priv_tiles(i);
+    for (int e = e0; e < e1; ++e) lt += priv_tiles(by_hkv.div(e));
     int T_pr;
     const int tbase = block_scan_excl(lt, s_tmp, T_pr);
-    // shared side, serial over the (few) groups: units of cost, then the cut of each group
+    // shared side: wave 0 sizes the shares, lanes over the groups (float reciprocals are
+    // exact here: every dividend is a tile or share count far below 2^24)
     __shared__ int s_plan[8];
-    if (tid == 0) {
-        long long U = 4ll * T_pr;
-        int T_sh = 0;
-        for (int gi = 0; gi < n_groups; ++gi) {
+    auto idiv = [](int x, int d) {
+        int qq = (int)((float)x * (1.0f / (float)d));
+        const int r = x - qq * d;
+        if (r >= d) ++qq;
+        if (r < 0) --qq;
+        return qq;
+    };
+    if (wave == 0) {
+        auto wsum = [&](long long x) {
+#pragma unroll
+            for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o);
+            return x;
+        };
+        const int fixed_tiles = a.split_user > 0 ? a.split_user >> 1 : 0;   // split_user is even
+        long long u_loc = 0, t_loc = 0;
+        for (int gi = lane; gi < n_groups; gi += 64) {
             const int ld = w.glist[gi];
-            const int tiles_r = by_mpt.cdiv(u.c.cnt[ld]), T_seg = (u.c.run[ld] + 1) >> 1;
-            const int wgt = tile_weight(min(a.mpt, u.c.cnt[ld]) * a.G);
-            U += (long long)Hkv * tiles_r * T_seg * wgt;
-            T_sh += Hkv * tiles_r * T_seg;
+            const long long t = (long long)Hkv * by_mpt.cdiv(u.c.cnt[ld]) * ((u.c.run[ld] + 1) >> 1);
+            u_loc += t * tile_weight(min(a.mpt, u.c.cnt[ld]) * a.G);
+            t_loc += t;
         }
-        int fixed_tiles = 0, q = 1, n_sh = 0;
-        if (a.split_user > 0) fixed_tiles = a.split_user >> 1;   // split_user is even
-        const long long total_tiles = (long long)T_pr + T_sh;
+        const long long U = wsum(u_loc) + 4ll * T_pr, total_tiles = wsum(t_loc) + T_pr;
         const int n_act = (int)max(1ll, min((long long)a.tune.n_waves, total_tiles / max(a.tune.min_piece, 1)));
         // Cost per share: start from an even split and grow it until shared pieces plus
         // private shares fit the waves (rounding pieces up to whole tiles and whole
         // segments can push the count over; a wave with two shares would be the tail).
-        long long Q = max(4ll, (U + n_act - 1) / n_act);
+        int Q = (int)min(1ll << 23, max(4ll, (U + n_act - 1) / n_act));
+        int q = 1, n_sh = 0;
         for (int round = 0; round < 4; ++round) {
-            n_sh = 0;
-            int seg_acc = 0;
-            for (int gi = 0; gi < n_groups; ++gi) {
+            int loc = 0;
+            for (int gi = lane; gi < n_groups; gi += 64) {
                 const int ld = w.glist[gi];
-                const int tiles_r = by_mpt.cdiv(u.c.cnt[ld]), T_seg = (u.c.run[ld] + 1) >> 1;
-                const int wgt = tile_weight(min(a.mpt, u.c.cnt[ld]) * a.G);
-                const int want = fixed_tiles > 0 ? fixed_tiles : (int)max(1ll, Q / wgt);   // tiles per piece
-                const int n_pc = (T_seg + want - 1) / want;
+                const int T_seg = (u.c.run[ld] + 1) >> 1;
+                const int want = fixed_tiles > 0 ? fixed_tiles : max(1, idiv(Q, tile_weight(min(a.mpt, u.c.cnt[ld]) * a.G)));
+                const int n_pc = idiv(T_seg + want - 1, want);
                 v.g.npc[gi] = n_pc;
-                v.g.ibase[gi] = n_sh;                       // its items are shares n_sh ..
-                u.c.gseg[gi] = seg_acc;
-                n_sh += Hkv * tiles_r * n_pc;
-                seg_acc += Hkv * tiles_r;
+                loc += Hkv * by_mpt.cdiv(u.c.cnt[ld]) * n_pc;
             }
+            n_sh = (int)wsum(loc);
             if (fixed_tiles > 0) break;
-            // private shares at the same cost
-            const long long n_pr = max(1ll, (4ll * T_pr + Q - 1) / Q);
-            q = (int)max(1ll, (T_pr + n_pr - 1) / n_pr);
-            const long long shares = n_sh + (T_pr + q - 1) / q;
+            const int n_pr = max(1, (int)((4ll * T_pr + Q - 1) / Q));
+            q = max(1, idiv(T_pr + n_pr - 1, n_pr));
+            const int shares = n_sh + idiv(T_pr + q - 1, q);
             if (shares <= n_act) break;
-            Q = (Q * shares + n_act - 1) / n_act + 1;
+            Q = (int)min(1ll << 23, ((long long)Q * shares + n_act - 1) / n_act + 1);
         }
-        s_plan[0] = fixed_tiles;
-        s_plan[1] = q;
-        s_plan[2] = n_sh;
+        // bases of the groups in list order: shares/items, segments, partial rows
+        int ib = 0, sb = 0, rb = 0;
+        for (int g0 = 0; g0 < n_groups; g0 += 64) {
+            const int gi = g0 + lane;
+            int ni = 0, nsg = 0, nr = 0;
+            if (gi < n_groups) {
+                const int ld = w.glist[gi];
+                nsg = Hkv * by_mpt.cdiv(u.c.cnt[ld]);
+                ni = nsg * v.g.npc[gi];
+                nr = Hkv * v.g.npc[gi] * u.c.cnt[ld] * a.G;
+            }
+            int ti, ts, tr;
+            const int xi = wave_scan_excl(ni, lane, ti), xs = wave_scan_excl(nsg, lane, ts), xr = wave_scan_excl(nr, lane, tr);
+            if (gi < n_groups) {
+                v.g.ibase[gi] = ib + xi;
+                u.c.gseg[gi] = sb + xs;
+                v.g.rbase[gi] = rb + xr;
+            }
+            ib += ti; sb += ts; rb += tr;
+        }
+        if (lane == 0) {
+            s_plan[0] = fixed_tiles;
+            s_plan[1] = q;
+            s_plan[2] = n_sh;
+            s_plan[3] = rb;
+        }
     }
     __syncthreads();
-    const int fixed_tiles = s_plan[0], q = s_plan[1], n_sh = s_plan[2];
-    const Cutter cut(fixed_tiles, q);
+    const int fixed_tiles = s_plan[0], q = s_plan[1], n_sh = s_plan[2], rows_sh = s_plan[3];
 
-    // partial-row bases of the groups (serial again: few groups) - items are counted in n_sh
-    if (tid == 0) {
-        int rb = 0;
-        for (int gi = 0; gi < n_groups; ++gi) {
-            v.g.rbase[gi] = rb;
-            rb += Hkv * v.g.npc[gi] * u.c.cnt[w.glist[gi]] * a.G;
+    // Cutting one segment of T_seg tiles into pieces, walking along the stream: `rem`
+    // tiles of share `k` are used up at the segment's start.  Calls f(jb, je,
+    // starts_share, k) for every piece, in order, and moves (k, rem) to the segment's end.
+    auto for_pieces = [&](int T_seg, int& k, int& rem, auto&& f) {
+        int jb = 0;
+        while (jb < T_seg) {
+            int take;
+            bool starts = false;
+            if (fixed_tiles > 0) {
+                take = min(T_seg - jb, fixed_tiles);
+            } else {
+                take = min(T_seg - jb, q - rem);
+                starts = rem == 0;
+            }
+            f(jb, jb + take, starts, k);
+            jb += take;
+            if (fixed_tiles == 0) {
+                rem += take;
+                if (rem == q) { rem = 0; ++k; }
+            }
         }
-        s_plan[3] = rb;
-    }
-    // ---- item and partial-row counts of the requests, scanned in stream order
+    };
+    const WideDiv by_q(max(q, 1));
+    const int k_start = by_q.div(tbase), rem_start = tbase - k_start * q;
+
+    // ---- item counts of the thread's segments, scanned in stream order
     int li = 0;
     {
-        int tb = tbase;
-        for (int i = r0; i < r1; ++i) {
-            const int T_seg = priv_tiles(i);
-            for (int g = 0; g < Hkv; ++g) li += cut.pieces(tb + g * T_seg, T_seg);
-            tb += Hkv * T_seg;
-        }
+        int k = k_start, rem = rem_start;
+        for (int e = e0; e < e1; ++e)
+            for_pieces(priv_tiles(by_hkv.div(e)), k, rem, [&](int, int, bool, int) { ++li; });
     }
     int priv_items;
-    const int ibase = n_sh + block_scan_excl(li, s_tmp, priv_items);   // (the scan's barriers publish s_plan[3])
-    const int rows_sh = s_plan[3];
+    const int ibase = n_sh + block_scan_excl(li, s_tmp, priv_items);
     const int total_items = n_sh + priv_items, total_rows = rows_sh + priv_items * a.G;
     const bool overflow = total_items > a.lay.max_items || total_rows > a.lay.max_rows;
 
@@ -411,37 +433,34 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
     }
     __syncthreads();   // defaults of wave_first[] are in place before pieces overwrite their entries
 
-    // ---- descriptors and items of the requests
+    // ---- descriptors and items of the requests' own columns
     {
-        int tb = tbase, idx = ibase;
-        for (int i = r0; i < r1; ++i) {
+        int k = k_start, rem = rem_start, idx = ibase;
+        for (int e = e0; e < e1; ++e) {
+            const int i = by_hkv.div(e), g = e - i * Hkv;
             const int L = len_of(i), nb = (L + kBlock - 1) / kBlock, c0 = run_of(i);
-            const int T_seg = priv_tiles(i);
-            ReqDesc rd;
-            rd.ns_sh = rd.sh_base0 = rd.sh_gstride = rd.sh_pstride = 0;   // a group fills these in below
-            rd.nb = nb;
-            rd.L = L;
-            rd.group = c0 > 0 ? (int)s_lead[i] : -1;
-            rd.priv_c0 = c0;
-            req[i] = rd;
-            for (int g = 0; g < Hkv; ++g) {
-                const int S = tb + g * T_seg;
-                const int np = overflow ? 0 : cut.pieces(S, T_seg);
-                SegDesc sd;
-                sd.pbase = rows_sh + (idx - n_sh) * a.G;
-                sd.npieces = np;
-                segs[(size_t)i * Hkv + g] = sd;
-                const int k0 = cut.by_q.div(S);
-                for (int p = 0; p < np; ++p) {
-                    int jb, je;
-                    cut.range(S, T_seg, k0, p, jb, je);
+            if (g == 0) {
+                ReqDesc rd;
+                rd.ns_sh = rd.sh_base0 = rd.sh_gstride = rd.sh_pstride = 0;   // a group fills these in below
+                rd.nb = nb;
+                rd.L = L;
+                rd.group = c0 > 0 ? (int)s_lead[i] : -1;
+                rd.priv_c0 = c0;
+                req[i] = rd;
+            }
+            const int seg_first = idx;
+            if (!overflow) {
+                for_pieces(((nb - c0) + 1) >> 1, k, rem, [&](int jb, int je, bool starts, int kk) {
                     const int cs = c0 + 2 * jb, ce = min(nb, c0 + 2 * je);
                     write_item(&items[idx], i, g, a.G, -1, cs, ce, rows_sh + (idx - n_sh) * a.G, min(L, ce * kBlock));
-                    if (fixed_tiles == 0 && (p > 0 || S == k0 * q)) wave_first[n_sh + k0 + p] = idx;
+                    if (starts) wave_first[n_sh + kk] = idx;
                     ++idx;
-                }
+                });
             }
-            tb += Hkv * T_seg;
+            SegDesc sd;
+            sd.pbase = rows_sh + (seg_first - n_sh) * a.G;
+            sd.npieces = idx - seg_first;
+            segs[e] = sd;
         }
     }
     // member lists of the groups (the rank lives with the thread that drew it)

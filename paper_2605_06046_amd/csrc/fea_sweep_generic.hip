@@ -26,6 +26,10 @@ template <> struct Elem<float> {
         f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
     }
     __device__ static void store(float* p, float v) { *p = v; }
+    __device__ static void store8(float* p, const float (&v)[8]) {   // p is 32-byte aligned
+        reinterpret_cast<float4*>(p)[0] = make_float4(v[0], v[1], v[2], v[3]);
+        reinterpret_cast<float4*>(p)[1] = make_float4(v[4], v[5], v[6], v[7]);
+    }
 };
 struct bf16_t { uint16_t bits; };
 template <> struct Elem<bf16_t> {
@@ -44,6 +48,17 @@ template <> struct Elem<bf16_t> {
         if ((u & 0x7FFFFFFFu) > 0x7F800000u) { p->bits = 0x7FC0; return; }
         u += 0x7FFFu + ((u >> 16) & 1u);
         p->bits = (uint16_t)(u >> 16);
+    }
+    __device__ static void store8(bf16_t* p, const float (&v)[8]) {   // p is 16-byte aligned: one store
+        bf16_t h[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) store(&h[k], v[k]);
+        uint4 w;
+        w.x = h[0].bits | ((uint32_t)h[1].bits << 16);
+        w.y = h[2].bits | ((uint32_t)h[3].bits << 16);
+        w.z = h[4].bits | ((uint32_t)h[5].bits << 16);
+        w.w = h[6].bits | ((uint32_t)h[7].bits << 16);
+        *reinterpret_cast<uint4*>(p) = w;
     }
 };
 
@@ -280,7 +295,8 @@ __global__ __launch_bounds__(256) void merge_kernel(SweepArgs a) {
     if (slot == 0) {
         const float inv = ns > 0 ? 1.f / den : 0.f;
 #pragma unroll
-        for (int k = 0; k < 8; ++k) Elem<T>::store(out + c * 8 + k, num[k] * inv);
+        for (int k = 0; k < 8; ++k) num[k] *= inv;
+        Elem<T>::store8(out + c * 8, num);
     }
 }
 
