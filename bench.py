@@ -136,19 +136,20 @@ class Case:
         return e0.elapsed_time(e1) / steps
 
     def kernel_times(self, steps, cold=True):
-        """Average (plan, sweep, merge) durations in ms from HIP events around each launch."""
+        """Average (plan, sweep, merge) durations in ms over `steps` back-to-back calls (no
+        host sync between), from HIP events attached to each dispatch on the launch stream."""
         torch, fea = self.torch, self.fea
         R = self.R if cold else 1
         sp = C.c_void_p(torch.cuda.current_stream().cuda_stream)
-        fea.fea_profile_enable(True)
-        acc = np.zeros(3)
+        for s in range(4):
+            self.step(s % R, sp)
+        fea.fea_profile_enable(steps, -1)
         try:
             for s in range(steps):
                 self.step(s % R, sp)
-                acc += np.array(fea.fea_profile_last())
+            return np.mean([fea.fea_profile_read(s) for s in range(steps)], axis=0)
         finally:
-            fea.fea_profile_enable(False)
-        return acc / steps
+            fea.fea_profile_enable(0, -1)
 
     def time_model_step(self, layers=32, reps=10):
         """Mean ms per attention call when one plan serves `layers` calls (the layers of
@@ -178,7 +179,7 @@ class Case:
     def measure(self, steps, warmup, graph=False):
         ms_cold = self.time_steps(steps, warmup, cold=True, graph=graph)
         ms_warm = self.time_steps(steps, warmup, cold=False, graph=graph)
-        kt = self.kernel_times(min(steps, 50))
+        kt = self.kernel_times(min(steps, 200))
         info = self.fea.fea_decode_plan_info(self.ws)
         return {
             "workload": self.label, "B": self.B, "ms_per_step": ms_cold, "ms_per_step_warm": ms_warm,

@@ -204,16 +204,20 @@ int32_t fea_decode_attention(const fea_attn_params* p,
 int32_t fea_decode_plan_info(const void* workspace /* DEVICE */, void* hip_stream,
                              int32_t* info /* HOST [8] */);
 
-/* Per-kernel timing for measurement runs.  While enabled, fea_decode_attention
- * records library-owned HIP events on the caller's stream before and after each
- * of its three launches (alias detection, KV sweep, merge).  fea_profile_last
- * waits for the most recent call to finish and returns the three durations in
- * milliseconds (HOST float[3]); with FEA_FLAG_REUSE_PLAN the first is ~0.
- * Process-wide, not thread-safe; leave it off in production.
- * Errors: FEA_EHIP if events cannot be created or read; FEA_EINVAL for NULL or
- * when profiling was never enabled. */
-int32_t fea_profile_enable(int32_t on);
-int32_t fea_profile_last(float* ms);
+/* Per-kernel timing for measurement runs.  fea_profile_enable(n, which) with n > 0
+ * makes the next fea_decode_attention calls attach a pair of library-owned HIP events
+ * to their launches; each pair takes the begin and end time of that one dispatch (no
+ * extra packets on the stream, no synchronisation).  The events of the most recent n
+ * calls are kept.  which = 0, 1 or 2 times only the alias detection, the KV sweep or
+ * the merge; which = -1 times all three.  fea_profile_read(c, ms) waits for the c-th
+ * call since enabling (0-based) and returns the durations in milliseconds (HOST
+ * float[3], zero where not timed, e.g. the first under FEA_FLAG_REUSE_PLAN).
+ * fea_profile_enable(0, -1) switches recording off.  Process-wide, not thread-safe;
+ * leave it off in production.
+ * Errors: FEA_EHIP if events cannot be created or read; FEA_EINVAL for NULL, bad
+ * arguments, or a call that was not recorded. */
+int32_t fea_profile_enable(int32_t max_calls, int32_t which);
+int32_t fea_profile_read(int32_t call, float* ms);
 
 #ifdef __cplusplus
 }

@@ -6,6 +6,7 @@
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
+#include <vector>
 
 #include "../../include/fea.h"
 #include "fea_internal.h"
@@ -30,9 +31,14 @@ struct Resolved {
     WsLayout lay;
 };
 
-// Optional per-kernel timing: four library-owned events around the three launches.
+// Optional per-kernel timing: each launch can carry a pair of library-owned events that
+// take the start and end time of that dispatch itself (no marker packets in between).
+constexpr int kEvPerCall = 6;               // (start, stop) for plan, sweep, merge
 static bool g_prof_on = false;
-static hipEvent_t g_ev[4] = {nullptr, nullptr, nullptr, nullptr};
+static std::vector<hipEvent_t> g_ev_pool;   // kEvPerCall events per recorded call
+static int g_prof_calls = 0;                // calls recorded since profiling was switched on
+static int g_prof_which = -1;               // -1: all three launches; 0, 1, 2: only that one
+static std::vector<unsigned char> g_prof_mask;   // per recorded call: bit k set if launch k was timed
 
 static int cu_count() {
     static int n = 0;
@@ -142,6 +148,21 @@ int32_t fea_decode_attention(const fea_attn_params* p, const void* q, const void
         return fail(FEA_ERANGE, "fea_decode_attention: workspace has %zu bytes, %zu needed", workspace_bytes, r.lay.total);
 
     const float scale = p->scale > 0.f ? p->scale : 1.0f / std::sqrt((float)p->head_dim);
+    Launch where[3] = {{hip_stream, nullptr, nullptr}, {hip_stream, nullptr, nullptr}, {hip_stream, nullptr, nullptr}};
+    if (g_prof_on && !g_ev_pool.empty()) {
+        const size_t slot = (size_t)(g_prof_calls % (int)(g_ev_pool.size() / kEvPerCall));
+        hipEvent_t* ev = &g_ev_pool[kEvPerCall * slot];
+        unsigned char mask = 0;
+        for (int k = 0; k < 3; ++k) {
+            if (g_prof_which >= 0 && g_prof_which != k) continue;
+            if (k == 0 && (p->flags & FEA_FLAG_REUSE_PLAN)) continue;
+            where[k].ev_start = ev[2 * k];
+            where[k].ev_stop = ev[2 * k + 1];
+            mask |= (unsigned char)(1u << k);
+        }
+        g_prof_mask[slot] = mask;
+        ++g_prof_calls;
+    }
     if (!(p->flags & FEA_FLAG_REUSE_PLAN)) {
         PlanArgs pa;
         std::memset(&pa, 0, sizeof pa);
@@ -159,12 +180,8 @@ int32_t fea_decode_attention(const fea_attn_params* p, const void* q, const void
         pa.grouping = r.grouping;
         pa.split_user = r.split_user;
         pa.variant = r.variant;
-        if (g_prof_on) hipEventRecord(g_ev[0], static_cast<hipStream_t>(hip_stream));
-        launch_plan(pa, hip_stream);
-    } else if (g_prof_on) {
-        hipEventRecord(g_ev[0], static_cast<hipStream_t>(hip_stream));
+        launch_plan(pa, where[0]);
     }
-    if (g_prof_on) hipEventRecord(g_ev[1], static_cast<hipStream_t>(hip_stream));
     SweepArgs sa;
     std::memset(&sa, 0, sizeof sa);
     sa.q = q;
@@ -181,33 +198,45 @@ int32_t fea_decode_attention(const fea_attn_params* p, const void* q, const void
     sa.Hkv = p->num_kv_heads;
     sa.G = r.G;
     sa.mpt = r.mpt;
-    if (r.variant == 1) launch_sweep_mfma(sa, r.grid, hip_stream);
-    else launch_sweep_generic(sa, p->dtype, p->head_dim, r.grid, hip_stream);
-    if (g_prof_on) hipEventRecord(g_ev[2], static_cast<hipStream_t>(hip_stream));
-    launch_merge(sa, p->dtype, p->head_dim, hip_stream);
-    if (g_prof_on) hipEventRecord(g_ev[3], static_cast<hipStream_t>(hip_stream));
+    if (r.variant == 1) launch_sweep_mfma(sa, r.grid, where[1]);
+    else launch_sweep_generic(sa, p->dtype, p->head_dim, r.grid, where[1]);
+    launch_merge(sa, p->dtype, p->head_dim, where[2]);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(FEA_EHIP, "fea_decode_attention: launch failed: %s", hipGetErrorString(e));
     return FEA_OK;
 }
 
-int32_t fea_profile_enable(int32_t on) {
-    if (on && !g_ev[0]) {
-        for (auto& ev : g_ev) {
-            const hipError_t e = hipEventCreate(&ev);
-            if (e != hipSuccess) return fail(FEA_EHIP, "fea_profile_enable: %s", hipGetErrorString(e));
-        }
+int32_t fea_profile_enable(int32_t max_calls, int32_t which) {
+    if (max_calls < 0 || max_calls > 65536) return fail(FEA_EINVAL, "fea_profile_enable: max_calls=%d out of range", max_calls);
+    if (which < -1 || which > 2) return fail(FEA_EINVAL, "fea_profile_enable: which=%d, expected -1, 0, 1 or 2", which);
+    g_prof_which = which;
+    while ((int)g_ev_pool.size() < kEvPerCall * max_calls) {
+        hipEvent_t ev;
+        const hipError_t e = hipEventCreate(&ev);
+        if (e != hipSuccess) return fail(FEA_EHIP, "fea_profile_enable: %s", hipGetErrorString(e));
+        g_ev_pool.push_back(ev);
     }
-    g_prof_on = on != 0;
+    g_prof_mask.assign(g_ev_pool.size() / kEvPerCall, 0);
+    g_prof_on = max_calls > 0;
+    g_prof_calls = 0;
     return FEA_OK;
 }
 
-int32_t fea_profile_last(float* ms) {
-    if (!ms) return fail(FEA_EINVAL, "fea_profile_last: ms is NULL");
-    if (!g_ev[0]) return fail(FEA_EINVAL, "fea_profile_last: profiling was never enabled");
-    hipError_t e = hipEventSynchronize(g_ev[3]);
-    for (int k = 0; k < 3 && e == hipSuccess; ++k) e = hipEventElapsedTime(&ms[k], g_ev[k], g_ev[k + 1]);
-    if (e != hipSuccess) return fail(FEA_EHIP, "fea_profile_last: %s", hipGetErrorString(e));
+int32_t fea_profile_read(int32_t call, float* ms) {
+    if (!ms) return fail(FEA_EINVAL, "fea_profile_read: ms is NULL");
+    const int slots = (int)(g_ev_pool.size() / kEvPerCall);
+    if (call < 0 || call >= g_prof_calls || g_prof_calls - call > slots)
+        return fail(FEA_EINVAL, "fea_profile_read: call %d was not recorded (or its events were reused)", call);
+    const size_t slot = (size_t)(call % slots);
+    hipEvent_t* ev = &g_ev_pool[kEvPerCall * slot];
+    hipError_t e = hipSuccess;
+    for (int k = 0; k < 3; ++k) {
+        ms[k] = 0.f;
+        if (!(g_prof_mask[slot] & (1u << k)) || e != hipSuccess) continue;
+        e = hipEventSynchronize(ev[2 * k + 1]);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms[k], ev[2 * k], ev[2 * k + 1]);
+    }
+    if (e != hipSuccess) return fail(FEA_EHIP, "fea_profile_read: %s", hipGetErrorString(e));
     return FEA_OK;
 }
 

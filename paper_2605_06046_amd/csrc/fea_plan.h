@@ -111,9 +111,17 @@ struct SweepArgs {
 };
 
 // launchers (defined next to their kernels); stream is a hipStream_t
-void launch_plan(const PlanArgs& a, void* stream);
-void launch_sweep_generic(const SweepArgs& a, int dtype, int head_dim, int grid, void* stream);
-void launch_sweep_mfma(const SweepArgs& a, int grid, void* stream);
-void launch_merge(const SweepArgs& a, int dtype, int head_dim, void* stream);
+// Where a kernel goes: the caller's stream and, when its duration is wanted, a pair of
+// events (hipEvent_t, or null) that take the start and the end time of that one dispatch.
+struct Launch {
+    void* stream;
+    void* ev_start;
+    void* ev_stop;
+};
+
+void launch_plan(const PlanArgs& a, const Launch& L);
+void launch_sweep_generic(const SweepArgs& a, int dtype, int head_dim, int grid, const Launch& L);
+void launch_sweep_mfma(const SweepArgs& a, int grid, const Launch& L);
+void launch_merge(const SweepArgs& a, int dtype, int head_dim, const Launch& L);
 
 }  // namespace fea

@@ -14,6 +14,7 @@
 // adds one partial result to it.  With an explicit split size the segments are
 // cut every `split` blocks instead and the pieces dealt out in equal numbers.
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <climits>
 
@@ -538,8 +539,9 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
     }
 }
 
-void launch_plan(const PlanArgs& a, void* stream) {
-    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, static_cast<hipStream_t>(stream), a);
+void launch_plan(const PlanArgs& a, const Launch& L) {
+    hipExtLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, static_cast<hipStream_t>(L.stream),
+                          static_cast<hipEvent_t>(L.ev_start), static_cast<hipEvent_t>(L.ev_stop), 0, a);
 }
 
 }  // namespace fea

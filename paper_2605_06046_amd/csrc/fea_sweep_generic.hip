@@ -12,6 +12,7 @@
 // with s_t = (q_h . k_t) * scale * log2(e)  -- the pieces of
 // softmax(q K^T / sqrt(d)) V (Section 2.1) that the merge kernel combines.
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include "../../include/fea.h"
 #include "fea_plan.h"
@@ -301,38 +302,40 @@ __global__ __launch_bounds__(256) void merge_kernel(SweepArgs a) {
 }
 
 template <typename T>
-static void launch_generic_t(const SweepArgs& a, int head_dim, int grid, hipStream_t st) {
+static void launch_generic_t(const SweepArgs& a, int head_dim, int grid, const Launch& L) {
+    hipStream_t st = static_cast<hipStream_t>(L.stream);
+    hipEvent_t e0 = static_cast<hipEvent_t>(L.ev_start), e1 = static_cast<hipEvent_t>(L.ev_stop);
     switch (head_dim) {
-        case 32: hipLaunchKernelGGL((sweep_generic_kernel<T, 32>), dim3(grid), dim3(kGenThreads), 0, st, a); break;
-        case 64: hipLaunchKernelGGL((sweep_generic_kernel<T, 64>), dim3(grid), dim3(kGenThreads), 0, st, a); break;
-        case 128: hipLaunchKernelGGL((sweep_generic_kernel<T, 128>), dim3(grid), dim3(kGenThreads), 0, st, a); break;
-        case 256: hipLaunchKernelGGL((sweep_generic_kernel<T, 256>), dim3(grid), dim3(kGenThreads), 0, st, a); break;
+        case 32: hipExtLaunchKernelGGL((sweep_generic_kernel<T, 32>), dim3(grid), dim3(kGenThreads), 0, st, e0, e1, 0, a); break;
+        case 64: hipExtLaunchKernelGGL((sweep_generic_kernel<T, 64>), dim3(grid), dim3(kGenThreads), 0, st, e0, e1, 0, a); break;
+        case 128: hipExtLaunchKernelGGL((sweep_generic_kernel<T, 128>), dim3(grid), dim3(kGenThreads), 0, st, e0, e1, 0, a); break;
+        case 256: hipExtLaunchKernelGGL((sweep_generic_kernel<T, 256>), dim3(grid), dim3(kGenThreads), 0, st, e0, e1, 0, a); break;
         default: break;
     }
 }
 
-void launch_sweep_generic(const SweepArgs& a, int dtype, int head_dim, int grid, void* stream) {
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    if (dtype == FEA_DTYPE_F32) launch_generic_t<float>(a, head_dim, grid, st);
-    else launch_generic_t<bf16_t>(a, head_dim, grid, st);
+void launch_sweep_generic(const SweepArgs& a, int dtype, int head_dim, int grid, const Launch& L) {
+    if (dtype == FEA_DTYPE_F32) launch_generic_t<float>(a, head_dim, grid, L);
+    else launch_generic_t<bf16_t>(a, head_dim, grid, L);
 }
 
 template <typename T>
-static void launch_merge_t(const SweepArgs& a, int head_dim, hipStream_t st) {
+static void launch_merge_t(const SweepArgs& a, int head_dim, const Launch& L) {
+    hipStream_t st = static_cast<hipStream_t>(L.stream);
+    hipEvent_t e0 = static_cast<hipEvent_t>(L.ev_start), e1 = static_cast<hipEvent_t>(L.ev_stop);
     const int grid = (a.B * a.Hq + 3) / 4;
     switch (head_dim) {
-        case 32: hipLaunchKernelGGL((merge_kernel<T, 32>), dim3(grid), dim3(256), 0, st, a); break;
-        case 64: hipLaunchKernelGGL((merge_kernel<T, 64>), dim3(grid), dim3(256), 0, st, a); break;
-        case 128: hipLaunchKernelGGL((merge_kernel<T, 128>), dim3(grid), dim3(256), 0, st, a); break;
-        case 256: hipLaunchKernelGGL((merge_kernel<T, 256>), dim3(grid), dim3(256), 0, st, a); break;
+        case 32: hipExtLaunchKernelGGL((merge_kernel<T, 32>), dim3(grid), dim3(256), 0, st, e0, e1, 0, a); break;
+        case 64: hipExtLaunchKernelGGL((merge_kernel<T, 64>), dim3(grid), dim3(256), 0, st, e0, e1, 0, a); break;
+        case 128: hipExtLaunchKernelGGL((merge_kernel<T, 128>), dim3(grid), dim3(256), 0, st, e0, e1, 0, a); break;
+        case 256: hipExtLaunchKernelGGL((merge_kernel<T, 256>), dim3(grid), dim3(256), 0, st, e0, e1, 0, a); break;
         default: break;
     }
 }
 
-void launch_merge(const SweepArgs& a, int dtype, int head_dim, void* stream) {
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    if (dtype == FEA_DTYPE_F32) launch_merge_t<float>(a, head_dim, st);
-    else launch_merge_t<bf16_t>(a, head_dim, st);
+void launch_merge(const SweepArgs& a, int dtype, int head_dim, const Launch& L) {
+    if (dtype == FEA_DTYPE_F32) launch_merge_t<float>(a, head_dim, L);
+    else launch_merge_t<bf16_t>(a, head_dim, L);
 }
 
 }  // namespace fea

@@ -40,6 +40,7 @@
 // base-2 domain.  Products are bf16 x bf16 accumulated in float32; the softmax
 // weights are rounded to bf16 for the second product, the sums stay float32.
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <cstdlib>
 
@@ -467,11 +468,12 @@ __global__ __launch_bounds__(64) void sweep_mfma_kernel(SweepArgs a, int log2G, 
     }
 }
 
-void launch_sweep_mfma(const SweepArgs& a, int grid, void* stream) {
+void launch_sweep_mfma(const SweepArgs& a, int grid, const Launch& L) {
     int log2G = 0;
     while ((1 << log2G) < a.G) ++log2G;
     static const int xcd_aware = [] { const char* v = std::getenv("FEA_XCD_AWARE"); return v && *v ? std::atoi(v) : 1; }();
-    hipLaunchKernelGGL(sweep_mfma_kernel, dim3(grid), dim3(64), 0, static_cast<hipStream_t>(stream), a, log2G, xcd_aware);
+    hipExtLaunchKernelGGL(sweep_mfma_kernel, dim3(grid), dim3(64), 0, static_cast<hipStream_t>(L.stream),
+                          static_cast<hipEvent_t>(L.ev_start), static_cast<hipEvent_t>(L.ev_stop), 0, a, log2G, xcd_aware);
 }
 
 }  // namespace fea

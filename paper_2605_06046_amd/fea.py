@@ -69,8 +69,8 @@ def load_library() -> C.CDLL:
         "fea_decode_workspace_bytes": (i32, [C.POINTER(AttnParams), i32, i32, C.POINTER(C.c_size_t)]),
         "fea_decode_attention": (i32, [C.POINTER(AttnParams), vp, vp, vp, vp, i32, vp, i32, vp, vp, C.c_size_t, vp]),
         "fea_decode_plan_info": (i32, [vp, vp, vp]),
-        "fea_profile_enable": (i32, [i32]),
-        "fea_profile_last": (i32, [vp]),
+        "fea_profile_enable": (i32, [i32, i32]),
+        "fea_profile_read": (i32, [i32, vp]),
     }
     for name, (res, args) in sigs.items():
         fn = getattr(lib, name)
@@ -200,12 +200,13 @@ def fea_decode_plan_info(workspace, stream=None) -> dict:
     return dict(zip(keys, (int(x) for x in info)))
 
 
-def fea_profile_enable(on: bool) -> None:
-    _check(load_library().fea_profile_enable(1 if on else 0))
+def fea_profile_enable(max_calls: int, which: int = -1) -> None:
+    """Attach timing events to the launches of the next calls (which: -1 all, 0 plan, 1 sweep, 2 merge)."""
+    _check(load_library().fea_profile_enable(int(max_calls), int(which)))
 
 
-def fea_profile_last():
-    """(plan_ms, sweep_ms, merge_ms) of the most recent fea_decode_attention call."""
+def fea_profile_read(call: int):
+    """(plan_ms, sweep_ms, merge_ms) of the call-th fea_decode_attention since profiling was enabled."""
     ms = np.zeros(3, dtype=np.float32)
-    _check(load_library().fea_profile_last(_np_ptr(ms)))
+    _check(load_library().fea_profile_read(call, _np_ptr(ms)))
     return float(ms[0]), float(ms[1]), float(ms[2])

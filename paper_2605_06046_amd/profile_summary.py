@@ -1,0 +1,99 @@
+"""Turns raw rocprofv3 output of bench.py into the short summaries kept under profiles/.
+
+    python -m paper_2605_06046_amd.profile_summary <raw_dir> <workload> <out_dir>
+
+<raw_dir> holds, for workload W (e.g. c2), the outputs of these three commands
+(run from /tmp with TMPDIR=/tmp; bench.py by absolute path):
+
+    rocprofv3 --kernel-trace --stats -d <raw_dir>/trace_W -o t --output-format csv -- \\
+        python3 bench.py --workload W --no-cpu-baseline --steps 200 --warmup 20
+    rocprofv3 --pmc FETCH_SIZE --kernel-trace -d <raw_dir>/pmc_FETCH_SIZE_W -o p --output-format csv -- \\
+        python3 bench.py --workload W --no-cpu-baseline --steps 40 --warmup 4 --copy-calibration
+    rocprofv3 --pmc WRITE_SIZE --kernel-trace -d <raw_dir>/pmc_WRITE_SIZE_W -o p --output-format csv -- \\
+        python3 bench.py --workload W --no-cpu-baseline --steps 40 --warmup 4 --copy-calibration
+
+--copy-calibration makes bench.py start with three plain 1 GiB device-to-device
+copies; what the counters read for them fixes the scale of each counter.
+"""
+from __future__ import annotations
+
+import csv
+import glob
+import hashlib
+import json
+import os
+import sys
+
+GIB_KIB = 1 << 20   # a 1 GiB copy moves this many KiB each way
+
+
+def kernel_rev(root: str) -> str:
+    h = hashlib.sha256()
+    for f in ("fea_sweep_mfma.hip", "fea_planner.hip", "fea_plan.h"):
+        h.update(open(os.path.join(root, "paper_2605_06046_amd", "csrc", f), "rb").read())
+    return h.hexdigest()[:12]
+
+
+def _one(pattern: str) -> str:
+    hits = glob.glob(pattern, recursive=True)
+    if not hits:
+        raise SystemExit(f"nothing matches {pattern}")
+    return hits[0]
+
+
+def _counter(raw: str, name: str, wl: str):
+    rows = [r for r in csv.DictReader(open(_one(f"{raw}/pmc_{name}_{wl}/**/*counter_collection.csv")))
+            if r["Counter_Name"] == name]
+    per = {}
+    for r in rows:
+        per.setdefault(r["Kernel_Name"], []).append(float(r["Counter_Value"]))
+    copies = sorted(v for k, vs in per.items() if "copyBuffer" in k for v in vs)[-3:]
+    scale = GIB_KIB / (sum(copies) / len(copies))
+    return per, scale, copies
+
+
+def main(raw: str, wl: str, out: str) -> None:
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    os.makedirs(out, exist_ok=True)
+    stats = list(csv.DictReader(open(_one(f"{raw}/trace_{wl}/**/*kernel_stats.csv"))))
+    ours = [r for r in stats if r["Name"].startswith(("fea::", "void fea::"))]
+    lines = [f"rocprofv3 --kernel-trace --stats of: python3 bench.py --workload {wl} --no-cpu-baseline --steps 200 --warmup 20",
+             "(library kernels only; durations in microseconds)", "",
+             f"{'kernel':58s} {'calls':>6s} {'avg':>9s} {'min':>9s} {'max':>9s} {'share':>7s}"]
+    for r in ours:
+        lines.append(f"{r['Name'][:58]:58s} {r['Calls']:>6s} {float(r['AverageNs']) / 1e3:9.2f} "
+                     f"{float(r['MinNs']) / 1e3:9.2f} {float(r['MaxNs']) / 1e3:9.2f} {float(r['Percentage']):6.2f}%")
+    sweep = next(r for r in ours if "sweep" in r["Name"])
+    res = {"workload": wl, "kernel": sweep["Name"], "avg_us": float(sweep["AverageNs"]) / 1e3,
+           "kernel_rev": kernel_rev(root)}
+    lines += ["", "HBM traffic of the sweep kernel per launch (rocprofv3 --pmc, one counter per run):"]
+    total = 0.0
+    for name in ("FETCH_SIZE", "WRITE_SIZE"):
+        per, scale, copies = _counter(raw, name, wl)
+        vals = next(v for k, v in per.items() if "sweep" in k)
+        mean = sum(vals) / len(vals)
+        lines.append(f"  {name}: {mean:12.1f} KiB raw over {len(vals)} launches; 1 GiB copies read "
+                     f"{[round(c, 1) for c in copies]} KiB -> scale {scale:.4f} -> {mean * scale * 1024 / 1e6:9.2f} MB")
+        res[name.lower() + "_kib_raw"] = mean
+        res[name.lower() + "_scale"] = scale
+        total += mean * scale * 1024
+        for k, v in per.items():
+            if "merge_kernel" in k or "plan_kernel" in k:
+                lines.append(f"      ({k[:40]}: {sum(v) / len(v) * scale * 1024 / 1e6:8.2f} MB per launch)")
+    res["traffic_bytes_per_launch"] = total
+    bench = json.loads(open(f"{raw}/trace_{wl}.json").read().strip().splitlines()[-1])
+    res["unique_kv_bytes"] = bench["roofline"]["bytes_per_launch"]
+    lines += [f"  total {total / 1e6:.2f} MB per launch; algorithmic (distinct live KV blocks, K and V): "
+              f"{res['unique_kv_bytes'] / 1e6:.2f} MB; ratio {total / res['unique_kv_bytes']:.3f}",
+              "", "bench.py line of the traced run (events inside bench.py, same command):",
+              f"  sweep avg {bench['kernel_us']['sweep']:.2f} us by HIP events vs {res['avg_us']:.2f} us by rocprofv3; "
+              f"roofline.achieved {bench['roofline']['achieved']:.0f} GB/s = {bench['roofline']['frac']:.3f} of 8000"]
+    open(os.path.join(out, f"sweep_mfma_{wl}_trace.txt"), "w").write("\n".join(lines) + "\n")
+    json.dump(res, open(os.path.join(out, f"sweep_mfma_{wl}_pmc.json"), "w"), indent=1)
+    print("\n".join(lines))
+
+
+if __name__ == "__main__":
+    if len(sys.argv) != 4:
+        raise SystemExit(__doc__)
+    main(*sys.argv[1:])

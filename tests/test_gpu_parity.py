@@ -178,3 +178,34 @@ def test_plan_reuse_flag_and_errors():
         fea_decode_attention(p, dq, dk, dv, dbt, dl, o1, ws[1:])          # misaligned workspace
     # B == 0 is a no-op
     fea_decode_attention(p, dq[:0], dk, dv, dbt[:0], dl[:0], o1[:0], ws)
+
+
+def test_profiling_events_bracket_each_kernel():
+    import torch
+    from paper_2605_06046_amd import (AttnParams, FEA_DTYPE_BF16, fea_decode_attention,
+                                      fea_decode_workspace_bytes, fea_profile_enable, fea_profile_read)
+    from gpu_harness import to_device
+    wl = W.generate(W.scaled(W.CONFIGS["c2"], **SMALL["c2"]))
+    bt, lens = library_tables(wl)
+    s = wl.spec
+    p = AttnParams(s.num_q_heads, s.num_kv_heads, s.head_dim, FEA_DTYPE_BF16)
+    dq, dk, dv = to_device(wl.q), to_device(wl.k_cache), to_device(wl.v_cache)
+    dbt, dl = torch.from_numpy(bt).cuda(), torch.from_numpy(lens).cuda()
+    ws = torch.empty(fea_decode_workspace_bytes(p, s.batch, bt.shape[1]), dtype=torch.uint8, device="cuda")
+    ref = torch.empty_like(dq)
+    fea_decode_attention(p, dq, dk, dv, dbt, dl, ref, ws)
+    for which in (-1, 0, 1, 2):
+        out = torch.empty_like(dq)
+        fea_profile_enable(3, which)
+        for _ in range(3):
+            fea_decode_attention(p, dq, dk, dv, dbt, dl, out, ws)
+        torch.cuda.synchronize()
+        for c in range(3):
+            ms = fea_profile_read(c)
+            for k in range(3):
+                if which in (-1, k):
+                    assert 0.0 < ms[k] < 50.0, (which, c, ms)
+                else:
+                    assert ms[k] == 0.0, (which, c, ms)
+        fea_profile_enable(0, -1)
+        assert torch.equal(out, ref)                     # measuring does not change the result
