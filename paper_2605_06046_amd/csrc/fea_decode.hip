@@ -83,7 +83,7 @@ static int32_t resolve(const fea_attn_params* p, int32_t B, int32_t stride, Reso
     r.tune.n_waves = r.grid;
     r.tune.min_piece = std::max(1, env_int("FEA_MIN_PIECE", 4));
     r.tune.min_run = std::max(1, env_int("FEA_MIN_RUN", 2));
-    r.tune.pad = 0;
+    r.tune.weights = std::min(255, std::max(4, env_int("FEA_W32", 5))) | (std::min(255, std::max(4, env_int("FEA_W64", 6))) << 8);
     const int64_t rows = (int64_t)B * p->num_q_heads;
     const int64_t segs = 2ll * B * p->num_kv_heads;          // private segments + at most as many shared ones
     const int64_t rows_per_item = std::max(kTileRows, r.mpt * r.G);

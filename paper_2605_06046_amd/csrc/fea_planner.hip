@@ -285,7 +285,8 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
     // equal pieces per segment, one piece per wave (a "share"); the private columns of
     // all requests form one stream of tiles that is cut into equal shares for the
     // remaining waves.  Both kinds of share are sized to the same cost.
-    auto tile_weight = [&](int rows) { return rows <= 16 ? 4 : (rows <= 32 ? 5 : 6); };
+    const int w32 = a.tune.weights & 255, w64 = (a.tune.weights >> 8) & 255;
+    auto tile_weight = [&](int rows) { return rows <= 16 ? 4 : (rows <= 32 ? w32 : w64); };
     auto run_of = [&](int i) {   // shared columns of request i (0 if ungrouped)
         if (i >= nG) return 0;
         const int lead = s_lead[i];

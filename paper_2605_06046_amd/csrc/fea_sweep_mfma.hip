@@ -57,6 +57,7 @@ constexpr int kTileTok = 32;            // tokens per tile (two blocks)
 constexpr int kBlkBytes = kBlock * kD * 2;      // one (block, KV head): 4096 bytes
 constexpr int kStageBytes = 4 * kBlkBytes;      // K b0 | K b1 | V b0 | V b1
 constexpr int kStages = 2;
+constexpr int kDescWindow = 8;           // item descriptors fetched into LDS at a time
 constexpr float kSlack = 24.f;           // log2 of the largest softmax weight tolerated before the reference is raised
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
@@ -117,6 +118,16 @@ __device__ __forceinline__ void scale_acc(f32x4& acc, float f) {
         : "v"(f));
     acc[0] = a0; acc[1] = a1; acc[2] = a2; acc[3] = a3;
 }
+// Stores issued by hand so that the wave can count them (see Stream): wave-uniform
+// base address in scalar registers, 32-bit byte offset per lane.
+__device__ __forceinline__ void store_f32x4(const char* base, uint32_t off, f32x4 v) {
+    asm volatile("s_nop 4\n\tglobal_store_dwordx4 %0, %1, %2" :: "v"(off), "v"(v), "s"(base) : "memory");
+}
+__device__ __forceinline__ void store_f32x2(const char* base, uint32_t off, float x, float y) {
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    const f32x2 v = {x, y};
+    asm volatile("s_nop 4\n\tglobal_store_dwordx2 %0, %1, %2" :: "v"(off), "v"(v), "s"(base) : "memory");
+}
 template <int N> __device__ __forceinline__ void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory"); }
 __device__ __forceinline__ void wait_lgkmcnt0() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 
@@ -148,6 +159,15 @@ __device__ __forceinline__ void fetch_tile(const SweepArgs& a, int g, int b0, in
 // Tile stream of one wave.  `phase` is the stage the current item's tile 0 uses,
 // `iss` counts the tiles issued so far, numbered from the current item's tile 0
 // (so it can already be 1 or 2 when the item starts: its predecessor fetched them).
+//
+// Everything the wave loads while it streams goes global -> LDS by hand-issued loads
+// the compiler does not see, and the hardware retires a wave's vector-memory
+// operations in issue order.  So the wave numbers them itself: `seq` counts the
+// loads issued, every consumer remembers the count right after "its" loads (a
+// mark), and waiting for a mark means letting at most seq - mark younger
+// operations stay outstanding; the stores of the partial rows are issued by hand
+// and counted as well.  An operation the compiler issues on its own and that is
+// not counted only makes a wait stricter.
 struct Stream {
     int phase;
     int iss;
@@ -155,13 +175,43 @@ struct Stream {
     // the current item, and the first window of the next item (which becomes the even
     // window when the items switch).
     int cb0, cb1, cbn;
-    bool cols_ready;   // the current item's first window was fetched while its predecessor ran
+    bool cols_ready;   // the current item's first window was requested while its predecessor ran
+    bool q_ready;      // so were its query rows (into the LDS query buffer)
+    uint32_t seq;      // hand-issued loads so far
+    uint32_t done;     // loads [0, done) are known to have landed
+    uint32_t tmark0, tmark1;          // mark of the tile in stage 0 / 1
+    uint32_t cmark0, cmark1, cmark2;  // marks of the three column windows
+    uint32_t qmark;                   // mark of the query buffer
 };
+
+__device__ __forceinline__ uint32_t pick3(int i, uint32_t a, uint32_t b, uint32_t c) { return i == 0 ? a : (i == 1 ? b : c); }
+
+// Wait until the load with this mark (and with it every older one) has landed.
+__device__ __forceinline__ void wait_for(Stream& sm, uint32_t mark) {
+    if ((int32_t)(mark - sm.done) <= 0) return;
+    uint32_t n = sm.seq - mark;   // younger loads: they may stay in flight
+    if (n > 50) n = 50;
+    switch (n) {                  // the wait takes its count as an immediate
+#define FEA_W(N) case N: wait_vmcnt<N>(); break;
+        FEA_W(0) FEA_W(1) FEA_W(2) FEA_W(3) FEA_W(4) FEA_W(5) FEA_W(6) FEA_W(7) FEA_W(8) FEA_W(9)
+        FEA_W(10) FEA_W(11) FEA_W(12) FEA_W(13) FEA_W(14) FEA_W(15) FEA_W(16) FEA_W(17) FEA_W(18) FEA_W(19)
+        FEA_W(20) FEA_W(21) FEA_W(22) FEA_W(23) FEA_W(24) FEA_W(25) FEA_W(26) FEA_W(27) FEA_W(28) FEA_W(29)
+        FEA_W(30) FEA_W(31) FEA_W(32) FEA_W(33) FEA_W(34) FEA_W(35) FEA_W(36) FEA_W(37) FEA_W(38) FEA_W(39)
+        FEA_W(40) FEA_W(41) FEA_W(42) FEA_W(43) FEA_W(44) FEA_W(45) FEA_W(46) FEA_W(47) FEA_W(48) FEA_W(49)
+        default: wait_vmcnt<50>(); break;
+#undef FEA_W
+    }
+    sm.done = sm.seq - n;
+}
+__device__ __forceinline__ void wait_all(Stream& sm) {
+    wait_vmcnt<0>();
+    sm.done = sm.seq;
+}
 
 template <int NT>
 __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item, const Item& next, bool has_next,
-                                           int log2G, char* s_stage, const int* s_cols, uint32_t lds_base,
-                                           uint32_t cols_base, const Lanes& L, int lane, Stream& sm) {
+                                           int log2G, char* s_stage, const int* s_cols, const char* s_q, uint32_t lds_base,
+                                           uint32_t cols_base, uint32_t q_base, const Lanes& L, int lane, Stream& sm) {
     const int n = L.n, kg = L.kg;
     const uint16_t* Q = static_cast<const uint16_t*>(a.q);
     const int* mlist = reinterpret_cast<const int*>(a.ws + a.lay.members) + item.mlist_off;
@@ -175,61 +225,102 @@ __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item,
     const int32_t* nrow = a.bt + (size_t)next.who * a.stride;
     auto fetch_cols = [&](const int32_t* row, int c0, int c1, int win, int buf) {   // clamped: never reads a dead entry
         dma4(sgpr(row), (uint32_t)min(c0 + 64 * win + lane, c1 - 1) * 4u, sgpr(cols_base + buf * 256));
+        sm.seq += 1;
+        sm.cmark0 = buf == 0 ? sm.seq : sm.cmark0;   // (value selects: the struct must stay in registers)
+        sm.cmark1 = buf == 1 ? sm.seq : sm.cmark1;
+        sm.cmark2 = buf == 2 ? sm.seq : sm.cmark2;
     };
     auto buf_of = [&](int win) { return (win & 1) ? sm.cb1 : sm.cb0; };
     // Issue stream tile `idx` (own tile idx, or tile idx - ntiles of the next item) if it
     // is the next one due and exists; own tiles must be asked for in increasing order.
     auto issue = [&](int idx) {
         if (idx != sm.iss) return;
-        const int* sc;
+        int buf, at;
         int g = item.g;
         if (idx < ntiles) {
             const int w = idx & 31, win = idx >> 5;
             if (w == 0 && idx > 0) fetch_cols(trow, item.c0, item.c1, win + 1, buf_of(win + 1));   // `win` came 32 tiles ago
-            sc = s_cols + buf_of(win) * 64 + 2 * w;
+            buf = buf_of(win);
+            at = 2 * w;
         } else {
             const int j = idx - ntiles;
             if (j >= next_pre) return;
-            sc = s_cols + sm.cbn * 64 + 2 * j;
+            buf = sm.cbn;
+            at = 2 * j;
             g = next.g;
         }
+        wait_for(sm, pick3(buf, sm.cmark0, sm.cmark1, sm.cmark2));   // the window's block ids must have landed
+        const int* sc = s_cols + buf * 64 + at;
         const int b0 = __builtin_amdgcn_readfirstlane(sc[0]);
         const int b1 = __builtin_amdgcn_readfirstlane(sc[1]);
-        fetch_tile(a, g, b0, b1, lds_base + ((sm.phase + idx) & 1) * kStageBytes, L);
+        const int stg = (sm.phase + idx) & 1;
+        fetch_tile(a, g, b0, b1, lds_base + stg * kStageBytes, L);
+        sm.seq += 16;
+        sm.tmark0 = stg == 0 ? sm.seq : sm.tmark0;
+        sm.tmark1 = stg == 1 ? sm.seq : sm.tmark1;
         sm.iss = idx + 1;
     };
     if (!sm.cols_ready) fetch_cols(trow, item.c0, item.c1, 0, sm.cb0);
     fetch_cols(trow, item.c0, item.c1, 1, sm.cb1);
     if (has_next) fetch_cols(nrow, next.c0, next.c1, 0, sm.cbn);
-    if (!sm.cols_ready) wait_vmcnt<0>();   // start of a share: the block ids must be there before tiles can be asked for
-    // Own tiles only at this point: the next item's column window has just been asked
-    // for and is not readable before the drain below.
+    // Own tiles only at this point (no-ops when the predecessor has asked for them):
+    // the next item's column window has only just been requested.
     issue(0);
     if (ntiles > 1) issue(1);
 
-    // B operand of the first product: Q^T, lane (n, kg) holds q[row n][32 ks + 8 kg .. +8]
+    // B operand of the first product: Q^T, lane (n, kg) holds q[row n][32 ks + 8 kg .. +8].
+    // The rows of a single request's query group are contiguous in q; the predecessor
+    // has then already brought them into the LDS query buffer (laid out like a K
+    // block: 16 rows, chunks swizzled by the row), and nothing has to be waited for
+    // that is younger than that.  Otherwise (first item of a share, rows gathered
+    // through a member list, more than 16 rows) they are loaded here and everything
+    // in flight is drained once.
     bf16x8 qB[NT][4];
+    bool q_from_lds = false;
+    if constexpr (NT == 1) q_from_lds = sm.q_ready;
+    if (q_from_lds) {
+        wait_for(sm, sm.qmark);
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-        const int row = nt * 16 + n;
-        const bool ok = row < item.nrows;
-        const int mem = row >> log2G, hh = row & ((1 << log2G) - 1);
-        const int req = ok ? (item.mlist_off < 0 ? item.who : mlist[mem]) : 0;
-        const uint16_t* qp = Q + ((size_t)req * a.Hq + item.g * a.G + hh) * kD + kg * 8;
+        for (int ks = 0; ks < 4; ++ks) qB[0][ks] = as_bf16x8(ld16(s_q + L.k_off[ks]));
+    } else {
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (ok) v = ld16(qp + ks * 32);
-            qB[nt][ks] = as_bf16x8(v);
+        for (int nt = 0; nt < NT; ++nt) {
+            const int row = nt * 16 + n;
+            const bool ok = row < item.nrows;
+            const int mem = row >> log2G, hh = row & ((1 << log2G) - 1);
+            const int req = ok ? (item.mlist_off < 0 ? item.who : mlist[mem]) : 0;
+            const uint16_t* qp = Q + ((size_t)req * a.Hq + item.g * a.G + hh) * kD + kg * 8;
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                u32x4 v = {0u, 0u, 0u, 0u};
+                if (ok) v = ld16(qp + ks * 32);
+                qB[nt][ks] = as_bf16x8(v);
+            }
         }
+        // Everything in flight is consumed here, before the tile loop, so that the
+        // compiler has no load of its own pending inside it.
+        wait_all(sm);
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) asm volatile("" : "+v"(qB[nt][ks]));
     }
-    // Everything the compiler knows to be in flight is consumed here, before the
-    // tile loop (this also covers the two column windows and the first tiles).
-    wait_vmcnt<0>();
+    // Bring in the next item's query rows if they are one contiguous run of at most 16.
+    const bool q_next = has_next && next.nrows <= 16 && next.mlist_off < 0;
+    if (q_next) {
+        wait_lgkmcnt0();   // the buffer has been read out
+        const char* qn = reinterpret_cast<const char*>(Q + ((size_t)next.who * a.Hq + next.g * a.G) * kD);
+        uint32_t off[4];
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) asm volatile("" : "+v"(qB[nt][ks]));
+        for (int j = 0; j < 4; ++j) {
+            const int row = 4 * j + kg;                          // row of the buffer this lane fills in load j
+            off[j] = (uint32_t)min(row, next.nrows - 1) * 256u + (uint32_t)((n ^ row) & 15) * 16u;   // rows past the end repeat the last one
+        }
+        const uint32_t qb = sgpr(q_base);
+        dma16x4(sgpr(qn), off[0], off[1], off[2], off[3], qb, qb + 1024, qb + 2048, qb + 3072);
+        sm.seq += 4;
+        sm.qmark = sm.seq;
+    }
 
     // The softmax denominator is accumulated by the matrix core as well: a V^T row
     // of ones turns the second product into sum_t p_t, taken over the same bf16-
@@ -248,9 +339,9 @@ __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item,
     }
 
     for (int t = 0; t < ntiles; ++t) {
-        const char* st = s_stage + ((sm.phase + t) & 1) * kStageBytes;
-        // tile t has landed once at most the 16 loads of stream tile t+1 are outstanding
-        if (sm.iss > t + 1) wait_vmcnt<16>(); else wait_vmcnt<0>();
+        const int stg = (sm.phase + t) & 1;
+        const char* st = s_stage + stg * kStageBytes;
+        wait_for(sm, stg == 0 ? sm.tmark0 : sm.tmark1);   // tile t has landed
         // Read the tile out of its stage and hand the stage back.  With 16 or 32 query
         // rows everything is read up front so that the refill starts at once; with 64
         // rows registers are short, so V is read after the first product (that
@@ -361,22 +452,23 @@ __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item,
     }
 
     // ---- partial rows: lane (n, kg) holds, for row 16 nt + n, dims 8 (4 kg + jj) + i: runs of 8 floats
-    float2* ml = reinterpret_cast<float2*>(a.ws + a.lay.ml);
-    float* pacc = reinterpret_cast<float*>(a.ws + a.lay.acc);
+    const char* ml = sgpr(a.ws + a.lay.ml + (size_t)item.pbase * sizeof(float2));          // the item's first partial row
+    const char* pacc = sgpr(a.ws + a.lay.acc + (size_t)item.pbase * (kD * sizeof(float)));
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
         const float l = lacc[nt][0];   // every element of the column holds the row's sum
         const int row = nt * 16 + n;
-        if (row < item.nrows) {
-            float* dst = pacc + (size_t)(item.pbase + row) * kD + kg * 32;
+        if (nt * 16 < item.nrows) {    // wave-uniform: lane 0 has a row here, so all nine stores are issued
+            if (row < item.nrows) {
+                const uint32_t dst = (uint32_t)row * (kD * 4u) + (uint32_t)kg * 128u;
 #pragma unroll
-            for (int jj = 0; jj < 4; ++jj) {
-                *reinterpret_cast<float4*>(dst + jj * 8) =
-                    make_float4(oacc[nt][0][jj], oacc[nt][1][jj], oacc[nt][2][jj], oacc[nt][3][jj]);
-                *reinterpret_cast<float4*>(dst + jj * 8 + 4) =
-                    make_float4(oacc[nt][4][jj], oacc[nt][5][jj], oacc[nt][6][jj], oacc[nt][7][jj]);
+                for (int jj = 0; jj < 4; ++jj) {
+                    store_f32x4(pacc, dst + jj * 32, f32x4{oacc[nt][0][jj], oacc[nt][1][jj], oacc[nt][2][jj], oacc[nt][3][jj]});
+                    store_f32x4(pacc, dst + jj * 32 + 16, f32x4{oacc[nt][4][jj], oacc[nt][5][jj], oacc[nt][6][jj], oacc[nt][7][jj]});
+                }
+                if (kg == 0) store_f32x2(ml, (uint32_t)row * 8u, m_run[nt], l);
             }
-            if (kg == 0) ml[item.pbase + row] = make_float2(m_run[nt], l);
+            sm.seq += 9;
         }
     }
     sm.phase = (sm.phase + ntiles) & 1;
@@ -386,11 +478,14 @@ __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item,
     sm.cbn = sm.cb1;
     sm.cb1 = old0;
     sm.cols_ready = has_next;
+    sm.q_ready = q_next;
 }
 
 __global__ __launch_bounds__(64) void sweep_mfma_kernel(SweepArgs a, int log2G, int xcd_aware) {
     __shared__ __attribute__((aligned(1024))) char s_stage[kStages * kStageBytes];
     __shared__ __attribute__((aligned(256))) int s_cols[3 * 64];
+    __shared__ __attribute__((aligned(256))) int s_desc[kDescWindow * 8];      // the next few item descriptors
+    __shared__ __attribute__((aligned(1024))) char s_q[kBlock * kD * 2];       // query rows of the next item
     const int lane = threadIdx.x;
     int* hdr = reinterpret_cast<int*>(a.ws);
     const Item* items = reinterpret_cast<const Item*>(a.ws + a.lay.items);
@@ -399,6 +494,10 @@ __global__ __launch_bounds__(64) void sweep_mfma_kernel(SweepArgs a, int log2G, 
         (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)s_stage);
     const uint32_t cols_base = __builtin_amdgcn_readfirstlane(
         (uint32_t)(uintptr_t)(__attribute__((address_space(3))) int*)s_cols);
+    const uint32_t desc_base = __builtin_amdgcn_readfirstlane(
+        (uint32_t)(uintptr_t)(__attribute__((address_space(3))) int*)s_desc);
+    const uint32_t q_base = __builtin_amdgcn_readfirstlane(
+        (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)s_q);
 
     Lanes L;
     L.n = lane & 15;
@@ -412,22 +511,20 @@ __global__ __launch_bounds__(64) void sweep_mfma_kernel(SweepArgs a, int log2G, 
         L.v_off[i] = vrow * 256 + ((L.n ^ vrow) & 15) * 16;    // chunk n of that row
     }
 
-    // Descriptors are fetched as two 16-byte words and made wave-uniform (scalar
-    // registers) before use; the fetch of the descriptor after next is left in
-    // flight across a whole item.
-    struct Raw { int4 w[2]; };
-    auto load_raw = [&](int it) {
-        Raw r;
-        const int4* p = reinterpret_cast<const int4*>(items + min(it, n_items - 1));
-#pragma unroll
-        for (int k = 0; k < 2; ++k) r.w[k] = p[k];
-        return r;
+    // Item descriptors come through LDS too, kDescWindow at a time (one load of 4
+    // bytes per lane); a descriptor is made wave-uniform (scalar registers) when it
+    // is taken out of the window.
+    auto fetch_desc = [&](int first, Stream& sm) {
+        dma4(sgpr(items), (uint32_t)min(first * 8 + lane, n_items * 8 - 1) * 4u, desc_base);
+        sm.seq += 1;
     };
-    auto uniform = [&](const Raw& r) {
+    auto read_desc = [&](int k) {
+        const int4* p = reinterpret_cast<const int4*>(s_desc + k * 8);
+        const int4 w0 = p[0], w1 = p[1];
         auto u = [](int v) { return __builtin_amdgcn_readfirstlane(v); };
         Item x;
-        x.who = u(r.w[0].x); x.g = u(r.w[0].y); x.nrows = u(r.w[0].z); x.mlist_off = u(r.w[0].w);
-        x.c0 = u(r.w[1].x); x.c1 = u(r.w[1].y); x.pbase = u(r.w[1].z); x.tok_end = u(r.w[1].w);
+        x.who = u(w0.x); x.g = u(w0.y); x.nrows = u(w0.z); x.mlist_off = u(w0.w);
+        x.c0 = u(w1.x); x.c1 = u(w1.y); x.pbase = u(w1.z); x.tok_end = u(w1.w);
         return x;
     };
 
@@ -447,20 +544,32 @@ __global__ __launch_bounds__(64) void sweep_mfma_kernel(SweepArgs a, int log2G, 
         int it = __builtin_amdgcn_readfirstlane(wave_first[share]);
         const int it_end = min(n_items, __builtin_amdgcn_readfirstlane(wave_first[share + 1]));
         if (it >= it_end) continue;
+        wait_vmcnt<0>();   // nothing of an earlier share is still on its way into LDS
+        wait_lgkmcnt0();
         Stream sm;
         sm.phase = 0;
         sm.iss = 0;
         sm.cb0 = 0; sm.cb1 = 1; sm.cbn = 2;
         sm.cols_ready = false;
-        Item item = uniform(load_raw(it));
-        Raw next_raw = load_raw(it + 1);
+        sm.q_ready = false;
+        sm.seq = sm.done = 0;
+        sm.tmark0 = sm.tmark1 = sm.cmark0 = sm.cmark1 = sm.cmark2 = sm.qmark = 0;
+        int win_first = it;
+        fetch_desc(win_first, sm);
+        wait_all(sm);
+        Item item = read_desc(0);
         for (;;) {
             const bool has_next = it + 1 < it_end;
-            const Item next = uniform(next_raw);
-            next_raw = load_raw(it + 2);
-            if (item.nrows <= 16) sweep_item<1>(a, item, next, has_next, log2G, s_stage, s_cols, lds_base, cols_base, L, lane, sm);
-            else if (item.nrows <= 32) sweep_item<2>(a, item, next, has_next, log2G, s_stage, s_cols, lds_base, cols_base, L, lane, sm);
-            else sweep_item<4>(a, item, next, has_next, log2G, s_stage, s_cols, lds_base, cols_base, L, lane, sm);
+            if (has_next && it + 1 - win_first == kDescWindow) {   // window used up: fetch the next one (drains the stream once)
+                wait_lgkmcnt0();
+                win_first = it + 1;
+                fetch_desc(win_first, sm);
+                wait_all(sm);
+            }
+            const Item next = has_next ? read_desc(it + 1 - win_first) : item;
+            if (item.nrows <= 16) sweep_item<1>(a, item, next, has_next, log2G, s_stage, s_cols, s_q, lds_base, cols_base, q_base, L, lane, sm);
+            else if (item.nrows <= 32) sweep_item<2>(a, item, next, has_next, log2G, s_stage, s_cols, s_q, lds_base, cols_base, q_base, L, lane, sm);
+            else sweep_item<4>(a, item, next, has_next, log2G, s_stage, s_cols, s_q, lds_base, cols_base, q_base, L, lane, sm);
             if (!has_next) break;
             ++it;
             item = next;
