@@ -80,21 +80,22 @@ __device__ __forceinline__ const char* sgpr(const void* p) {
 // addresses are wave-uniform and go through M0.  The scalar operands may have been
 // produced by a vector instruction (v_readfirstlane) just before; the hardware
 // wants five wait states between such a write and a memory instruction that reads
-// the register, and the compiler cannot see into this block, hence the s_nop.
+// the register, and the compiler cannot see into this block, hence the s_nop (and
+// one wait state between each write of M0 and the load that uses it).
 __device__ __forceinline__ void dma16x4(const char* base, uint32_t off0, uint32_t off1, uint32_t off2, uint32_t off3,
                                         uint32_t lds0, uint32_t lds1, uint32_t lds2, uint32_t lds3) {
     asm volatile(
         "s_nop 4\n\t"
-        "s_mov_b32 m0, %5\n\tglobal_load_lds_dwordx4 %0, %4\n\t"
-        "s_mov_b32 m0, %6\n\tglobal_load_lds_dwordx4 %1, %4\n\t"
-        "s_mov_b32 m0, %7\n\tglobal_load_lds_dwordx4 %2, %4\n\t"
-        "s_mov_b32 m0, %8\n\tglobal_load_lds_dwordx4 %3, %4"
+        "s_mov_b32 m0, %5\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %4\n\t"
+        "s_mov_b32 m0, %6\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %4\n\t"
+        "s_mov_b32 m0, %7\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %4\n\t"
+        "s_mov_b32 m0, %8\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %3, %4"
         :: "v"(off0), "v"(off1), "v"(off2), "v"(off3), "s"(base), "s"(lds0), "s"(lds1), "s"(lds2), "s"(lds3)
         : "memory", "m0");
 }
 // One load of 4 bytes per lane (block ids of 64 table columns), same conventions.
 __device__ __forceinline__ void dma4(const void* base, uint32_t lane_off, uint32_t lds_addr) {
-    asm volatile("s_nop 4\n\ts_mov_b32 m0, %2\n\tglobal_load_lds_dword %0, %1"
+    asm volatile("s_nop 4\n\ts_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
                  :: "v"(lane_off), "s"(base), "s"(lds_addr) : "memory", "m0");
 }
 // acc *= f for an accumulator tuple that lives in the accumulation registers.  Done
@@ -119,14 +120,17 @@ __device__ __forceinline__ void scale_acc(f32x4& acc, float f) {
     acc[0] = a0; acc[1] = a1; acc[2] = a2; acc[3] = a3;
 }
 // Stores issued by hand so that the wave can count them (see Stream): wave-uniform
-// base address in scalar registers, 32-bit byte offset per lane.
+// base address in scalar registers, 32-bit byte offset per lane.  The hardware reads
+// the data registers of a wide store a little after issue and does not interlock
+// against a vector instruction overwriting them meanwhile; the compiler pads its own
+// stores for that but cannot see these, hence the trailing s_nop.
 __device__ __forceinline__ void store_f32x4(const char* base, uint32_t off, f32x4 v) {
-    asm volatile("s_nop 4\n\tglobal_store_dwordx4 %0, %1, %2" :: "v"(off), "v"(v), "s"(base) : "memory");
+    asm volatile("s_nop 4\n\tglobal_store_dwordx4 %0, %1, %2\n\ts_nop 1" :: "v"(off), "v"(v), "s"(base) : "memory");
 }
 __device__ __forceinline__ void store_f32x2(const char* base, uint32_t off, float x, float y) {
     typedef float f32x2 __attribute__((ext_vector_type(2)));
     const f32x2 v = {x, y};
-    asm volatile("s_nop 4\n\tglobal_store_dwordx2 %0, %1, %2" :: "v"(off), "v"(v), "s"(base) : "memory");
+    asm volatile("s_nop 4\n\tglobal_store_dwordx2 %0, %1, %2\n\ts_nop 1" :: "v"(off), "v"(v), "s"(base) : "memory");
 }
 template <int N> __device__ __forceinline__ void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory"); }
 __device__ __forceinline__ void wait_lgkmcnt0() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
@@ -338,7 +342,15 @@ __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item,
         for (int i = 0; i < 8; ++i) oacc[nt][i] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
-    for (int t = 0; t < ntiles; ++t) {
+    // One tile in two halves.  front(t): wait for the tile, read it out of its stage
+    // (handing the stage back for the refill), S^T = K Q^T, V transposed, and the
+    // scaled scores with their per-lane maximum.  back(): weights, denominators and
+    // O^T += V^T P^T.  Between the two the reference exponents may have to be raised;
+    // that happens in a second copy of the loop, entered at most once per item.
+    float rr[NT][8];   // scores of this lane's 8 tokens per row tile (masked), before scaling
+    float tmax[NT];    // scaled maximum of those
+    bf16x8 vA[8];      // vA[i]: head dim 8*(lane%16) + i, k-slots = the lane group's 8 tokens
+    auto front = [&](int t) {
         const int stg = (sm.phase + t) & 1;
         const char* st = s_stage + stg * kStageBytes;
         wait_for(sm, stg == 0 ? sm.tmark0 : sm.tmark1);   // tile t has landed
@@ -390,14 +402,13 @@ __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item,
         }
 
         // ---- V: zero rows past the end (they may hold anything), then 8x8 transposes of 16-bit values
-        if (ragged) {
+        if (__builtin_expect(ragged, 0)) {
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const int pos = tile_pos + (j >> 2) * 16 + kg * 4 + (j & 3);
                 if (pos >= item.tok_end) vr[j] = u32x4{0u, 0u, 0u, 0u};
             }
         }
-        bf16x8 vA[8];   // vA[i]: head dim 8*(lane%16) + i, k-slots = the lane group's 8 tokens
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
@@ -407,31 +418,39 @@ __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item,
             vA[i] = as_bf16x8(o);
         }
 
-        // ---- online softmax, one query row per lane (per row tile), then O^T += V^T P^T.
-        // The running "maximum" is a reference exponent m_ref per row: weights are
-        // 2^(s - m_ref).  It is raised to the true row maximum (and l, O rescaled)
-        // only when some score exceeds it by more than kSlack, which float32 sums
-        // absorb without loss; on the first tile it is -inf, so that always happens
-        // there.  Softmax is shift-invariant, so the result is the same, and the
-        // common case costs no cross-lane traffic and no rescale of O.
+        // ---- scores, one query row per lane (per row tile)
+        bool raise = false;
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
-            float r[8];
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-                for (int jj = 0; jj < 4; ++jj) r[mt * 4 + jj] = sacc[nt][mt][jj];
-            if (ragged) {
+                for (int jj = 0; jj < 4; ++jj) rr[nt][mt * 4 + jj] = sacc[nt][mt][jj];
+            if (__builtin_expect(ragged, 0)) {
 #pragma unroll
                 for (int x = 0; x < 8; ++x) {
                     const int pos = tile_pos + (x >> 2) * 16 + kg * 4 + (x & 3);
-                    if (pos >= item.tok_end) r[x] = -INFINITY;
+                    if (pos >= item.tok_end) rr[nt][x] = -INFINITY;
                 }
             }
-            const float tmax = a.scale_log2 *
+            const float* r = rr[nt];
+            tmax[nt] = a.scale_log2 *
                 fmaxf(fmaxf(fmaxf(r[0], r[1]), fmaxf(r[2], r[3])), fmaxf(fmaxf(r[4], r[5]), fmaxf(r[6], r[7])));
-            if (__any(tmax > m_run[nt] + kSlack)) {
-                float rmax = fmaxf(tmax, __shfl_xor(tmax, 16));
+            raise = raise || tmax[nt] > m_run[nt] + kSlack;
+        }
+        return __any(raise);
+    };
+    // Online softmax.  The running "maximum" is a reference exponent m_ref per row:
+    // weights are 2^(s - m_ref).  It is raised to the true row maximum (and l, O
+    // rescaled) only when some score exceeds it by more than kSlack, which float32
+    // sums absorb without loss; on the first tile it is -inf, so that always happens
+    // there.  Softmax is shift-invariant, so the result is the same, and the common
+    // case costs no cross-lane traffic and no rescale of O.
+    auto raise_refs = [&]() {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            if (__any(tmax[nt] > m_run[nt] + kSlack)) {
+                float rmax = fmaxf(tmax[nt], __shfl_xor(tmax[nt], 16));
                 rmax = fmaxf(rmax, __shfl_xor(rmax, 32));
                 const float m_new = fmaxf(m_run[nt], rmax);
                 const float alpha = fast_exp2(m_run[nt] - m_new);
@@ -440,14 +459,45 @@ __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item,
                 for (int i = 0; i < 8; ++i) scale_acc(oacc[nt][i], alpha);
                 m_run[nt] = m_new;
             }
+        }
+    };
+    auto back = [&]() {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
             const float neg_m = -m_run[nt];
             bf16x8 pB;
 #pragma unroll
-            for (int x = 0; x < 8; ++x) pB[x] = (__bf16)fast_exp2(fmaf(r[x], a.scale_log2, neg_m));
+            for (int x = 0; x < 8; ++x) pB[x] = (__bf16)fast_exp2(fmaf(rr[nt][x], a.scale_log2, neg_m));
             lacc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pB, lacc[nt], 0, 0, 0);
 #pragma unroll
             for (int i = 0; i < 8; ++i)
                 oacc[nt][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vA[i], pB, oacc[nt][i], 0, 0, 0);
+        }
+    };
+    // First tile: the reference is its row maximum, nothing to rescale yet.
+    front(0);
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        float rmax = fmaxf(tmax[nt], __shfl_xor(tmax[nt], 16));
+        m_run[nt] = fmaxf(rmax, __shfl_xor(rmax, 32));
+    }
+    back();
+    // Fast loop: no reference is ever raised in here, the accumulators are only touched
+    // by the matrix core.  It is left for good (to the loop below) the first time a
+    // score outgrows its reference.
+    int t = 1;
+    bool need = false;
+    for (; t < ntiles; ++t) {
+        need = front(t);
+        if (__builtin_expect(need, 0)) break;
+        back();
+    }
+    if (need) {
+        for (;;) {   // tile t has been through front()
+            raise_refs();
+            back();
+            if (++t >= ntiles) break;
+            front(t);
         }
     }
 
