@@ -54,6 +54,17 @@ struct WideDiv {
     }
 };
 
+// floor(x / d) for 0 <= x < 2^52 and d >= 1 through double precision: the 64-bit
+// integer division expands to hundreds of dependent instructions, which is felt in
+// the serial stretches of a single-workgroup kernel.
+__device__ __forceinline__ long long ddiv(long long x, int d) {
+    long long q = (long long)((double)x / (double)d);
+    const long long r = x - q * d;
+    if (r >= d) ++q;
+    if (r < 0) --q;
+    return q;
+}
+
 // Exclusive prefix sum of one int per thread over the 1024-thread block.
 __device__ int block_scan_excl(int v, int* s_tmp, int& total) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -81,17 +92,6 @@ __device__ int block_scan_excl(int v, int* s_tmp, int& total) {
     total = s_tmp[31];
     __syncthreads();
     return base + x - v;
-}
-
-__device__ int wave_scan_excl(int v, int lane, int& total) {
-    int x = v;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        const int y = __shfl_up(x, o);
-        if (lane >= o) x += y;
-    }
-    total = __shfl(x, 63);
-    return x - v;
 }
 
 __device__ __forceinline__ uint32_t slot_of(int key) { return ((uint32_t)key * 2654435761u) >> 20; }  // 12 bits
@@ -317,10 +317,25 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
         return qq;
     };
     if (wave == 0) {
-        auto wsum = [&](long long x) {
-#pragma unroll
-            for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o);
-            return x;
+        // Sums and scans over the groups, one group per lane.  Cross-lane moves cost an LDS
+        // round trip each and this stretch is serial, so only as many butterfly steps are
+        // taken as the lanes that hold a group need (none for a single group).
+        int span = 1;
+        while (span < min(n_groups, 64)) span <<= 1;
+        auto wsum = [&](long long x) {   // lanes >= n_groups pass 0 (and are handed the total too)
+            for (int o = 1; o < span; o <<= 1) x += __shfl_xor(x, o);
+            const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)x);
+            const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)((unsigned long long)x >> 32));
+            return (long long)(((unsigned long long)hi << 32) | lo);
+        };
+        auto scan_excl = [&](int v, int& total) {   // the same for an exclusive prefix sum
+            int x = v;
+            for (int o = 1; o < span; o <<= 1) {
+                const int y = __shfl_up(x, o);
+                if (lane >= o) x += y;
+            }
+            total = __shfl(x, span - 1);
+            return x - v;
         };
         const int fixed_tiles = a.split_user > 0 ? a.split_user >> 1 : 0;   // split_user is even
         long long u_loc = 0, t_loc = 0;
@@ -331,11 +346,11 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
             t_loc += t;
         }
         const long long U = wsum(u_loc) + 4ll * T_pr, total_tiles = wsum(t_loc) + T_pr;
-        const int n_act = (int)max(1ll, min((long long)a.tune.n_waves, total_tiles / max(a.tune.min_piece, 1)));
+        const int n_act = (int)max(1ll, min((long long)a.tune.n_waves, ddiv(total_tiles, max(a.tune.min_piece, 1))));
         // Cost per share: start from an even split and grow it until shared pieces plus
         // private shares fit the waves (rounding pieces up to whole tiles and whole
         // segments can push the count over; a wave with two shares would be the tail).
-        int Q = (int)min(1ll << 23, max(4ll, (U + n_act - 1) / n_act));
+        int Q = (int)min(1ll << 23, max(4ll, ddiv(U + n_act - 1, n_act)));
         int q = 1, n_sh = 0;
         for (int round = 0; round < 4; ++round) {
             int loc = 0;
@@ -349,11 +364,11 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
             }
             n_sh = (int)wsum(loc);
             if (fixed_tiles > 0) break;
-            const int n_pr = max(1, (int)((4ll * T_pr + Q - 1) / Q));
+            const int n_pr = max(1, (int)ddiv(4ll * T_pr + Q - 1, Q));
             q = max(1, idiv(T_pr + n_pr - 1, n_pr));
             const int shares = n_sh + idiv(T_pr + q - 1, q);
             if (shares <= n_act) break;
-            Q = (int)min(1ll << 23, ((long long)Q * shares + n_act - 1) / n_act + 1);
+            Q = (int)min(1ll << 23, ddiv((long long)Q * shares + n_act - 1, n_act) + 1);
         }
         // bases of the groups in list order: shares/items, segments, partial rows
         int ib = 0, sb = 0, rb = 0;
@@ -367,7 +382,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
                 nr = Hkv * v.g.npc[gi] * u.c.cnt[ld] * a.G;
             }
             int ti, ts, tr;
-            const int xi = wave_scan_excl(ni, lane, ti), xs = wave_scan_excl(nsg, lane, ts), xr = wave_scan_excl(nr, lane, tr);
+            const int xi = scan_excl(ni, ti), xs = scan_excl(nsg, ts), xr = scan_excl(nr, tr);
             if (gi < n_groups) {
                 v.g.ibase[gi] = ib + xi;
                 u.c.gseg[gi] = sb + xs;
@@ -428,7 +443,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
     for (int x = tid; x <= a.lay.max_items; x += kPlanThreads) {
         int first = overflow ? 0 : total_items;
         if (!overflow) {
-            if (fixed_tiles > 0) { if (x < n_shares) first = (int)(((long long)x * total_items) / n_shares); }
+            if (fixed_tiles > 0) { if (x < n_shares) first = (int)ddiv((long long)x * total_items, n_shares); }
             else if (x <= n_sh) first = x;
         }
         if (x <= n_shares || x == a.lay.max_items) wave_first[x] = first;
@@ -471,17 +486,21 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
         if (lead >= 0 && viable(lead)) members[u.c.moff[lead] + my_rank[k]] = i;
     }
     __syncthreads();   // request descriptors and member lists are written: groups may amend them
-    // ---- descriptors and items of the groups: one wave per group, lanes over its items.
+    // ---- descriptors and items of the groups: one team of waves per group, its lanes
+    // over the group's items (the fewer groups, the bigger the teams).
     // Order: KV head, piece, row tile - the row tiles of one piece read the same KV bytes
     // and sit on neighbouring shares, which the sweep maps to one XCD.
     if (!overflow) {
-        for (int gi = wave; gi < n_groups; gi += kPlanThreads / 64) {
+        int team = kPlanThreads / 64;   // waves per team: the largest power of two with teams >= groups (at least 1)
+        while (team > 1 && (kPlanThreads / 64) / team < n_groups) team >>= 1;
+        const int lstep = team * 64, l0 = tid & (lstep - 1), n_teams = kPlanThreads / lstep;
+        for (int gi = tid / lstep; gi < n_groups; gi += n_teams) {
             const int ld = w.glist[gi];
             const int cnt = u.c.cnt[ld], run = u.c.run[ld];
             const int tiles_r = by_mpt.cdiv(cnt), T_seg = (run + 1) >> 1;
             const int n_pc = v.g.npc[gi];
             const int ps = fixed_tiles > 0 ? fixed_tiles : (T_seg + n_pc - 1) / n_pc;   // tiles per piece
-            if (lane == 0) {
+            if (l0 == 0) {
                 GroupDesc gd;
                 gd.leader = ld;
                 gd.members = cnt;
@@ -497,7 +516,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
             const int full_rows = a.mpt * a.G, last_rows = (cnt - (tiles_r - 1) * a.mpt) * a.G;
             // partial rows of segment (g, tau): pieces p = 0 .. n_pc-1, rows(tau) each; segments in (g, tau) order
             const int rows_per_head = cnt * a.G;
-            for (int k = lane; k < n; k += 64) {
+            for (int k = l0; k < n; k += lstep) {
                 const int rest = by_tr.div(k), tau = k - rest * tiles_r;
                 const int g = by_pc.div(rest), pc = rest - g * n_pc;
                 const int rows = tau == tiles_r - 1 ? last_rows : full_rows;
@@ -514,7 +533,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
             }
             // where each member finds the partials of the shared run (rank r = position in the member list)
             const FastDiv by_m(a.mpt);
-            for (int r = lane; r < cnt; r += 64) {
+            for (int r = l0; r < cnt; r += lstep) {
                 const int i = members[u.c.moff[ld] + r];
                 const int tau = by_m.div(r);
                 int4 shared;
