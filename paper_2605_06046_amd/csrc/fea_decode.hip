@@ -80,10 +80,14 @@ static int32_t resolve(const fea_attn_params* p, int32_t B, int32_t stride, Reso
     // the sweep grid the plan is cut for: one single-wave workgroup per SIMD on the
     // matrix-core path, a few workgroups per CU on the generic path
     r.grid = std::max(1, env_int("FEA_SWEEP_GRID", (r.variant == 1 ? 4 : 8) * cu_count()));
-    r.tune.n_waves = r.grid;
+    // The plan is cut for a few waves fewer than the grid has.  With every one of the
+    // 4 x CUs single-wave workgroups busy from start to end, a handful of them (the first
+    // ones dispatched) were measured to run about 1.5x longer than the rest, whatever
+    // their work; with some workgroups exiting at once this does not happen.
+    r.tune.n_waves = std::max(1, r.grid - std::min(r.grid / 2, std::max(0, env_int("FEA_SPARE_WAVES", 16))));
     r.tune.min_piece = std::max(1, env_int("FEA_MIN_PIECE", 4));
     r.tune.min_run = std::max(1, env_int("FEA_MIN_RUN", 2));
-    r.tune.weights = std::min(255, std::max(4, env_int("FEA_W32", 5))) | (std::min(255, std::max(4, env_int("FEA_W64", 6))) << 8);
+    r.tune.weights = std::min(255, std::max(16, env_int("FEA_W32", 20))) | (std::min(255, std::max(16, env_int("FEA_W64", 24))) << 8);
     const int64_t rows = (int64_t)B * p->num_q_heads;
     const int64_t segs = 2ll * B * p->num_kv_heads;          // private segments + at most as many shared ones
     const int64_t rows_per_item = std::max(kTileRows, r.mpt * r.G);

@@ -281,12 +281,12 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
     const int n_groups = s_ngroups;
 
     // ---- cost model.  A 32-token tile costs a wave more the more query rows ride on
-    // it; weights in quarter units of a one-row-tile sweep.  Shared runs are cut into
+    // it; weights in sixteenths of a 16-row tile's sweep.  Shared runs are cut into
     // equal pieces per segment, one piece per wave (a "share"); the private columns of
     // all requests form one stream of tiles that is cut into equal shares for the
     // remaining waves.  Both kinds of share are sized to the same cost.
     const int w32 = a.tune.weights & 255, w64 = (a.tune.weights >> 8) & 255;
-    auto tile_weight = [&](int rows) { return rows <= 16 ? 4 : (rows <= 32 ? w32 : w64); };
+    auto tile_weight = [&](int rows) { return rows <= 16 ? 16 : (rows <= 32 ? w32 : w64); };
     auto run_of = [&](int i) {   // shared columns of request i (0 if ungrouped)
         if (i >= nG) return 0;
         const int lead = s_lead[i];
@@ -345,12 +345,12 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
             u_loc += t * tile_weight(min(a.mpt, u.c.cnt[ld]) * a.G);
             t_loc += t;
         }
-        const long long U = wsum(u_loc) + 4ll * T_pr, total_tiles = wsum(t_loc) + T_pr;
+        const long long U = wsum(u_loc) + 16ll * T_pr, total_tiles = wsum(t_loc) + T_pr;
         const int n_act = (int)max(1ll, min((long long)a.tune.n_waves, ddiv(total_tiles, max(a.tune.min_piece, 1))));
         // Cost per share: start from an even split and grow it until shared pieces plus
         // private shares fit the waves (rounding pieces up to whole tiles and whole
         // segments can push the count over; a wave with two shares would be the tail).
-        int Q = (int)min(1ll << 23, max(4ll, ddiv(U + n_act - 1, n_act)));
+        int Q = (int)min(1ll << 25, max(16ll, ddiv(U + n_act - 1, n_act)));
         int q = 1, n_sh = 0;
         for (int round = 0; round < 4; ++round) {
             int loc = 0;
@@ -364,11 +364,11 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
             }
             n_sh = (int)wsum(loc);
             if (fixed_tiles > 0) break;
-            const int n_pr = max(1, (int)ddiv(4ll * T_pr + Q - 1, Q));
+            const int n_pr = max(1, (int)ddiv(16ll * T_pr + Q - 1, Q));
             q = max(1, idiv(T_pr + n_pr - 1, n_pr));
             const int shares = n_sh + idiv(T_pr + q - 1, q);
             if (shares <= n_act) break;
-            Q = (int)min(1ll << 23, ddiv((long long)Q * shares + n_act - 1, n_act) + 1);
+            Q = (int)min(1ll << 25, ddiv((long long)Q * shares + n_act - 1, n_act) + 1);
         }
         // bases of the groups in list order: shares/items, segments, partial rows
         int ib = 0, sb = 0, rb = 0;
