@@ -364,6 +364,64 @@ def run_suite(args):
         torch.cuda.empty_cache()
     yield {"workload": "H1_eight_homogeneous_launches_of_32", "B": B, "ms_per_step": total_ms,
            "ms_per_step_warm": total_ms_warm, "tokens_per_s": B / (total_ms * 1e-3)}
+    yield from scheduler_comparison(steps, warm, args.graph)
+
+
+def scheduler_comparison(steps, warm, graph):
+    """The 256 requests of c3 (8 prefix groups, arriving interleaved) served as batches of 32
+    chosen first-come-first-served or by the Chunked Hash Tree with the rule-based stop
+    policy: summed attention time over the 8 batches of each schedule, and the tree's
+    time per operation."""
+    import dataclasses
+    import torch
+    import paper_2605_06046_amd as fea
+    base = W.CONFIGS["c3"]
+    wl = W.generate(base, with_kv=False)
+    B = base.batch
+    reqs = [wl.request_tokens(i) for i in range(B)]
+    t_ops = {}
+    tree = fea.Cht()
+    t0 = time.perf_counter()
+    for i, r in enumerate(reqs):
+        tree.insert(i, tokens=r)
+    t_ops["insert_ns"] = (time.perf_counter() - t0) / B * 1e9
+    policy = dict(small_batch=2, loss_small=1 << 30, loss_limit=8, peers_relax=16, loss_relaxed=32)
+    cht_batches, t_build, t_finish = [], 0.0, 0.0
+    while tree.stats()["waiting"] > 0:
+        t0 = time.perf_counter()
+        ids = tree.build_batch(32, **policy)
+        t_build += time.perf_counter() - t0
+        cht_batches.append(ids)
+        t0 = time.perf_counter()
+        for rid in ids:
+            tree.finish(rid)
+        t_finish += time.perf_counter() - t0
+    t_ops["find_best_plus_add_ns"] = t_build / B * 1e9
+    t_ops["finish_ns"] = t_finish / B * 1e9
+    fcfs_batches = [list(range(b0, min(B, b0 + 32))) for b0 in range(0, B, 32)]
+
+    def sub(sel):
+        toks = np.concatenate([reqs[i] for i in sel])
+        offs = np.zeros(len(sel) + 1, dtype=np.int64)
+        offs[1:] = np.cumsum([len(reqs[i]) for i in sel])
+        return dataclasses.replace(wl, tokens=toks, tok_offsets=offs, group_of=wl.group_of[sel], q=wl.q[sel],
+                                   num_blocks=int(sum(-(-len(reqs[i]) // 16) for i in sel)))
+
+    for name, batches in (("sched_fcfs_batches_of_32", fcfs_batches), ("sched_cht_batches_of_32", cht_batches)):
+        total_ms, n, groups_per_batch = 0.0, 0, []
+        for k, sel in enumerate(batches):
+            sp = dataclasses.replace(base, name=f"{name}_{k}", batch=len(sel))
+            c = Case(sp, tokens=sub(sel), label=sp.name)
+            total_ms += c.measure(steps, warm, graph=graph)["ms_per_step"]
+            n += c.B
+            groups_per_batch.append(int(len(set(wl.group_of[sel].tolist()))))
+            del c
+            torch.cuda.empty_cache()
+        out = {"workload": name, "B": n, "batches": len(batches), "prefix_groups_per_batch": groups_per_batch,
+               "ms_per_step": total_ms, "tokens_per_s": n / (total_ms * 1e-3)}
+        if name.startswith("sched_cht"):
+            out["tree_ns_per_request"] = {k: round(v) for k, v in t_ops.items()}
+        yield out
 
 
 if __name__ == "__main__":

@@ -204,6 +204,79 @@ int32_t fea_decode_attention(const fea_attn_params* p,
 int32_t fea_decode_plan_info(const void* workspace /* DEVICE */, void* hip_stream,
                              int32_t* info /* HOST [8] */);
 
+/* ------------------------------------------------------------------------
+ * Chunked Hash Tree: which waiting requests should join the running batch
+ * (Section 4.2 "Chunked Hash Tree"; appendix "Algorithms": Insert, FindBest,
+ * AddToBatch, Finish, Remove, BuildBatch).  Host bookkeeping only; it is the
+ * step before fea_build_block_tables: the batch it forms is what gets tables.
+ *
+ * A request is its vector of cumulative chunk hashes (fea_chunk_hashes).  The
+ * tree keeps the working set {(level, hash) of every active request}, for each
+ * waiting request its missing count (hashes of it not in the working set), a
+ * min-heap of (missing count, request id) with lazy deletion, a reverse index
+ * from (level, hash) to the waiting requests carrying it, and the shared prefix
+ * tip: the deepest level at which all active requests carry the same hash
+ * (level 0 when nothing is active).  Request ids are the caller's; ties in the
+ * missing count go to the smaller id (the heap orders pairs).
+ *
+ * Readings of the paper where its text and listings differ: the first request
+ * of a batch enters the working set like any other; the tip after an addition
+ * is the least common ancestor of the active requests; Finish always drops the
+ * request from all structures.
+ *
+ * All pointers HOST.  Not thread-safe.  Errors: FEA_EINVAL (NULL, unknown id,
+ * id in the wrong state, duplicate id), FEA_ENOMEM.  On error nothing changed.
+ */
+typedef struct fea_cht fea_cht;
+
+/* chunk_tokens must be FEA_BLOCK_TOKENS (the chunk size of fea_chunk_hashes). */
+int32_t fea_cht_create(int32_t chunk_tokens, fea_cht** out);
+void    fea_cht_destroy(fea_cht* t);
+
+/* Insert: register a request as waiting, from its tokens (hashed here) or from a
+ * ready hash vector of n values. */
+int32_t fea_cht_insert(fea_cht* t, int64_t request_id, const int32_t* tokens /* [n_tokens] */, int64_t n_tokens);
+int32_t fea_cht_insert_hashes(fea_cht* t, int64_t request_id, const uint64_t* hashes /* [n] */, int32_t n);
+
+/* FindBest: the waiting request with the smallest missing count.  Also yields
+ * the tip depth now, the depth the tip would have with the request added (the
+ * deepest level, not below the tip, whose node of the request is in the working
+ * set; 0 if none), the number of waiting requests that carry the request's hash
+ * at that depth (the request included; every waiting request when that depth is
+ * 0) and its missing count; any of these four may be NULL.  Changes nothing (the
+ * answer is cached until the next mutation).  Returns FEA_OK, or 1 if no request
+ * is waiting (then nothing is written). */
+int32_t fea_cht_find_best(fea_cht* t, int64_t* request_id, int32_t* tip_before, int32_t* tip_after,
+                          int32_t* peers, int32_t* missing);
+
+/* AddToBatch / Finish / Remove: waiting -> active, active -> gone, waiting -> gone. */
+int32_t fea_cht_add_to_batch(fea_cht* t, int64_t request_id);
+int32_t fea_cht_finish(fea_cht* t, int64_t request_id);
+int32_t fea_cht_remove(fea_cht* t, int64_t request_id);
+
+/* Missing count of a waiting request; sizes and the tip (any pointer may be NULL;
+ * working_set = distinct (level, hash) nodes of the active requests, heap_entries
+ * counts stale entries too). */
+int32_t fea_cht_missing(const fea_cht* t, int64_t request_id, int32_t* missing);
+int32_t fea_cht_stats(const fea_cht* t, int64_t* n_waiting, int64_t* n_active, int32_t* tip_level,
+                      uint64_t* tip_hash, int64_t* working_set, int64_t* heap_entries);
+
+/* The rule-based stop policy of Section 4.3 ("Heuristic Policy").  With b requests
+ * in the batch so far, a candidate whose addition would shorten the tip by `loss`
+ * levels and which has `peers` waiting requests at the new depth is added if
+ * loss <= 0; else if b < small_batch: if loss <= loss_small; else if loss <=
+ * loss_limit; else if peers >= peers_relax and loss <= loss_relaxed.  The paper
+ * gives no constants: all five are the caller's. */
+typedef struct fea_stop_policy {
+    int32_t small_batch, loss_small, loss_limit, peers_relax, loss_relaxed;
+} fea_stop_policy;
+
+/* BuildBatch: FindBest / policy / AddToBatch until the policy stops, nothing is
+ * waiting, or max_batch requests were added.  ids (HOST [max_batch]) receives the
+ * added requests in order, *n_out their number.  Requests added stay added. */
+int32_t fea_cht_build_batch(fea_cht* t, const fea_stop_policy* policy, int32_t max_batch,
+                            int64_t* ids, int32_t* n_out);
+
 /* Per-kernel timing for measurement runs.  fea_profile_enable(n, which) with n > 0
  * makes the next fea_decode_attention calls attach a pair of library-owned HIP events
  * to their launches; each pair takes the begin and end time of that one dispatch (no

@@ -23,4 +23,10 @@ What pins each function (see the tests that do not need a GPU):
   and leaves Hash/InitConst open, so the *values* follow this build's written
   specification only: parity of hash values is "parity unpinned" beyond two
   independently written implementations agreeing bit for bit.
+* cht.ChunkedHashTree - the scheduler's sets and queries written out from their
+  definitions (no heap, no reverse index, no incremental state); pinned by the
+  walk-through of Section 4.2, the R1..R4 example and the four caption values of
+  the appendix on the alternative FindBest heuristic, and that appendix's
+  theorem checked on random trees.  The constants of the stop policy are free
+  parameters in the paper: policy parity is unpinned.
 """

@@ -39,6 +39,12 @@ def library_path() -> str:
     return os.environ.get("FEA_LIBRARY") or os.path.join(_HERE, "libfea.so")
 
 
+class StopPolicy(C.Structure):
+    """fea_stop_policy: the five constants of the rule-based stop policy."""
+    _fields_ = [("small_batch", C.c_int32), ("loss_small", C.c_int32), ("loss_limit", C.c_int32),
+                ("peers_relax", C.c_int32), ("loss_relaxed", C.c_int32)]
+
+
 def load_library() -> C.CDLL:
     """Loads libfea.so; raises if it has not been built (there is no fallback path)."""
     global _LIB
@@ -71,6 +77,17 @@ def load_library() -> C.CDLL:
         "fea_decode_plan_info": (i32, [vp, vp, vp]),
         "fea_profile_enable": (i32, [i32, i32]),
         "fea_profile_read": (i32, [i32, vp]),
+        "fea_cht_create": (i32, [i32, C.POINTER(vp)]),
+        "fea_cht_destroy": (None, [vp]),
+        "fea_cht_insert": (i32, [vp, i64, vp, i64]),
+        "fea_cht_insert_hashes": (i32, [vp, i64, vp, i32]),
+        "fea_cht_find_best": (i32, [vp, C.POINTER(i64), C.POINTER(i32), C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)]),
+        "fea_cht_add_to_batch": (i32, [vp, i64]),
+        "fea_cht_finish": (i32, [vp, i64]),
+        "fea_cht_remove": (i32, [vp, i64]),
+        "fea_cht_missing": (i32, [vp, i64, C.POINTER(i32)]),
+        "fea_cht_stats": (i32, [vp, C.POINTER(i64), C.POINTER(i64), C.POINTER(i32), C.POINTER(u64), C.POINTER(i64), C.POINTER(i64)]),
+        "fea_cht_build_batch": (i32, [vp, C.POINTER(StopPolicy), i32, vp, C.POINTER(i32)]),
     }
     for name, (res, args) in sigs.items():
         fn = getattr(lib, name)
@@ -210,3 +227,65 @@ def fea_profile_read(call: int):
     ms = np.zeros(3, dtype=np.float32)
     _check(load_library().fea_profile_read(call, _np_ptr(ms)))
     return float(ms[0]), float(ms[1]), float(ms[2])
+
+
+class Cht:
+    """fea_cht_*: the scheduler's Chunked Hash Tree (argument marshalling only)."""
+
+    def __init__(self, chunk_tokens: int = 16):
+        self._lib = load_library()
+        h = C.c_void_p()
+        _check(self._lib.fea_cht_create(chunk_tokens, C.byref(h)))
+        self._h = h
+
+    def close(self):
+        if self._h:
+            self._lib.fea_cht_destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+    def insert(self, rid: int, tokens=None, hash_vector=None):
+        if hash_vector is not None:
+            hv = np.ascontiguousarray(hash_vector, dtype=np.uint64)
+            _check(self._lib.fea_cht_insert_hashes(self._h, rid, _np_ptr(hv), hv.size))
+        else:
+            tk = np.ascontiguousarray(tokens, dtype=np.int32)
+            _check(self._lib.fea_cht_insert(self._h, rid, _np_ptr(tk), tk.size))
+
+    def find_best(self):
+        """(request, tip depth now, tip depth with it added, peers, missing count) or None."""
+        rid, a, b, p, m = C.c_int64(), C.c_int32(), C.c_int32(), C.c_int32(), C.c_int32()
+        rc = self._lib.fea_cht_find_best(self._h, C.byref(rid), C.byref(a), C.byref(b), C.byref(p), C.byref(m))
+        if rc == 1:
+            return None
+        _check(rc)
+        return rid.value, a.value, b.value, p.value, m.value
+
+    def add_to_batch(self, rid: int):
+        _check(self._lib.fea_cht_add_to_batch(self._h, rid))
+
+    def finish(self, rid: int):
+        _check(self._lib.fea_cht_finish(self._h, rid))
+
+    def remove(self, rid: int):
+        _check(self._lib.fea_cht_remove(self._h, rid))
+
+    def missing(self, rid: int) -> int:
+        m = C.c_int32()
+        _check(self._lib.fea_cht_missing(self._h, rid, C.byref(m)))
+        return m.value
+
+    def stats(self):
+        nw, na, ws, he = C.c_int64(), C.c_int64(), C.c_int64(), C.c_int64()
+        tl, th = C.c_int32(), C.c_uint64()
+        _check(self._lib.fea_cht_stats(self._h, C.byref(nw), C.byref(na), C.byref(tl), C.byref(th), C.byref(ws), C.byref(he)))
+        return {"waiting": nw.value, "active": na.value, "tip_level": tl.value, "tip_hash": th.value,
+                "working_set": ws.value, "heap_entries": he.value}
+
+    def build_batch(self, max_batch: int, **policy):
+        pol = StopPolicy(**policy)
+        ids = np.zeros(max(max_batch, 1), dtype=np.int64)
+        n = C.c_int32()
+        _check(self._lib.fea_cht_build_batch(self._h, C.byref(pol), max_batch, _np_ptr(ids), C.byref(n)))
+        return ids[:n.value].tolist()

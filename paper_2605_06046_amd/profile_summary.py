@@ -12,6 +12,10 @@
     rocprofv3 --pmc WRITE_SIZE --kernel-trace -d <raw_dir>/pmc_WRITE_SIZE_W -o p --output-format csv -- \\
         python3 bench.py --workload W --no-cpu-baseline --steps 40 --warmup 4 --copy-calibration
 
+and, optionally, <raw_dir>/untraced_W.json: the output line of the first command run
+without the profiler (the library's own per-dispatch events read longer while the
+profiler intercepts the launches, so this is the line to compare with).
+
 --copy-calibration makes bench.py start with three plain 1 GiB device-to-device
 copies; what the counters read for them fixes the scale of each counter.
 """
@@ -85,9 +89,15 @@ def main(raw: str, wl: str, out: str) -> None:
     res["unique_kv_bytes"] = bench["roofline"]["bytes_per_launch"]
     lines += [f"  total {total / 1e6:.2f} MB per launch; algorithmic (distinct live KV blocks, K and V): "
               f"{res['unique_kv_bytes'] / 1e6:.2f} MB; ratio {total / res['unique_kv_bytes']:.3f}",
-              "", "bench.py line of the traced run (events inside bench.py, same command):",
-              f"  sweep avg {bench['kernel_us']['sweep']:.2f} us by HIP events vs {res['avg_us']:.2f} us by rocprofv3; "
-              f"roofline.achieved {bench['roofline']['achieved']:.0f} GB/s = {bench['roofline']['frac']:.3f} of 8000"]
+              "", "bench.py line of the traced run (events inside bench.py, same command; the profiler's interception adds to them):",
+              f"  sweep avg {bench['kernel_us']['sweep']:.2f} us by HIP events vs {res['avg_us']:.2f} us by rocprofv3"]
+    un = f"{raw}/untraced_{wl}.json"
+    if os.path.exists(un):
+        b2 = json.loads(open(un).read().strip().splitlines()[-1])
+        lines += ["bench.py line of the same command without the profiler:",
+                  f"  sweep avg {b2['kernel_us']['sweep']:.2f} us by HIP events vs {res['avg_us']:.2f} us by rocprofv3; "
+                  f"roofline.achieved {b2['roofline']['achieved']:.0f} GB/s = {b2['roofline']['frac']:.3f} of 8000; "
+                  f"whole step {b2['ms_per_step'] * 1e3:.1f} us = {b2['value']:.0f} {b2['unit']}"]
     open(os.path.join(out, f"sweep_mfma_{wl}_trace.txt"), "w").write("\n".join(lines) + "\n")
     json.dump(res, open(os.path.join(out, f"sweep_mfma_{wl}_pmc.json"), "w"), indent=1)
     print("\n".join(lines))
