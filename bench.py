@@ -248,6 +248,8 @@ def main():
     ap.add_argument("--graph", action="store_true", help="replay the steps from a captured HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--suite", action="store_true", help="also run all shapes and the homogeneity comparisons")
+    ap.add_argument("--scheduler", action="store_true",
+                    help="also compare first-come-first-served batches with batches formed by the Chunked Hash Tree")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run a plain 1 GiB device-to-device copy three times (known traffic, for counter runs)")
     args = ap.parse_args()
@@ -300,6 +302,14 @@ def main():
     else:
         line["cpu_baseline"] = None
 
+    if args.scheduler and not args.suite:
+        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+        with open(os.path.join(ROOT, "gpurun_out", "scheduler.jsonl"), "w") as f:
+            del case
+            torch.cuda.empty_cache()
+            for res in scheduler_comparison(max(50, args.steps // 4), max(10, args.warmup // 2), args.graph):
+                f.write(json.dumps(res) + "\n")
+                log(json.dumps(res))
     if args.suite:
         os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
         with open(os.path.join(ROOT, "gpurun_out", "suite.jsonl"), "w") as f:
@@ -410,7 +420,7 @@ def scheduler_comparison(steps, warm, graph):
     for name, batches in (("sched_fcfs_batches_of_32", fcfs_batches), ("sched_cht_batches_of_32", cht_batches)):
         total_ms, n, groups_per_batch = 0.0, 0, []
         for k, sel in enumerate(batches):
-            sp = dataclasses.replace(base, name=f"{name}_{k}", batch=len(sel))
+            sp = dataclasses.replace(base, name=f"{name}_{k}")
             c = Case(sp, tokens=sub(sel), label=sp.name)
             total_ms += c.measure(steps, warm, graph=graph)["ms_per_step"]
             n += c.B
