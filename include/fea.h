@@ -205,6 +205,36 @@ int32_t fea_decode_plan_info(const void* workspace /* DEVICE */, void* hip_strea
                              int32_t* info /* HOST [8] */);
 
 /* ------------------------------------------------------------------------
+ * One decode step's growth of the KV history (Section 2.1: every decode step
+ * appends one token's key and value per request; Section 3: in 16-token blocks).
+ *
+ * fea_kv_extend (HOST bookkeeping): every request's length grows by one; a
+ * request whose length was a multiple of 16 (0 included) gets a fresh block from
+ * the head of the free list, requests in index order, written into its table row
+ * at column old_length / 16.  Such a block is private: it holds no registered
+ * prefix and is never aliased.  block_tables (HOST [B x table_stride]) and
+ * seq_lens (HOST [B]) are updated in place; *n_new_blocks (may be NULL) receives
+ * the number of table entries written, so the caller knows whether the device
+ * copy of the tables is stale.  Errors: FEA_ERANGE if a row has no column left,
+ * FEA_ENOMEM if the pool has too few free blocks, FEA_EINVAL; nothing changed then.
+ *
+ * fea_kv_append (DEVICE, asynchronous on hip_stream): writes request i's new key
+ * and value rows (k_new, v_new: [B, num_kv_heads, head_dim], the caches' dtype)
+ * into the caches at token position seq_lens[i] - 1 - the lengths passed already
+ * count the new token, as after fea_kv_extend.  Requests with length 0, a table
+ * too narrow for the position or a padding entry there are skipped.  Only
+ * num_kv_heads, head_dim, block_size and dtype of params are read.
+ * Errors: FEA_EINVAL (NULL, shape, alignment: all device pointers 16-byte
+ * aligned), FEA_EHIP.
+ */
+int32_t fea_kv_extend(fea_kv_pool* pool, int32_t* block_tables /* HOST in/out */, int32_t table_stride,
+                      int32_t* seq_lens /* HOST in/out */, int32_t B, int32_t* n_new_blocks /* HOST, may be NULL */);
+int32_t fea_kv_append(const fea_attn_params* params, const void* k_new /* DEVICE */, const void* v_new /* DEVICE */,
+                      void* k_cache /* DEVICE */, void* v_cache /* DEVICE */,
+                      const int32_t* block_tables /* DEVICE */, int32_t table_stride,
+                      const int32_t* seq_lens /* DEVICE */, int32_t B, void* hip_stream);
+
+/* ------------------------------------------------------------------------
  * Chunked Hash Tree: which waiting requests should join the running batch
  * (Section 4.2 "Chunked Hash Tree"; appendix "Algorithms": Insert, FindBest,
  * AddToBatch, Finish, Remove, BuildBatch).  Host bookkeeping only; it is the

@@ -301,6 +301,38 @@ int32_t fea_release(fea_kv_pool* pool, const int32_t* row, int32_t nb) {
     return FEA_OK;
 }
 
+int32_t fea_kv_extend(fea_kv_pool* pool, int32_t* bt, int32_t stride, int32_t* seq_lens, int32_t B, int32_t* n_new_blocks) {
+    if (!pool) return fail(FEA_EINVAL, "fea_kv_extend: pool is NULL");
+    if (B < 0 || stride < 0 || (B > 0 && (!bt || !seq_lens))) return fail(FEA_EINVAL, "fea_kv_extend: bad arguments");
+    // validate everything and count the blocks needed before touching anything
+    size_t need = 0;
+    for (int32_t i = 0; i < B; ++i) {
+        const int32_t L = seq_lens[i];
+        if (L < 0 || L == INT32_MAX) return fail(FEA_EINVAL, "fea_kv_extend: seq_lens[%d]=%d out of range", i, L);
+        if (L % kK == 0) {
+            if (L / kK >= stride) return fail(FEA_ERANGE, "fea_kv_extend: request %d needs column %d, the table has %d", i, L / kK, stride);
+            ++need;
+        }
+    }
+    if (need > pool->free_list.size())
+        return fail(FEA_ENOMEM, "fea_kv_extend: %zu blocks needed, %zu free", need, pool->free_list.size());
+    for (int32_t i = 0; i < B; ++i) {
+        const int32_t L = seq_lens[i];
+        if (L % kK == 0) {   // the new token opens a block: a private one, it holds no registered prefix
+            const int32_t b = pool->free_list.front();
+            pool->free_list.pop_front();
+            fea::BlockMeta& m = pool->meta[b];
+            m.refcount = 1;
+            m.parent = -1;
+            m.level = -1;
+            bt[(size_t)i * stride + L / kK] = b;
+        }
+        seq_lens[i] = L + 1;
+    }
+    if (n_new_blocks) *n_new_blocks = (int32_t)need;
+    return FEA_OK;
+}
+
 int32_t fea_validate_block_tables(const int32_t* bt, int32_t stride, const int32_t* seq_lens, int32_t B, uint32_t num_blocks) {
     if (B < 0 || stride < 0 || (B > 0 && (!bt || !seq_lens))) return fail(FEA_EINVAL, "fea_validate_block_tables: bad arguments");
     for (int32_t i = 0; i < B; ++i) {

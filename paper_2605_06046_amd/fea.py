@@ -77,6 +77,8 @@ def load_library() -> C.CDLL:
         "fea_decode_plan_info": (i32, [vp, vp, vp]),
         "fea_profile_enable": (i32, [i32, i32]),
         "fea_profile_read": (i32, [i32, vp]),
+        "fea_kv_extend": (i32, [vp, vp, i32, vp, i32, C.POINTER(i32)]),
+        "fea_kv_append": (i32, [C.POINTER(AttnParams), vp, vp, vp, vp, vp, i32, vp, i32, vp]),
         "fea_cht_create": (i32, [i32, C.POINTER(vp)]),
         "fea_cht_destroy": (None, [vp]),
         "fea_cht_insert": (i32, [vp, i64, vp, i64]),
@@ -172,6 +174,15 @@ def fea_release(pool: KVPool, row: np.ndarray) -> None:
     _check(load_library().fea_release(pool.handle, _np_ptr(row), len(row)))
 
 
+def fea_kv_extend(pool: KVPool, tables: np.ndarray, seq_lens: np.ndarray) -> int:
+    """One decode step of bookkeeping, in place on the C-contiguous int32 host arrays; returns the blocks added."""
+    assert tables.dtype == np.int32 and seq_lens.dtype == np.int32 and tables.flags.c_contiguous and seq_lens.flags.c_contiguous
+    n = C.c_int32()
+    _check(load_library().fea_kv_extend(pool.handle, _np_ptr(tables), tables.shape[1], _np_ptr(seq_lens),
+                                        tables.shape[0], C.byref(n)))
+    return n.value
+
+
 def fea_validate_block_tables(tables: np.ndarray, seq_lens: np.ndarray, num_blocks: int) -> None:
     tables = np.ascontiguousarray(tables, dtype=np.int32)
     seq_lens = np.ascontiguousarray(seq_lens, dtype=np.int32)
@@ -215,6 +226,15 @@ def fea_decode_plan_info(workspace, stream=None) -> dict:
     keys = ("items", "groups", "grouped_requests", "split_blocks", "partial_rows", "shared_blocks",
             "variant", "overflow")
     return dict(zip(keys, (int(x) for x in info)))
+
+
+def fea_kv_append(params: AttnParams, k_new, v_new, k_cache, v_cache, block_tables, seq_lens, stream=None) -> None:
+    """Torch tensors on the GPU; writes each request's new K/V rows at position seq_lens - 1.  Asynchronous."""
+    import torch
+    st = stream if stream is not None else torch.cuda.current_stream()
+    _check(load_library().fea_kv_append(C.byref(params), _dev_ptr(k_new), _dev_ptr(v_new), _dev_ptr(k_cache),
+                                        _dev_ptr(v_cache), _dev_ptr(block_tables), block_tables.shape[1],
+                                        _dev_ptr(seq_lens), block_tables.shape[0], C.c_void_p(st.cuda_stream)))
 
 
 def fea_profile_enable(max_calls: int, which: int = -1) -> None:
