@@ -38,17 +38,23 @@ def log(*a):
 class Case:
     """One batch on the device: tables from the library, q and a replicated KV pool."""
 
-    def __init__(self, spec, replicas_bytes=1 << 30, seed_shift=0, tokens=None, max_group=0, label=None):
+    def __init__(self, spec, replicas_bytes=1 << 30, seed_shift=0, tokens=None, max_group=0, label=None,
+                 extra_blocks=0, extra_cols=0):
         import torch
         import paper_2605_06046_amd as fea
         self.fea, self.torch, self.spec = fea, torch, spec
         self.label = label or spec.name
         wl = W.generate(spec, with_kv=False) if tokens is None else tokens
+        if extra_blocks or extra_cols:   # room for the history to grow (decode loop)
+            import dataclasses
+            wl = dataclasses.replace(wl, num_blocks=wl.num_blocks + extra_blocks,
+                                     max_blocks_per_seq=wl.max_blocks_per_seq + extra_cols)
         self.wl = wl
         t0 = time.perf_counter()
         pool = fea.fea_kv_alloc(wl.num_blocks, 16, wl.perm_seed)
         bt, lens, _, _ = fea.fea_build_block_tables(pool, wl.tokens, wl.tok_offsets, wl.max_blocks_per_seq)
         self.table_build_s = time.perf_counter() - t0
+        self.pool = pool
         self.bt, self.lens = bt, lens
         self.B = bt.shape[0]
         live = np.unique(bt[bt >= 0])
@@ -248,6 +254,8 @@ def main():
     ap.add_argument("--graph", action="store_true", help="replay the steps from a captured HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--suite", action="store_true", help="also run all shapes and the homogeneity comparisons")
+    ap.add_argument("--decode-loop", type=int, default=0, metavar="N",
+                    help="also run N decode steps (extend, append, attend over the KV replicas as layers)")
     ap.add_argument("--scheduler", action="store_true",
                     help="also compare first-come-first-served batches with batches formed by the Chunked Hash Tree")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -302,6 +310,11 @@ def main():
     else:
         line["cpu_baseline"] = None
 
+    if args.decode_loop > 0:
+        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+        res = decode_loop(args.decode_loop)
+        open(os.path.join(ROOT, "gpurun_out", "decode_loop.json"), "w").write(json.dumps(res) + "\n")
+        log(json.dumps(res))
     if args.scheduler and not args.suite:
         os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
         with open(os.path.join(ROOT, "gpurun_out", "scheduler.jsonl"), "w") as f:
@@ -375,6 +388,52 @@ def run_suite(args):
     yield {"workload": "H1_eight_homogeneous_launches_of_32", "B": B, "ms_per_step": total_ms,
            "ms_per_step_warm": total_ms_warm, "tokens_per_s": B / (total_ms * 1e-3)}
     yield from scheduler_comparison(steps, warm, args.graph)
+
+
+def decode_loop(n_steps, layers=None):
+    """A run of decode steps on the c2 batch: per step the host extends tables and lengths by one
+    token, and every layer (a replica of the KV pool stands for a layer's cache) appends its new K/V
+    rows and attends; alias detection runs once per step and is shared by the layers."""
+    import torch
+    import paper_2605_06046_amd as fea
+    spec = W.CONFIGS["c2"]
+    c = Case(spec, extra_blocks=spec.batch * (n_steps // 16 + 2), extra_cols=n_steps // 16 + 2)
+    L = c.R if layers is None else min(layers, c.R)
+    p_plan = c.params
+    p_reuse = fea.AttnParams(spec.num_q_heads, spec.num_kv_heads, spec.head_dim, p_plan.dtype, flags=fea.FEA_FLAG_REUSE_PLAN)
+    g = torch.Generator(device="cuda"); g.manual_seed(5)
+    shape_new = (c.B, spec.num_kv_heads, spec.head_dim)
+    k_new = torch.randn(shape_new, generator=g, device="cuda").to(c.k.dtype)
+    v_new = torch.randn(shape_new, generator=g, device="cuda").to(c.k.dtype)
+    bt, lens = c.bt, c.lens
+    pin_l = torch.from_numpy(lens.copy()).pin_memory()
+    pin_t = torch.from_numpy(bt.copy()).pin_memory()
+
+    def step():
+        n_new = fea.fea_kv_extend(c.pool, bt, lens)
+        pin_l.copy_(torch.from_numpy(lens)); c.dl.copy_(pin_l, non_blocking=True)
+        if n_new:
+            pin_t.copy_(torch.from_numpy(bt)); c.dbt.copy_(pin_t, non_blocking=True)
+        for l in range(L):
+            fea.fea_kv_append(p_plan, k_new, v_new, c.k[l], c.v[l], c.dbt, c.dl)
+            fea.fea_decode_attention(p_plan if l == 0 else p_reuse, c.q, c.k[l], c.v[l], c.dbt, c.dl, c.out, c.ws)
+
+    for _ in range(5):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(n_steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms = e0.elapsed_time(e1) / n_steps
+    return {"workload": f"decode_loop_c2_{L}_layers", "B": c.B, "decode_steps": n_steps, "layers": L,
+            "ms_per_decode_step": ms, "us_per_layer": ms * 1e3 / L, "tokens_per_s_per_layer_call": c.B / (ms * 1e-3 / L),
+            "tokens_per_s_model_of_these_layers": c.B / (ms * 1e-3), "host_wall_ms_per_step": wall * 1e3 / n_steps,
+            "final_len_mean": float(lens.mean())}
 
 
 def scheduler_comparison(steps, warm, graph):
