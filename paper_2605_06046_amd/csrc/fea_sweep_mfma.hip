@@ -347,9 +347,24 @@ __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item,
     // scaled scores with their per-lane maximum.  back(): weights, denominators and
     // O^T += V^T P^T.  Between the two the reference exponents may have to be raised;
     // that happens in a second copy of the loop, entered at most once per item.
-    float rr[NT][8];   // scores of this lane's 8 tokens per row tile (masked), before scaling
-    float tmax[NT];    // scaled maximum of those
+    f32x4 sacc[NT][2]; // S^T of the tile: this lane's 8 tokens (two blocks of 4) per row tile
+    float tmax[NT];    // scaled maximum of those, positions past the end left out
+    int tile_pos = 0;  // position of the tile's first token
+    bool ragged = false;   // the tile reaches past the item's last token (wave-uniform)
     bf16x8 vA[8];      // vA[i]: head dim 8*(lane%16) + i, k-slots = the lane group's 8 tokens
+    auto scores = [&](int nt, float (&r)[8]) {   // this lane's 8 scores of row tile nt; -inf past the end
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) r[mt * 4 + jj] = sacc[nt][mt][jj];
+        if (__builtin_expect(ragged, 0)) {
+#pragma unroll
+            for (int x = 0; x < 8; ++x) {
+                const int pos = tile_pos + (x >> 2) * 16 + kg * 4 + (x & 3);
+                if (pos >= item.tok_end) r[x] = -INFINITY;
+            }
+        }
+    };
     auto front = [&](int t) {
         const int stg = (sm.phase + t) & 1;
         const char* st = s_stage + stg * kStageBytes;
@@ -372,11 +387,10 @@ __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item,
             issue(t + 2);
         }
 
-        const int tile_pos = (item.c0 + 2 * t) * kBlock;          // position of the tile's first token
-        const bool ragged = tile_pos + kTileTok > item.tok_end;   // wave-uniform
+        tile_pos = (item.c0 + 2 * t) * kBlock;
+        ragged = tile_pos + kTileTok > item.tok_end;
 
         // ---- S^T = K Q^T
-        f32x4 sacc[NT][2];
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) sacc[nt][0] = sacc[nt][1] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -418,22 +432,13 @@ __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item,
             vA[i] = as_bf16x8(o);
         }
 
-        // ---- scores, one query row per lane (per row tile)
+        // ---- row maxima, one query row per lane (per row tile); the scores themselves stay
+        // in the accumulation registers until back() turns them into weights
         bool raise = false;
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                for (int jj = 0; jj < 4; ++jj) rr[nt][mt * 4 + jj] = sacc[nt][mt][jj];
-            if (__builtin_expect(ragged, 0)) {
-#pragma unroll
-                for (int x = 0; x < 8; ++x) {
-                    const int pos = tile_pos + (x >> 2) * 16 + kg * 4 + (x & 3);
-                    if (pos >= item.tok_end) rr[nt][x] = -INFINITY;
-                }
-            }
-            const float* r = rr[nt];
+            float r[8];
+            scores(nt, r);
             tmax[nt] = a.scale_log2 *
                 fmaxf(fmaxf(fmaxf(r[0], r[1]), fmaxf(r[2], r[3])), fmaxf(fmaxf(r[4], r[5]), fmaxf(r[6], r[7])));
             raise = raise || tmax[nt] > m_run[nt] + kSlack;
@@ -465,9 +470,11 @@ __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item,
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
             const float neg_m = -m_run[nt];
+            float r[8];
+            scores(nt, r);
             bf16x8 pB;
 #pragma unroll
-            for (int x = 0; x < 8; ++x) pB[x] = (__bf16)fast_exp2(fmaf(rr[nt][x], a.scale_log2, neg_m));
+            for (int x = 0; x < 8; ++x) pB[x] = (__bf16)fast_exp2(fmaf(r[x], a.scale_log2, neg_m));
             lacc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pB, lacc[nt], 0, 0, 0);
 #pragma unroll
             for (int i = 0; i < 8; ++i)
