@@ -334,15 +334,24 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
                 const int y = __shfl_up(x, o);
                 if (lane >= o) x += y;
             }
-            total = __shfl(x, span - 1);
+            total = span > 1 ? __shfl(x, span - 1) : __builtin_amdgcn_readfirstlane(x);
             return x - v;
         };
         const int fixed_tiles = a.split_user > 0 ? a.split_user >> 1 : 0;   // split_user is even
+        // group gi's leader, members and run: the lane keeps those of group `lane` in registers
+        // (every pass below starts there, and there are rarely more than 64 groups)
+        int my_ld = 0, my_cnt = 0, my_run = 0;
+        if (lane < n_groups) { my_ld = w.glist[lane]; my_cnt = u.c.cnt[my_ld]; my_run = u.c.run[my_ld]; }
+        auto group = [&](int gi, int& ld, int& cnt, int& run) {
+            if (gi == lane) { ld = my_ld; cnt = my_cnt; run = my_run; }
+            else { ld = w.glist[gi]; cnt = u.c.cnt[ld]; run = u.c.run[ld]; }
+        };
         long long u_loc = 0, t_loc = 0;
         for (int gi = lane; gi < n_groups; gi += 64) {
-            const int ld = w.glist[gi];
-            const long long t = (long long)Hkv * by_mpt.cdiv(u.c.cnt[ld]) * ((u.c.run[ld] + 1) >> 1);
-            u_loc += t * tile_weight(min(a.mpt, u.c.cnt[ld]) * a.G);
+            int ld, cnt, run;
+            group(gi, ld, cnt, run);
+            const long long t = (long long)Hkv * by_mpt.cdiv(cnt) * ((run + 1) >> 1);
+            u_loc += t * tile_weight(min(a.mpt, cnt) * a.G);
             t_loc += t;
         }
         const long long U = wsum(u_loc) + 16ll * T_pr, total_tiles = wsum(t_loc) + T_pr;
@@ -355,12 +364,13 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
         for (int round = 0; round < 4; ++round) {
             int loc = 0;
             for (int gi = lane; gi < n_groups; gi += 64) {
-                const int ld = w.glist[gi];
-                const int T_seg = (u.c.run[ld] + 1) >> 1;
-                const int want = fixed_tiles > 0 ? fixed_tiles : max(1, idiv(Q, tile_weight(min(a.mpt, u.c.cnt[ld]) * a.G)));
+                int ld, cnt, run;
+                group(gi, ld, cnt, run);
+                const int T_seg = (run + 1) >> 1;
+                const int want = fixed_tiles > 0 ? fixed_tiles : max(1, idiv(Q, tile_weight(min(a.mpt, cnt) * a.G)));
                 const int n_pc = idiv(T_seg + want - 1, want);
                 v.g.npc[gi] = n_pc;
-                loc += Hkv * by_mpt.cdiv(u.c.cnt[ld]) * n_pc;
+                loc += Hkv * by_mpt.cdiv(cnt) * n_pc;
             }
             n_sh = (int)wsum(loc);
             if (fixed_tiles > 0) break;
@@ -376,10 +386,11 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
             const int gi = g0 + lane;
             int ni = 0, nsg = 0, nr = 0;
             if (gi < n_groups) {
-                const int ld = w.glist[gi];
-                nsg = Hkv * by_mpt.cdiv(u.c.cnt[ld]);
+                int ld, cnt, run;
+                group(gi, ld, cnt, run);
+                nsg = Hkv * by_mpt.cdiv(cnt);
                 ni = nsg * v.g.npc[gi];
-                nr = Hkv * v.g.npc[gi] * u.c.cnt[ld] * a.G;
+                nr = Hkv * v.g.npc[gi] * cnt * a.G;
             }
             int ti, ts, tr;
             const int xi = scan_excl(ni, ti), xs = scan_excl(nsg, ts), xr = scan_excl(nr, tr);
@@ -440,15 +451,15 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
     // shares: a shared piece each, then the cuts of the private stream; with a fixed
     // split all items are dealt out in equal numbers instead
     const int n_shares = overflow ? 0 : (fixed_tiles > 0 ? min(a.tune.n_waves, total_items) : n_sh + (T_pr + q - 1) / q);
-    for (int x = tid; x <= a.lay.max_items; x += kPlanThreads) {
-        int first = overflow ? 0 : total_items;
-        if (!overflow) {
-            if (fixed_tiles > 0) { if (x < n_shares) first = (int)ddiv((long long)x * total_items, n_shares); }
-            else if (x <= n_sh) first = x;
-        }
-        if (x <= n_shares || x == a.lay.max_items) wave_first[x] = first;
+    // first item of every share: a shared piece is its own share, the private shares'
+    // entries are written by whoever emits their first item (below); with a fixed split
+    // the items are dealt out evenly; then the end marks
+    for (int x = tid; x <= n_shares; x += kPlanThreads) {
+        if (x == n_shares) wave_first[x] = overflow ? 0 : total_items;
+        else if (fixed_tiles > 0) wave_first[x] = (int)ddiv((long long)x * total_items, n_shares);
+        else if (x < n_sh) wave_first[x] = x;
     }
-    __syncthreads();   // defaults of wave_first[] are in place before pieces overwrite their entries
+    if (tid == 0) wave_first[a.lay.max_items] = overflow ? 0 : total_items;
 
     // ---- descriptors and items of the requests' own columns
     {
