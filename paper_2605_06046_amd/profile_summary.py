@@ -61,8 +61,13 @@ def main(raw: str, wl: str, out: str) -> None:
     os.makedirs(out, exist_ok=True)
     stats = list(csv.DictReader(open(_one(f"{raw}/trace_{wl}/**/*kernel_stats.csv"))))
     ours = [r for r in stats if r["Name"].startswith(("fea::", "void fea::"))]
-    lines = [f"rocprofv3 --kernel-trace --stats of: python3 bench.py --workload {wl} --no-cpu-baseline --steps 200 --warmup 20",
-             "(library kernels only; durations in microseconds)", "",
+    lines = ["Commands (from /tmp with TMPDIR=/tmp, bench.py by its absolute path; raw output in <raw>):",
+             f"  rocprofv3 --kernel-trace --stats -d <raw>/trace_{wl} -o t --output-format csv -- python3 bench.py --workload {wl} --no-cpu-baseline --steps 200 --warmup 20",
+             f"  rocprofv3 --pmc FETCH_SIZE --kernel-trace -d <raw>/pmc_FETCH_SIZE_{wl} -o p --output-format csv -- python3 bench.py --workload {wl} --no-cpu-baseline --steps 40 --warmup 4 --copy-calibration",
+             f"  rocprofv3 --pmc WRITE_SIZE --kernel-trace -d <raw>/pmc_WRITE_SIZE_{wl} -o p --output-format csv -- python3 bench.py --workload {wl} --no-cpu-baseline --steps 40 --warmup 4 --copy-calibration",
+             f"  python3 bench.py --workload {wl} --no-cpu-baseline --steps 200 --warmup 20    (no profiler)",
+             f"  python3 -m paper_2605_06046_amd.profile_summary <raw> {wl} profiles",
+             "", "Kernel trace (library kernels only; durations in microseconds)", "",
              f"{'kernel':58s} {'calls':>6s} {'avg':>9s} {'min':>9s} {'max':>9s} {'share':>7s}"]
     for r in ours:
         lines.append(f"{r['Name'][:58]:58s} {r['Calls']:>6s} {float(r['AverageNs']) / 1e3:9.2f} "
