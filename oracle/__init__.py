@@ -29,4 +29,12 @@ What pins each function (see the tests that do not need a GPU):
   the appendix on the alternative FindBest heuristic, and that appendix's
   theorem checked on random trees.  The constants of the stop policy are free
   parameters in the paper: policy parity is unpinned.
+* policy.UcbBandit / policy.QLearner - the two update rules of Section 4.3 taken
+  literally over dictionaries; pinned by values worked by hand (one UCB index,
+  two passes of a three-step Q-learning episode, the Bellman fixed point of a
+  chain), the logarithmic bound on the pulls of a worse arm under deterministic
+  rewards, and written-out bin tables.  The bins' shape, the tie rules and
+  which transitions receive the reward are readings (listed in that module);
+  the paper gives no constants, so learned *behaviour* on a workload is
+  unpinned.
 """
