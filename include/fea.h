@@ -307,6 +307,75 @@ typedef struct fea_stop_policy {
 int32_t fea_cht_build_batch(fea_cht* t, const fea_stop_policy* policy, int32_t max_batch,
                             int64_t* ids, int32_t* n_out);
 
+/* Learned stop policies of Section 4.3 ("Contextual Bandit", "Q-Learning Policy").
+ * The state of a decision is (b, loss, peers) as for the rule-based policy,
+ * discretised: b and peers into exponential bins (0 for 0, else 1 + floor(log2 x),
+ * capped at bins - 1), loss into the number of the ascending loss_thresholds it
+ * exceeds.  Actions: FEA_ADD, FEA_STOP.
+ *   FEA_POLICY_UCB: takes the action with the larger mu/n + c sqrt(ln S / n)
+ *     (mu: summed reward of the entry, n: times credited, S: all credited
+ *     decisions); an entry never credited goes first, ADD before STOP; ties: ADD.
+ *   FEA_POLICY_QLEARN: epsilon-greedy over a table Q (all zero at first); after
+ *     an episode each of its transitions, in the order taken, is updated by
+ *     Q += alpha (r + gamma max_a' Q(next state, a') - Q); the state after the
+ *     last decision is terminal.  reward_every_step != 0 hands the reward to
+ *     every transition, 0 to the last one only.  Then eps = max(eps_min,
+ *     eps * eps_decay).
+ * The paper fixes none of the constants. */
+enum { FEA_ADD = 0, FEA_STOP = 1 };
+enum { FEA_POLICY_UCB = 1, FEA_POLICY_QLEARN = 2 };
+#define FEA_POLICY_MAX_THRESHOLDS 8
+typedef struct fea_policy_params {
+    int32_t kind;                    /* FEA_POLICY_UCB | FEA_POLICY_QLEARN */
+    int32_t b_bins, w_bins;          /* 1..64 each */
+    int32_t n_loss_thresholds;       /* 0..FEA_POLICY_MAX_THRESHOLDS */
+    int32_t loss_thresholds[FEA_POLICY_MAX_THRESHOLDS];   /* ascending */
+    int32_t reward_every_step;       /* Q-learning only */
+    double c;                        /* UCB exploration coefficient, >= 0 */
+    double alpha, gamma;             /* Q-learning: 0 < alpha <= 1, 0 <= gamma <= 1 */
+    double eps, eps_min, eps_decay;  /* Q-learning: all in [0, 1] */
+} fea_policy_params;
+typedef struct fea_policy fea_policy;
+
+/* Creates a policy with empty tables (b_bins x (n_loss_thresholds + 1) x w_bins x 2
+ * entries).  Errors: FEA_EINVAL for NULL or parameters outside the ranges above. */
+int32_t fea_policy_create(const fea_policy_params* params, fea_policy** out);
+void    fea_policy_destroy(fea_policy* p);
+
+/* The discretised state of (b, loss, peers); any output may be NULL. */
+int32_t fea_policy_state(const fea_policy* p, int32_t b, int32_t loss, int32_t peers,
+                         int32_t* b_bin, int32_t* loss_bin, int32_t* w_bin);
+
+/* One decision: writes FEA_ADD or FEA_STOP to *action and appends (state, action)
+ * to the open episode.  u_explore and u_action are the caller's uniform draws in
+ * [0, 1) (used by Q-learning only: explore when u_explore < eps, and then ADD when
+ * u_action < 1/2). */
+int32_t fea_policy_decide(fea_policy* p, int32_t b, int32_t loss, int32_t peers,
+                          double u_explore, double u_action, int32_t* action);
+
+/* Closes the open episode with the observed decode throughput as its reward and
+ * updates the tables as described above (an empty episode only decays eps). */
+int32_t fea_policy_reward(fea_policy* p, double reward);
+
+/* One table entry: UCB: *value = mean reward (0 if never credited), *count = n;
+ * Q-learning: *value = Q, *count = updates of the entry.  FEA_ERANGE for a bin or
+ * action outside the table. */
+int32_t fea_policy_entry(const fea_policy* p, int32_t b_bin, int32_t loss_bin, int32_t w_bin,
+                         int32_t action, double* value, int64_t* count);
+
+/* Credited decisions (S), closed episodes, the current eps (0 for UCB), decisions
+ * in the open episode; any pointer may be NULL. */
+int32_t fea_policy_info(const fea_policy* p, int64_t* decisions, int64_t* episodes, double* eps,
+                        int32_t* open_decisions);
+
+/* BuildBatch (appendix "Batch Formation") with a learned policy: FindBest, state,
+ * decision, AddToBatch until the policy stops, nothing is waiting, or max_batch
+ * requests were added.  draws (HOST [2 * max_batch]) holds one (u_explore,
+ * u_action) pair per decision, read in order; may be NULL for FEA_POLICY_UCB.
+ * The caller runs the batch and then calls fea_policy_reward. */
+int32_t fea_cht_build_batch_learned(fea_cht* t, fea_policy* policy, int32_t max_batch,
+                                    const double* draws, int64_t* ids, int32_t* n_out);
+
 /* Per-kernel timing for measurement runs.  fea_profile_enable(n, which) with n > 0
  * makes the next fea_decode_attention calls attach a pair of library-owned HIP events
  * to their launches; each pair takes the begin and end time of that one dispatch (no

@@ -10,5 +10,6 @@ from .fea import (  # noqa: F401
     fea_build_block_tables, fea_chunk_hashes, fea_decode_attention, fea_decode_plan_info,
     fea_decode_workspace_bytes, fea_kv_alloc, fea_kv_free, fea_kv_stats, fea_release,
     fea_validate_block_tables, fea_profile_enable, fea_profile_read, library_path, load_library,
-    Cht, StopPolicy, fea_kv_extend, fea_kv_append,
+    Cht, StopPolicy, fea_kv_extend, fea_kv_append, Policy, PolicyParams,
+    FEA_ADD, FEA_STOP, FEA_POLICY_UCB, FEA_POLICY_QLEARN,
 )

@@ -45,6 +45,18 @@ class StopPolicy(C.Structure):
                 ("peers_relax", C.c_int32), ("loss_relaxed", C.c_int32)]
 
 
+FEA_ADD, FEA_STOP = 0, 1
+FEA_POLICY_UCB, FEA_POLICY_QLEARN = 1, 2
+
+
+class PolicyParams(C.Structure):
+    """fea_policy_params: kind, bins and constants of a learned stop policy."""
+    _fields_ = [("kind", C.c_int32), ("b_bins", C.c_int32), ("w_bins", C.c_int32),
+                ("n_loss_thresholds", C.c_int32), ("loss_thresholds", C.c_int32 * 8),
+                ("reward_every_step", C.c_int32), ("c", C.c_double), ("alpha", C.c_double),
+                ("gamma", C.c_double), ("eps", C.c_double), ("eps_min", C.c_double), ("eps_decay", C.c_double)]
+
+
 def load_library() -> C.CDLL:
     """Loads libfea.so; raises if it has not been built (there is no fallback path)."""
     global _LIB
@@ -90,6 +102,14 @@ def load_library() -> C.CDLL:
         "fea_cht_missing": (i32, [vp, i64, C.POINTER(i32)]),
         "fea_cht_stats": (i32, [vp, C.POINTER(i64), C.POINTER(i64), C.POINTER(i32), C.POINTER(u64), C.POINTER(i64), C.POINTER(i64)]),
         "fea_cht_build_batch": (i32, [vp, C.POINTER(StopPolicy), i32, vp, C.POINTER(i32)]),
+        "fea_policy_create": (i32, [C.POINTER(PolicyParams), C.POINTER(vp)]),
+        "fea_policy_destroy": (None, [vp]),
+        "fea_policy_state": (i32, [vp, i32, i32, i32, C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)]),
+        "fea_policy_decide": (i32, [vp, i32, i32, i32, C.c_double, C.c_double, C.POINTER(i32)]),
+        "fea_policy_reward": (i32, [vp, C.c_double]),
+        "fea_policy_entry": (i32, [vp, i32, i32, i32, i32, C.POINTER(C.c_double), C.POINTER(i64)]),
+        "fea_policy_info": (i32, [vp, C.POINTER(i64), C.POINTER(i64), C.POINTER(C.c_double), C.POINTER(i32)]),
+        "fea_cht_build_batch_learned": (i32, [vp, vp, i32, vp, vp, C.POINTER(i32)]),
     }
     for name, (res, args) in sigs.items():
         fn = getattr(lib, name)
@@ -309,3 +329,63 @@ class Cht:
         n = C.c_int32()
         _check(self._lib.fea_cht_build_batch(self._h, C.byref(pol), max_batch, _np_ptr(ids), C.byref(n)))
         return ids[:n.value].tolist()
+
+    def build_batch_learned(self, policy: "Policy", max_batch: int, draws=None):
+        """fea_cht_build_batch_learned; draws: [max_batch, 2] uniforms (None for the bandit)."""
+        ids = np.zeros(max(max_batch, 1), dtype=np.int64)
+        n = C.c_int32()
+        d = None
+        if draws is not None:
+            d = np.ascontiguousarray(draws, dtype=np.float64).reshape(-1)
+            if d.size < 2 * max_batch:
+                raise ValueError("draws must hold 2 * max_batch values")
+        _check(self._lib.fea_cht_build_batch_learned(self._h, policy._h, max_batch, _np_ptr(d), _np_ptr(ids), C.byref(n)))
+        return ids[:n.value].tolist()
+
+
+class Policy:
+    """fea_policy_*: a learned stop policy (argument marshalling only)."""
+
+    def __init__(self, kind: int, b_bins: int, w_bins: int, loss_thresholds=(), c: float = 0.0, alpha: float = 0.0,
+                 gamma: float = 0.0, eps: float = 0.0, eps_min: float = 0.0, eps_decay: float = 1.0,
+                 reward_every_step: bool = True):
+        self._lib = load_library()
+        self._h = None
+        thr = list(loss_thresholds)
+        if len(thr) > 8:
+            raise ValueError("at most 8 loss thresholds")
+        prm = PolicyParams(kind, b_bins, w_bins, len(thr), (C.c_int32 * 8)(*thr), int(reward_every_step),
+                           c, alpha, gamma, eps, eps_min, eps_decay)
+        h = C.c_void_p()
+        _check(self._lib.fea_policy_create(C.byref(prm), C.byref(h)))
+        self._h = h
+
+    def close(self):
+        if self._h:
+            self._lib.fea_policy_destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+    def state(self, b: int, loss: int, peers: int):
+        sb, sl, sw = C.c_int32(), C.c_int32(), C.c_int32()
+        _check(self._lib.fea_policy_state(self._h, b, loss, peers, C.byref(sb), C.byref(sl), C.byref(sw)))
+        return sb.value, sl.value, sw.value
+
+    def decide(self, b: int, loss: int, peers: int, u_explore: float = 0.0, u_action: float = 0.0) -> int:
+        a = C.c_int32()
+        _check(self._lib.fea_policy_decide(self._h, b, loss, peers, u_explore, u_action, C.byref(a)))
+        return a.value
+
+    def reward(self, r: float):
+        _check(self._lib.fea_policy_reward(self._h, r))
+
+    def entry(self, state, action: int):
+        v, n = C.c_double(), C.c_int64()
+        _check(self._lib.fea_policy_entry(self._h, state[0], state[1], state[2], action, C.byref(v), C.byref(n)))
+        return v.value, n.value
+
+    def info(self):
+        d, e, eps, o = C.c_int64(), C.c_int64(), C.c_double(), C.c_int32()
+        _check(self._lib.fea_policy_info(self._h, C.byref(d), C.byref(e), C.byref(eps), C.byref(o)))
+        return {"decisions": d.value, "episodes": e.value, "eps": eps.value, "open": o.value}

@@ -178,3 +178,133 @@ def test_build_batch_forms_the_state_from_find_best():
         t2.insert(i, hash_vector=[7, 100 + i])
     pol2 = Scripted([ADD] * 4)
     assert build_batch_learned(t2, pol2, 2, draws, **BINS) == [0, 1] and len(pol2.states) == 2
+
+
+# ----------------------------------------------------------------- the library against the oracle
+
+fea = pytest.importorskip("paper_2605_06046_amd")
+
+
+def make_pair(kind, **kw):
+    if kind == "ucb":
+        lib = fea.Policy(fea.FEA_POLICY_UCB, BINS["b_bins"], BINS["w_bins"], BINS["loss_thresholds"], c=kw["c"])
+        ora = UcbBandit(c=kw["c"])
+    else:
+        lib = fea.Policy(fea.FEA_POLICY_QLEARN, BINS["b_bins"], BINS["w_bins"], BINS["loss_thresholds"], **kw)
+        ora = QLearner(**kw)
+    return lib, ora
+
+
+def same_tables(lib, ora, states):
+    for s in states:
+        for a in (ADD, STOP):
+            lv, ln = lib.entry(s, a)
+            ov, on = ora.value(s, a)
+            assert ln == on, (s, a)
+            assert lv == pytest.approx(ov, rel=1e-13, abs=1e-13), (s, a)
+
+
+def test_library_bins_match():
+    lib, _ = make_pair("ucb", c=1.0)
+    rng = random.Random(5)
+    cases = [(0, 0, 0), (1, -1, 1), (500, 9, 100000), (2 ** 31 - 1, 2 ** 31 - 1, 2 ** 31 - 1)]
+    cases += [(rng.randrange(0, 600), rng.randrange(-2, 40), rng.randrange(0, 3000)) for _ in range(300)]
+    for b, d, w in cases:
+        assert lib.state(b, d, w) == discretize(b, d, w, **BINS)
+
+
+@pytest.mark.parametrize("kind,kw", [
+    ("ucb", dict(c=1.0)), ("ucb", dict(c=0.0)), ("ucb", dict(c=2.5)),
+    ("q", dict(alpha=0.3, gamma=0.9, eps=1.0, eps_min=0.05, eps_decay=0.97, reward_every_step=True)),
+    ("q", dict(alpha=1.0, gamma=0.5, eps=0.5, eps_min=0.0, eps_decay=0.9, reward_every_step=False)),
+])
+def test_library_policy_follows_the_oracle(kind, kw):
+    lib, ora = make_pair(kind, **kw)
+    rng = random.Random(11)
+    seen = set()
+    for ep in range(400):
+        b = 0
+        for _ in range(rng.randrange(0, 12)):
+            loss, peers = rng.choice([0, 0, 1, 2, 3, 9, 20]), rng.randrange(0, 70)
+            u1, u2 = rng.random(), rng.random()
+            s = discretize(b, loss, peers, **BINS)
+            seen.add(s)
+            a = lib.decide(b, loss, peers, u1, u2)
+            assert a == ora.decide(s, u1, u2), (ep, b)
+            if a == STOP:
+                break
+            b += 1
+        assert lib.info()["open"] == len(ora.episode)
+        r = rng.choice([0.25, 0.5, 1.0, 1.5]) * (1.0 + 0.1 * rng.random())
+        lib.reward(r)
+        ora.reward(r)
+        if ep % 50 == 0:
+            same_tables(lib, ora, seen)
+    same_tables(lib, ora, seen)
+    info = lib.info()
+    assert info["episodes"] == 400 and info["open"] == 0
+    if kind == "ucb":
+        assert info["decisions"] == ora.S
+    else:
+        assert info["eps"] == pytest.approx(ora.eps, rel=1e-13)
+
+
+@pytest.mark.parametrize("kind", ["ucb", "q"])
+def test_library_batch_formation_follows_the_oracle(kind):
+    from oracle.hashing import chunk_hashes
+    rng = random.Random(3)
+    nprng = np.random.default_rng(3)
+    kw = dict(c=0.7) if kind == "ucb" else dict(alpha=0.4, gamma=0.8, eps=0.6, eps_min=0.02, eps_decay=0.95)
+    lib, ora = make_pair(kind, **kw)
+    prefixes = [nprng.integers(0, 50000, size=rng.choice([64, 160, 320]), dtype=np.int32) for _ in range(4)]
+    t_lib, t_ora = fea.Cht(), ChunkedHashTree()
+    next_id = 0
+    for rnd in range(60):
+        for _ in range(rng.randrange(2, 9)):                 # arrivals
+            pre = prefixes[rng.randrange(4)]
+            keep = rng.choice([len(pre), len(pre), len(pre) // 2])
+            toks = np.concatenate([pre[:keep], nprng.integers(0, 50000, size=rng.randrange(1, 70), dtype=np.int32)])
+            hv = chunk_hashes(toks, 16)
+            t_lib.insert(next_id, hash_vector=hv)
+            t_ora.insert(next_id, hash_vector=hv)
+            next_id += 1
+        cap = rng.choice([3, 8, 32])
+        draws = [(rng.random(), rng.random()) for _ in range(cap)]
+        got = t_lib.build_batch_learned(lib, cap, draws)
+        want = build_batch_learned(t_ora, ora, cap, draws, **BINS)
+        assert got == want, rnd
+        r = len(want) / (1.0 + 0.01 * sum(len(t_ora.hashes[i]) for i in want))     # any deterministic reward
+        lib.reward(r)
+        ora.reward(r)
+        for rid in want:
+            t_lib.finish(rid)
+            t_ora.finish(rid)
+    assert lib.info()["episodes"] == 60
+
+
+def test_library_policy_errors():
+    with pytest.raises(fea.FeaError):
+        fea.Policy(7, 4, 4)
+    with pytest.raises(fea.FeaError):
+        fea.Policy(fea.FEA_POLICY_UCB, 0, 4, c=1.0)
+    with pytest.raises(fea.FeaError):
+        fea.Policy(fea.FEA_POLICY_UCB, 4, 4, (3, 3), c=1.0)          # thresholds must ascend
+    with pytest.raises(fea.FeaError):
+        fea.Policy(fea.FEA_POLICY_UCB, 4, 4, c=-1.0)
+    with pytest.raises(fea.FeaError):
+        fea.Policy(fea.FEA_POLICY_QLEARN, 4, 4, alpha=0.0, gamma=0.5)
+    with pytest.raises(fea.FeaError):
+        fea.Policy(fea.FEA_POLICY_QLEARN, 4, 4, alpha=0.5, gamma=1.5)
+    p = fea.Policy(fea.FEA_POLICY_QLEARN, 4, 4, (1,), alpha=0.5, gamma=0.5, eps=0.0)
+    with pytest.raises(fea.FeaError):
+        p.entry((4, 0, 0), ADD)
+    with pytest.raises(fea.FeaError):
+        p.entry((0, 2, 0), ADD)
+    with pytest.raises(fea.FeaError):
+        p.entry((0, 0, 0), 2)
+    with pytest.raises(fea.FeaError):
+        p.reward(float("nan"))
+    with pytest.raises(fea.FeaError):
+        fea.Cht().build_batch_learned(p, 4, None)                     # Q-learning needs draws
+    p.reward(1.0)                                                     # an empty episode is fine
+    assert p.info() == {"decisions": 0, "episodes": 1, "eps": 0.0, "open": 0}
