@@ -258,6 +258,11 @@ def main():
                     help="also run N decode steps (extend, append, attend over the KV replicas as layers)")
     ap.add_argument("--scheduler", action="store_true",
                     help="also compare first-come-first-served batches with batches formed by the Chunked Hash Tree")
+    ap.add_argument("--batch-sweep", action="store_true",
+                    help="also sweep the batch size on one shared 10K-token prefix vs five of them (Experiment 5's shape)")
+    ap.add_argument("--policies", type=int, default=0, metavar="ROUNDS",
+                    help="also form ROUNDS batches per stop policy (first-come-first-served, rule-based, bandit, "
+                         "Q-learning) from a five-group queue, the measured decode throughput as the reward")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run a plain 1 GiB device-to-device copy three times (known traffic, for counter runs)")
     args = ap.parse_args()
@@ -323,6 +328,17 @@ def main():
             for res in scheduler_comparison(max(50, args.steps // 4), max(10, args.warmup // 2), args.graph):
                 f.write(json.dumps(res) + "\n")
                 log(json.dumps(res))
+    for flag, name, gen in ((args.batch_sweep, "batch_sweep.jsonl", lambda: batch_sweep(max(50, args.steps // 4), max(10, args.warmup // 2))),
+                            (args.policies > 0, "policies.jsonl", lambda: policy_comparison(args.policies))):
+        if flag:
+            os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+            case = None
+            torch.cuda.empty_cache()
+            with open(os.path.join(ROOT, "gpurun_out", name), "w") as f:
+                for res in gen():
+                    f.write(json.dumps(res) + "\n")
+                    f.flush()
+                    log(json.dumps(res))
     if args.suite:
         os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
         with open(os.path.join(ROOT, "gpurun_out", "suite.jsonl"), "w") as f:
@@ -491,6 +507,115 @@ def scheduler_comparison(steps, warm, graph):
         if name.startswith("sched_cht"):
             out["tree_ns_per_request"] = {k: round(v) for k, v in t_ops.items()}
         yield out
+
+
+def batch_sweep(steps, warm):
+    """Decode-attention throughput against the batch size for a homogeneous batch (every request
+    on one 10K-token prefix) and a heterogeneous one (the requests spread over five such
+    prefixes, in arrival order): the shape of the paper's Experiment 5 on a Llama-3-8B layer."""
+    import torch
+    base = W.CONFIGS["c2"]
+    for B in (5, 10, 20, 40, 80, 160, 320, 500):
+        for kind, groups in (("homogeneous", ((B, 10240),)), ("heterogeneous", tuple((B // 5, 10240) for _ in range(5)))):
+            sp = W.Spec(f"sweep_{kind}_{B}", 60 + (B % 50), "bf16", base.num_q_heads, base.num_kv_heads, base.head_dim,
+                        groups, (64, 256), interleave=True)
+            c = Case(sp, label=sp.name)
+            m = c.measure(steps, warm)
+            yield {"workload": sp.name, "B": c.B, "kind": kind, "ms_per_step": m["ms_per_step"],
+                   "tokens_per_s": m["tokens_per_s"], "unique_kv_MB": c.unique_bytes / 1e6,
+                   "logical_kv_MB": c.logical_bytes / 1e6, "kernel_us": m["kernel_us"]}
+            del c
+            torch.cuda.empty_cache()
+
+
+def policy_comparison(rounds, max_batch=256, queue=320, n_groups=5, prefix=5120, ucb_c=0.1, q_every_step=True,
+                      names=("fcfs", "rule_based", "bandit", "q_learning")):
+    """Batch formation with the stop policies of Section 4.3 on a queue fed from five prefix groups
+    (5K-token prefixes, equal shares; the queue is topped up to `queue` waiting requests before
+    every batch).  Each formed batch runs one decode-attention step; its measured tokens/s is the
+    reward of the learned policies.  Reported per policy over the second half of the rounds:
+    tokens/s (summed tokens over summed attention time), mean batch size, prefix groups per batch."""
+    import torch
+    import paper_2605_06046_amd as fea
+    base = W.CONFIGS["c2"]
+    rng = np.random.default_rng(W.SEED_BASE + 77)
+    prefixes = [rng.integers(0, 32000, size=prefix, dtype=np.int32) for _ in range(n_groups)]
+    cols = (prefix + 256) // 16 + 2
+    n_blocks = n_groups * (prefix // 16) + max_batch * 18 + 64
+    params = fea.AttnParams(base.num_q_heads, base.num_kv_heads, base.head_dim, fea.FEA_DTYPE_BF16)
+    R = 4
+    g = torch.Generator(device="cuda"); g.manual_seed(9)
+    kv = [[torch.randn((n_blocks, base.num_kv_heads, 16, base.head_dim), generator=g, device="cuda").to(torch.bfloat16)
+           for _ in range(2)] for _ in range(R)]
+    q = torch.randn((max_batch, base.num_q_heads, base.head_dim), generator=g, device="cuda").to(torch.bfloat16)
+    out = torch.empty_like(q)
+    ws = torch.empty(fea.fea_decode_workspace_bytes(params, max_batch, cols), dtype=torch.uint8, device="cuda")
+    dbt = torch.empty((max_batch, cols), dtype=torch.int32, device="cuda")
+    dl = torch.empty(max_batch, dtype=torch.int32, device="cuda")
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    bins = dict(b_bins=10, w_bins=10, loss_thresholds=(0, 16, 128))
+    rule = dict(small_batch=16, loss_small=1 << 30, loss_limit=8, peers_relax=32, loss_relaxed=64)
+
+    def run(name):
+        prng = np.random.default_rng(W.SEED_BASE + 78)          # every policy sees the same arrivals and draws
+        tree, pool = fea.Cht(), fea.fea_kv_alloc(n_blocks, 16, 0)
+        pol = {"bandit": lambda: fea.Policy(fea.FEA_POLICY_UCB, c=ucb_c, **bins),
+               "q_learning": lambda: fea.Policy(fea.FEA_POLICY_QLEARN, alpha=0.2, gamma=0.9, eps=1.0, eps_min=0.002,
+                                                eps_decay=0.99, reward_every_step=q_every_step, **bins)}.get(name, lambda: None)()
+        toks, grp, order, next_id = {}, {}, [], 0
+        tok_s, t_s, sizes, mixes, form_s = 0.0, 0.0, [], [], 0.0
+        for rnd in range(rounds):
+            while len(order) < queue:
+                gi = int(prng.integers(n_groups))
+                t = np.concatenate([prefixes[gi], prng.integers(0, 32000, size=int(prng.integers(64, 257)), dtype=np.int32)])
+                toks[next_id], grp[next_id] = t, gi
+                tree.insert(next_id, tokens=t)
+                order.append(next_id)
+                next_id += 1
+            t0 = time.perf_counter()
+            if name == "fcfs":
+                ids = order[:max_batch]
+                for rid in ids:
+                    tree.add_to_batch(rid)
+            elif name == "rule_based":
+                ids = tree.build_batch(max_batch, **rule)
+            else:
+                ids = tree.build_batch_learned(pol, max_batch, prng.random((max_batch, 2)))
+            form_s += time.perf_counter() - t0
+            if not ids:                                            # a learned policy may stop at once: nothing runs
+                if pol is not None:
+                    pol.reward(0.0)
+                continue
+            B = len(ids)
+            offs = np.zeros(B + 1, dtype=np.int64)
+            offs[1:] = np.cumsum([len(toks[i]) for i in ids])
+            bt, lens, _, _ = fea.fea_build_block_tables(pool, np.concatenate([toks[i] for i in ids]), offs, cols)
+            dbt[:B].copy_(torch.from_numpy(bt)); dl[:B].copy_(torch.from_numpy(lens))
+            for r in range(R + 1):                                 # one untimed call, then one per KV replica
+                if r == 1:
+                    e0.record()
+                fea.fea_decode_attention(params, q[:B], kv[r % R][0], kv[r % R][1], dbt[:B], dl[:B], out[:B], ws)
+            e1.record()
+            torch.cuda.synchronize()
+            sec = e0.elapsed_time(e1) * 1e-3 / R
+            if pol is not None:
+                pol.reward(B / sec * 1e-6)                         # M tokens/s
+            if rnd >= rounds // 2:
+                tok_s += B; t_s += sec; sizes.append(B); mixes.append(len({grp[i] for i in ids}))
+            for row, rid in zip(bt, ids):
+                fea.fea_release(pool, row[row >= 0])
+                tree.finish(rid)
+                del toks[rid], grp[rid]
+            done = set(ids)
+            order = [i for i in order if i not in done]
+        return {"workload": f"policy_{name}", "rounds": rounds, "max_batch": max_batch, "queue": queue,
+                "tokens_per_s": tok_s / max(t_s, 1e-12), "mean_batch": float(np.mean(sizes)) if sizes else 0.0,
+                "prefix_groups_per_batch": float(np.mean(mixes)) if mixes else 0.0,
+                "formation_us_per_batch": form_s / rounds * 1e6,
+                "policy": pol.info() if pol is not None else None}
+
+    for name in names:
+        yield run(name)
 
 
 if __name__ == "__main__":
