@@ -404,6 +404,35 @@ def run_suite(args):
     yield {"workload": "H1_eight_homogeneous_launches_of_32", "B": B, "ms_per_step": total_ms,
            "ms_per_step_warm": total_ms_warm, "tokens_per_s": B / (total_ms * 1e-3)}
     yield from scheduler_comparison(steps, warm, args.graph)
+    yield from device_hashing()
+
+
+def device_hashing(reps=50):
+    """Chunk hashes of a whole batch on the device (the chunk-parallel formulation) against the
+    host function, on the token streams of c2 (64 long requests) and c5 (512 requests)."""
+    import torch
+    import paper_2605_06046_amd as fea
+    for name in ("c2", "c5"):
+        wl = W.generate(W.CONFIGS[name], with_kv=False)
+        hoff = np.zeros(len(wl.tok_offsets), dtype=np.int64)
+        hoff[1:] = np.cumsum(-(-np.diff(wl.tok_offsets) // 16))
+        d_tok, d_toff, d_hoff = (torch.from_numpy(x).cuda() for x in (wl.tokens, wl.tok_offsets, hoff))
+        d_h = torch.zeros(int(hoff[-1]), dtype=torch.int64, device="cuda")
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for r in range(reps + 5):
+            if r == 5:
+                e0.record()
+            fea.fea_chunk_hashes_device(d_tok, d_toff, d_hoff, d_h)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / reps
+        t0 = time.perf_counter()
+        host = [fea.fea_chunk_hashes(wl.request_tokens(i)) for i in range(wl.spec.batch)]
+        host_us = (time.perf_counter() - t0) * 1e6
+        same = bool(np.array_equal(np.concatenate(host), d_h.cpu().numpy().view(np.uint64)))
+        yield {"workload": f"device_chunk_hashes_{name}", "B": wl.spec.batch, "tokens": int(len(wl.tokens)),
+               "us_per_call": us, "tokens_per_s": len(wl.tokens) / (us * 1e-6), "host_us": host_us,
+               "host_tokens_per_s": len(wl.tokens) / (host_us * 1e-6), "equal_to_host": same}
 
 
 def decode_loop(n_steps, layers=None):

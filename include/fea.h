@@ -111,6 +111,42 @@ int32_t fea_kv_stats(const fea_kv_pool* pool, uint32_t* num_blocks, uint32_t* fr
 int32_t fea_chunk_hashes(const int32_t* tokens /* HOST [T] */, int64_t T,
                          uint64_t* hashes /* HOST [ceil(T/16)] */);
 
+/* The sequential formulation of the same vector (appendix "Prefix Hash
+ * Computation", Algorithm 1): one incremental xxHash-64 state is fed the tokens
+ * in order (each as 4 little-endian bytes) and digested after every 16th token
+ * and after the last, so h_c = XXH64(first min(16c, T) tokens, seed).  Same
+ * count, same prefix-consistency property, different values than
+ * fea_chunk_hashes (the paper notes the two formulations differ in value).
+ * Errors: as fea_chunk_hashes. */
+int32_t fea_chunk_hashes_xxh64(const int32_t* tokens /* HOST [T] */, int64_t T, uint64_t seed,
+                               uint64_t* hashes /* HOST [ceil(T/16)] */);
+
+/* fea_chunk_hashes for a whole batch on the DEVICE (asynchronous on hip_stream;
+ * Algorithm 2 as it is meant to run: the chunks of all requests hashed in
+ * parallel, then one short chain per request).  tokens [n_tokens], tok_offsets
+ * [B+1] and hash_offsets [B+1] are DEVICE arrays; request i's ceil(T_i/16) values
+ * go to hashes[hash_offsets[i] ...] (DEVICE [n_hashes]), bit-identical to
+ * fea_chunk_hashes.  A request whose offsets are negative, descending, beyond
+ * n_tokens, or whose values would not fit below n_hashes is skipped (nothing is
+ * written for it; the device cannot report an error without a synchronisation).
+ * Never allocates or synchronises.
+ * Errors: FEA_EINVAL for negative sizes or NULL pointers; FEA_EHIP if the launch
+ * fails. */
+int32_t fea_chunk_hashes_device(const int32_t* tokens /* DEVICE */, int64_t n_tokens,
+                                const int64_t* tok_offsets /* DEVICE [B+1] */, int32_t B,
+                                const int64_t* hash_offsets /* DEVICE [B+1] */,
+                                uint64_t* hashes /* DEVICE [n_hashes] */, int64_t n_hashes, void* hip_stream);
+
+/* Which formulation a pool (fea_build_block_tables) or a tree (fea_cht_insert)
+ * hashes with: FEA_HASH_CHAINED (fea_chunk_hashes, the default; seed ignored) or
+ * FEA_HASH_XXH64.  Block tables do not depend on the choice (aliasing is verified
+ * on tokens); the hash vectors handed back do.
+ * Errors: FEA_EINVAL for NULL, an unknown kind, a pool that already holds
+ * registered prefixes or a tree that already holds requests. */
+enum { FEA_HASH_CHAINED = 0, FEA_HASH_XXH64 = 1 };
+int32_t fea_kv_set_hash(fea_kv_pool* pool, int32_t kind, uint64_t seed);
+/* fea_cht_set_hash: declared with the tree below. */
+
 /* ------------------------------------------------------------------------
  * Block tables for a batch, with prefix aliasing (HOST in, HOST out).
  *
@@ -262,6 +298,7 @@ typedef struct fea_cht fea_cht;
 /* chunk_tokens must be FEA_BLOCK_TOKENS (the chunk size of fea_chunk_hashes). */
 int32_t fea_cht_create(int32_t chunk_tokens, fea_cht** out);
 void    fea_cht_destroy(fea_cht* t);
+int32_t fea_cht_set_hash(fea_cht* tree, int32_t kind, uint64_t seed);   /* see fea_kv_set_hash */
 
 /* Insert: register a request as waiting, from its tokens (hashed here) or from a
  * ready hash vector of n values. */

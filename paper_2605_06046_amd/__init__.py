@@ -11,5 +11,6 @@ from .fea import (  # noqa: F401
     fea_decode_workspace_bytes, fea_kv_alloc, fea_kv_free, fea_kv_stats, fea_release,
     fea_validate_block_tables, fea_profile_enable, fea_profile_read, library_path, load_library,
     Cht, StopPolicy, fea_kv_extend, fea_kv_append, Policy, PolicyParams,
-    FEA_ADD, FEA_STOP, FEA_POLICY_UCB, FEA_POLICY_QLEARN,
+    FEA_ADD, FEA_STOP, FEA_POLICY_UCB, FEA_POLICY_QLEARN, FEA_HASH_CHAINED, FEA_HASH_XXH64,
+    fea_chunk_hashes_xxh64, fea_kv_set_hash, fea_chunk_hashes_device,
 )

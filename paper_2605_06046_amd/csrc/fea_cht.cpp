@@ -60,6 +60,8 @@ struct fea_cht {
     int64_t n_waiting = 0;
     int32_t tip_level = 0;
     uint64_t tip_hash = 0;
+    int32_t hash_kind = FEA_HASH_CHAINED;
+    uint64_t hash_seed = 0;
     bool cache_valid = false;
     bool cache_found = false;
     int64_t c_id = 0;
@@ -108,6 +110,15 @@ int32_t fea_cht_create(int32_t chunk_tokens, fea_cht** out) {
 
 void fea_cht_destroy(fea_cht* t) { delete t; }
 
+int32_t fea_cht_set_hash(fea_cht* t, int32_t kind, uint64_t seed) {
+    if (!t) return fail(FEA_EINVAL, "fea_cht_set_hash: tree is NULL");
+    if (kind != FEA_HASH_CHAINED && kind != FEA_HASH_XXH64) return fail(FEA_EINVAL, "fea_cht_set_hash: unknown kind %d", kind);
+    if (!t->req.empty()) return fail(FEA_EINVAL, "fea_cht_set_hash: requests are present; set the hash on an empty tree");
+    t->hash_kind = kind;
+    t->hash_seed = seed;
+    return FEA_OK;
+}
+
 int32_t fea_cht_insert_hashes(fea_cht* t, int64_t id, const uint64_t* hashes, int32_t n) {
     if (!t || (n > 0 && !hashes) || n < 0) return fail(FEA_EINVAL, "fea_cht_insert: bad argument");
     if (t->req.count(id)) return fail(FEA_EINVAL, "fea_cht_insert: request %lld is already present", (long long)id);
@@ -129,7 +140,8 @@ int32_t fea_cht_insert(fea_cht* t, int64_t id, const int32_t* tokens, int64_t n_
     if (!t || n_tokens < 0 || (n_tokens > 0 && !tokens)) return fail(FEA_EINVAL, "fea_cht_insert: bad argument");
     if (n_tokens > (int64_t)0x7FFFFFFF * t->K) return fail(FEA_EINVAL, "fea_cht_insert: sequence too long");
     std::vector<uint64_t> H((size_t)((n_tokens + t->K - 1) / t->K));
-    const int32_t rc = fea_chunk_hashes(tokens, n_tokens, H.data());
+    const int32_t rc = t->hash_kind == FEA_HASH_XXH64 ? fea_chunk_hashes_xxh64(tokens, n_tokens, t->hash_seed, H.data())
+                                                      : fea_chunk_hashes(tokens, n_tokens, H.data());
     if (rc != FEA_OK) return rc;
     return fea_cht_insert_hashes(t, id, H.data(), (int32_t)H.size());
 }

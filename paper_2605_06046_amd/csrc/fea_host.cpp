@@ -74,6 +74,66 @@ static void chunk_hashes(const int32_t* tok, int64_t T, uint64_t* H) {
     }
 }
 
+// ---- the sequential formulation: one running XXH64 state, digested at every
+// chunk boundary (appendix "Prefix Hash Computation", Algorithm 1).  Tokens enter
+// as 4-byte little-endian words.  A full chunk is 64 bytes = two 32-byte stripes,
+// so the stripe buffer is empty at every boundary but the last.
+static constexpr uint64_t kP1 = 0x9E3779B185EBCA87ull, kP2 = 0xC2B2AE3D27D4EB4Full, kP3 = 0x165667B19E3779F9ull,
+                          kP4 = 0x85EBCA77C2B2AE63ull, kP5 = 0x27D4EB2F165667C5ull;
+static inline uint64_t rotl64(uint64_t x, int r) { return (x << r) | (x >> (64 - r)); }
+static inline uint64_t xround(uint64_t acc, uint64_t lane) { return rotl64(acc + lane * kP2, 31) * kP1; }
+static inline uint64_t xmerge(uint64_t h, uint64_t v) { return (h ^ xround(0, v)) * kP1 + kP4; }
+static inline uint64_t word64(const int32_t* t) { return (uint64_t)(uint32_t)t[0] | ((uint64_t)(uint32_t)t[1] << 32); }
+
+struct Xxh64Stream {
+    uint64_t v[4], seed;
+    int64_t stripes = 0;                       // 32-byte stripes consumed
+    explicit Xxh64Stream(uint64_t sd) : seed(sd) {
+        v[0] = sd + kP1 + kP2; v[1] = sd + kP2; v[2] = sd; v[3] = sd - kP1;
+    }
+    void stripe(const int32_t* t) {            // 8 tokens
+        for (int i = 0; i < 4; ++i) v[i] = xround(v[i], word64(t + 2 * i));
+        ++stripes;
+    }
+    // Digest after the consumed stripes plus `n` (< 8) further tokens at `t`.
+    uint64_t digest(const int32_t* t, int n) const {
+        uint64_t h;
+        if (stripes > 0) {
+            h = rotl64(v[0], 1) + rotl64(v[1], 7) + rotl64(v[2], 12) + rotl64(v[3], 18);
+            for (int i = 0; i < 4; ++i) h = xmerge(h, v[i]);
+        } else {
+            h = seed + kP5;
+        }
+        h += (uint64_t)(stripes * 32 + 4 * n);
+        int j = 0;
+        for (; j + 2 <= n; j += 2) h = rotl64(h ^ xround(0, word64(t + j)), 27) * kP1 + kP4;
+        if (j < n) h = rotl64(h ^ ((uint64_t)(uint32_t)t[j] * kP1), 23) * kP2 + kP3;
+        h ^= h >> 33; h *= kP2; h ^= h >> 29; h *= kP3; h ^= h >> 32;
+        return h;
+    }
+};
+
+static void chunk_hashes_xxh64(const int32_t* tok, int64_t T, uint64_t seed, uint64_t* H) {
+    Xxh64Stream s(seed);
+    const int64_t full = T / kK;
+    for (int64_t c = 0; c < full; ++c) {
+        s.stripe(tok + c * kK);
+        s.stripe(tok + c * kK + 8);
+        H[c] = s.digest(nullptr, 0);
+    }
+    int rest = (int)(T - full * kK);
+    if (rest > 0) {
+        const int32_t* t = tok + full * kK;
+        if (rest >= 8) { s.stripe(t); t += 8; rest -= 8; }
+        H[full] = s.digest(t, rest);
+    }
+}
+
+static void chunk_hashes_of_kind(int32_t kind, uint64_t seed, const int32_t* tok, int64_t T, uint64_t* H) {
+    if (kind == FEA_HASH_XXH64) chunk_hashes_xxh64(tok, T, seed, H);
+    else chunk_hashes(tok, T, H);
+}
+
 struct BlockMeta {
     int32_t refcount = 0;
     int32_t parent = -1;      // block of the previous column (-1 at level 0)
@@ -101,6 +161,8 @@ struct fea_kv_pool {
     // than one entry only after a 64-bit collision between different prefixes.
     std::unordered_map<fea::Key, std::vector<int32_t>, fea::KeyHash> index;
     uint32_t collisions = 0;
+    int32_t hash_kind = FEA_HASH_CHAINED;
+    uint64_t hash_seed = 0;
 
     void unindex(int32_t b) {
         fea::BlockMeta& m = meta[b];
@@ -175,6 +237,24 @@ int32_t fea_chunk_hashes(const int32_t* tokens, int64_t T, uint64_t* hashes) {
     return FEA_OK;
 }
 
+int32_t fea_chunk_hashes_xxh64(const int32_t* tokens, int64_t T, uint64_t seed, uint64_t* hashes) {
+    if (T < 0) return fail(FEA_EINVAL, "fea_chunk_hashes_xxh64: T=%lld is negative", (long long)T);
+    if (T == 0) return FEA_OK;
+    if (!tokens || !hashes) return fail(FEA_EINVAL, "fea_chunk_hashes_xxh64: NULL pointer");
+    chunk_hashes_xxh64(tokens, T, seed, hashes);
+    return FEA_OK;
+}
+
+int32_t fea_kv_set_hash(fea_kv_pool* pool, int32_t kind, uint64_t seed) {
+    if (!pool) return fail(FEA_EINVAL, "fea_kv_set_hash: pool is NULL");
+    if (kind != FEA_HASH_CHAINED && kind != FEA_HASH_XXH64) return fail(FEA_EINVAL, "fea_kv_set_hash: unknown kind %d", kind);
+    if (!pool->index.empty())
+        return fail(FEA_EINVAL, "fea_kv_set_hash: the pool holds registered prefixes; set the hash before the first table is built");
+    pool->hash_kind = kind;
+    pool->hash_seed = seed;
+    return FEA_OK;
+}
+
 int32_t fea_build_block_tables(fea_kv_pool* pool, const int32_t* tokens, const int64_t* tok_offsets, int32_t B,
                                int32_t max_blocks_per_seq, int32_t* block_tables, int32_t* seq_lens,
                                uint64_t* hashes, int64_t* hash_offsets) {
@@ -212,7 +292,7 @@ int32_t fea_build_block_tables(fea_kv_pool* pool, const int32_t* tokens, const i
             const int64_t T = tok_offsets[i + 1] - tok_offsets[i];
             const int64_t C = (T + kK - 1) / kK;
             uint64_t* H = hs.data() + hpos;
-            chunk_hashes(tok, T, H);                                    // a1
+            chunk_hashes_of_kind(pool->hash_kind, pool->hash_seed, tok, T, H);   // a1
             int32_t parent = -1;
             for (int64_t c = 0; c < C; ++c) {                           // a2
                 const bool full = (c + 1) * kK <= T;

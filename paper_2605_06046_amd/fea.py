@@ -46,6 +46,7 @@ class StopPolicy(C.Structure):
 
 
 FEA_ADD, FEA_STOP = 0, 1
+FEA_HASH_CHAINED, FEA_HASH_XXH64 = 0, 1
 FEA_POLICY_UCB, FEA_POLICY_QLEARN = 1, 2
 
 
@@ -81,6 +82,10 @@ def load_library() -> C.CDLL:
         "fea_kv_free": (i32, [vp]),
         "fea_kv_stats": (i32, [vp, C.POINTER(u32), C.POINTER(u32), C.POINTER(u32), vp]),
         "fea_chunk_hashes": (i32, [vp, i64, vp]),
+        "fea_chunk_hashes_xxh64": (i32, [vp, i64, u64, vp]),
+        "fea_kv_set_hash": (i32, [vp, i32, u64]),
+        "fea_chunk_hashes_device": (i32, [vp, i64, vp, i32, vp, vp, i64, vp]),
+        "fea_cht_set_hash": (i32, [vp, i32, u64]),
         "fea_build_block_tables": (i32, [vp, vp, vp, i32, i32, vp, vp, vp, vp]),
         "fea_release": (i32, [vp, vp, i32]),
         "fea_validate_block_tables": (i32, [vp, i32, vp, i32, u32]),
@@ -170,6 +175,17 @@ def fea_chunk_hashes(tokens: np.ndarray) -> np.ndarray:
     return out
 
 
+def fea_chunk_hashes_xxh64(tokens: np.ndarray, seed: int = 0) -> np.ndarray:
+    tokens = np.ascontiguousarray(tokens, dtype=np.int32)
+    out = np.zeros(-(-len(tokens) // 16), dtype=np.uint64)
+    _check(load_library().fea_chunk_hashes_xxh64(_np_ptr(tokens), len(tokens), seed, _np_ptr(out)))
+    return out
+
+
+def fea_kv_set_hash(pool: KVPool, kind: int, seed: int = 0) -> None:
+    _check(load_library().fea_kv_set_hash(pool.handle, kind, seed))
+
+
 def fea_build_block_tables(pool: KVPool, tokens: np.ndarray, tok_offsets: np.ndarray,
                            max_blocks_per_seq: int, want_hashes: bool = False):
     """Returns (block_tables[B, max_blocks] int32, seq_lens[B] int32, hashes, hash_offsets)."""
@@ -238,6 +254,22 @@ def fea_decode_attention(params: AttnParams, q, k_cache, v_cache, block_tables, 
         workspace.numel() * workspace.element_size(), C.c_void_p(st.cuda_stream)))
 
 
+def fea_chunk_hashes_device(tokens, tok_offsets, hash_offsets, hashes, stream=None) -> None:
+    """Contiguous GPU tensors: tokens int32 [n], tok_offsets and hash_offsets int64 [B+1], hashes int64 [m]
+    (the 64-bit values, to be viewed as unsigned).  Asynchronous."""
+    import torch
+    if tokens.dtype != torch.int32 or tok_offsets.dtype != torch.int64 or hash_offsets.dtype != torch.int64 \
+            or hashes.dtype != torch.int64 or tok_offsets.numel() != hash_offsets.numel():
+        raise ValueError("tokens int32; tok_offsets, hash_offsets (equal lengths) and hashes int64")
+    for t in (tokens, tok_offsets, hash_offsets, hashes):
+        if not t.is_cuda or not t.is_contiguous():
+            raise ValueError("all arguments must be contiguous GPU tensors")
+    st = stream if stream is not None else torch.cuda.current_stream()
+    _check(load_library().fea_chunk_hashes_device(_dev_ptr(tokens), tokens.numel(), _dev_ptr(tok_offsets),
+                                                  tok_offsets.numel() - 1, _dev_ptr(hash_offsets), _dev_ptr(hashes),
+                                                  hashes.numel(), C.c_void_p(st.cuda_stream)))
+
+
 def fea_decode_plan_info(workspace, stream=None) -> dict:
     import torch
     st = stream if stream is not None else torch.cuda.current_stream()
@@ -284,6 +316,9 @@ class Cht:
             self._h = None
 
     __del__ = close
+
+    def set_hash(self, kind: int, seed: int = 0):
+        _check(self._lib.fea_cht_set_hash(self._h, kind, seed))
 
     def insert(self, rid: int, tokens=None, hash_vector=None):
         if hash_vector is not None:

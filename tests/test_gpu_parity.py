@@ -209,3 +209,49 @@ def test_profiling_events_bracket_each_kernel():
                     assert ms[k] == 0.0, (which, c, ms)
         fea_profile_enable(0, -1)
         assert torch.equal(out, ref)                     # measuring does not change the result
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("B,prefix,Hq,Hkv", [(300, 320, 32, 8), (500, 96, 32, 8), (130, 512, 64, 8)])
+def test_wide_prefix_groups(B, prefix, Hq, Hkv):
+    """One prefix group far wider than a workgroup's row tiles (the paper's large homogeneous
+    batches, Experiment 5): every request's rows against the oracle."""
+    spec = W.Spec("wide", 21, "bf16", Hq, Hkv, 128, ((B, prefix),), (1, 70), interleave=True)
+    wl = W.generate(spec)
+    out, bt, lens, info = run_workload(wl)
+    assert info["groups"] == 1 and info["grouped_requests"] == B and info["overflow"] == 0
+    assert_close(out, oracle_for(wl, bt, lens), "bf16", what=f"wide group B={B}")
+
+
+@pytest.mark.gpu
+def test_device_chunk_hashes_match_the_oracle():
+    """Algorithm 2 on the device, bit for bit against the oracle's hash vectors: ragged lengths,
+    empty requests, a request longer than one staging tile, unaligned starts."""
+    import torch
+    from oracle.hashing import chunk_hashes
+    from paper_2605_06046_amd import fea_chunk_hashes_device
+    rng = np.random.default_rng(17)
+    lens = [0, 1, 15, 16, 17, 31, 32, 33, 100, 0, 4673, 16 * 2048, 16 * 2048 + 1, 16 * 2048 * 2 + 5, 3]
+    seqs = [rng.integers(-2 ** 31, 2 ** 31, size=n, dtype=np.int64).astype(np.int32) for n in lens]
+    toks = np.concatenate(seqs)
+    toff = np.zeros(len(seqs) + 1, dtype=np.int64)
+    toff[1:] = np.cumsum(lens)
+    hoff = np.zeros(len(seqs) + 1, dtype=np.int64)
+    hoff[1:] = np.cumsum([-(-n // 16) for n in lens])
+    sentinel = 0x5A5A5A5A5A5A5A5A
+    hashes = torch.full((int(hoff[-1]) + 3,), sentinel, dtype=torch.int64, device="cuda")
+    fea_chunk_hashes_device(torch.from_numpy(toks).cuda(), torch.from_numpy(toff).cuda(), torch.from_numpy(hoff).cuda(), hashes)
+    torch.cuda.synchronize()
+    got = hashes.cpu().numpy().view(np.uint64)
+    for i, s in enumerate(seqs):
+        assert got[hoff[i]:hoff[i + 1]].tolist() == chunk_hashes(s), i
+    assert (got[hoff[-1]:] == sentinel).all()                  # nothing written past the last request
+    # a row that would not fit is skipped, the others are still written
+    short = torch.full((int(hoff[-2]),), sentinel, dtype=torch.int64, device="cuda")
+    fea_chunk_hashes_device(torch.from_numpy(toks).cuda(), torch.from_numpy(toff).cuda(), torch.from_numpy(hoff).cuda(), short)
+    torch.cuda.synchronize()
+    got2 = short.cpu().numpy().view(np.uint64)
+    assert np.array_equal(got2, got[:hoff[-2]])
+    # the same values as the host function of the library
+    from paper_2605_06046_amd import fea_chunk_hashes
+    assert got[hoff[10]:hoff[11]].tolist() == fea_chunk_hashes(seqs[10]).tolist()

@@ -172,3 +172,58 @@ def test_workspace_size_and_param_checks():
                 AttnParams(32, 8, 128, FEA_DTYPE_BF16, scale=-1.0), AttnParams(32, 8, 32, FEA_DTYPE_BF16)):
         with pytest.raises(FeaError):
             fea_decode_workspace_bytes(bad, 4, 20)
+
+
+# ---- the sequential formulation (Algorithm 1, XXH64) as the pool's and the tree's hash
+
+@pytest.mark.parametrize("T", [0, 1, 7, 8, 9, 15, 16, 17, 23, 24, 25, 31, 32, 33, 63, 64, 65, 80, 1000, 4673])
+@pytest.mark.parametrize("seed", [0, 0xFEA7FEA7FEA7])
+def test_xxh64_chunk_hashes_match_oracle(T, seed):
+    from oracle.hashing import chunk_hashes_xxh64
+    from paper_2605_06046_amd import fea_chunk_hashes_xxh64
+    rng = np.random.default_rng(T + 1)
+    toks = rng.integers(-2 ** 31, 2 ** 31, size=T, dtype=np.int64).astype(np.int32)
+    assert fea_chunk_hashes_xxh64(toks, seed).tolist() == chunk_hashes_xxh64(toks, 16, seed)
+
+
+@pytest.mark.parametrize("name", ["c1", "c3"])
+def test_tables_do_not_depend_on_the_hash_formulation(name):
+    from oracle.hashing import chunk_hashes_xxh64
+    from paper_2605_06046_amd import FEA_HASH_CHAINED, FEA_HASH_XXH64, fea_kv_set_hash
+    wl = W.generate(W.scaled(W.CONFIGS[name], 1, 4) if name != "c1" else W.CONFIGS[name], with_kv=False)
+    pool = fea_kv_alloc(wl.num_blocks, 16, wl.perm_seed)
+    fea_kv_set_hash(pool, FEA_HASH_XXH64, 5)
+    bt, lens, hs, hoff = fea_build_block_tables(pool, wl.tokens, wl.tok_offsets, wl.max_blocks_per_seq, True)
+    obt, olens, orc = build_block_tables(_seqs(wl), wl.num_blocks, wl.perm_seed, wl.max_blocks_per_seq)
+    assert np.array_equal(bt, obt) and np.array_equal(lens, olens)
+    assert np.array_equal(fea_kv_stats(pool)[3], orc)
+    for i in sorted({0, wl.spec.batch - 1}):
+        assert hs[hoff[i]:hoff[i + 1]].tolist() == chunk_hashes_xxh64(wl.request_tokens(i), 16, 5)
+    with pytest.raises(FeaError):
+        fea_kv_set_hash(pool, FEA_HASH_CHAINED)          # prefixes are registered: too late
+    with pytest.raises(FeaError):
+        fea_kv_set_hash(fea_kv_alloc(4), 9)
+
+
+def test_tree_decisions_do_not_depend_on_the_hash_formulation():
+    from paper_2605_06046_amd import Cht, FEA_HASH_XXH64
+    rng = np.random.default_rng(8)
+    stems = [rng.integers(0, 1000, size=n, dtype=np.int32) for n in (64, 200, 330)]
+    reqs = [np.concatenate([stems[i % 3][:int(rng.choice([32, 64, 999]))], rng.integers(0, 1000, size=int(rng.integers(1, 50)), dtype=np.int32)])
+            for i in range(40)]
+    a, b = Cht(), Cht()
+    b.set_hash(FEA_HASH_XXH64, 3)
+    for i, r in enumerate(reqs):
+        a.insert(i, tokens=r)
+        b.insert(i, tokens=r)
+    with pytest.raises(FeaError):
+        b.set_hash(FEA_HASH_XXH64, 4)
+    pol = dict(small_batch=2, loss_small=1 << 30, loss_limit=1, peers_relax=4, loss_relaxed=3)
+    while a.stats()["waiting"]:
+        fa, fb = a.find_best(), b.find_best()
+        assert fa == fb
+        ia, ib = a.build_batch(8, **pol), b.build_batch(8, **pol)
+        assert ia == ib and ia
+        for rid in ia:
+            a.finish(rid)
+            b.finish(rid)
