@@ -111,11 +111,12 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
         struct { int keys[kHashSlots]; int vals[kHashSlots]; } h;                     // leader finding only
         struct { int run[kGroupReqMax]; int cnt[kGroupReqMax]; int moff[kGroupReqMax];
                  int gseg[kGroupMax]; } c;                                            // afterwards
+        unsigned short r1[kGroupReqMax];                                              // between the two (nested runs)
     } u;
     __shared__ short s_lead[kGroupReqMax];      // request ids fit 16 bits (kGroupReqMax <= 32767)
     __shared__ int s_len[kGroupReqMax];
     __shared__ union {
-        int lcp[kGroupReqMax];                                  // until the group runs are known
+        struct { int lcp[kGroupReqMax]; short lead2[kGroupReqMax]; } x;   // until the group runs are known
         struct { int npc[kGroupMax]; int ibase[kGroupMax]; int rbase[kGroupMax]; } g;   // then the cut of each group
     } v;
     __shared__ union {
@@ -123,7 +124,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
         unsigned short glist[kGroupMax];        // then the list of viable leaders
     } w;
     __shared__ int s_tmp[64];
-    __shared__ int s_ngroups, s_ngrouped, s_shared_blocks, s_nflw;
+    __shared__ int s_ngroups, s_ngrouped, s_shared_blocks, s_nflw, s_nest;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -181,18 +182,20 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
                 if (lead != i) w.flw[atomicAdd(&s_nflw, 1)] = (unsigned short)i;
             }
             s_lead[i] = (short)lead;
-            v.lcp[i] = lcp;
+            v.x.lcp[i] = lcp;
         }
     }
     __syncthreads();   // the hash table is dead from here on; its memory becomes run/cnt/moff/...
-    for (int i = tid; i < nG; i += kPlanThreads) { u.c.run[i] = INT_MAX; u.c.cnt[i] = 0; u.c.moff[i] = 0; }
+    auto reset_groups = [&](int moff0) {
+        for (int i = tid; i < nG; i += kPlanThreads) { u.c.run[i] = INT_MAX; u.c.cnt[i] = 0; u.c.moff[i] = moff0; }
+    };
+    reset_groups(0);
 
     // ---- longest common run of block ids with the leader's row.  All (follower,
     // column group) pairs are spread flat over the threads, eight at a time so that
     // their loads are in flight together; a mismatch lowers the follower's run with
-    // an LDS atomic.
-    {
-        const int nflw = s_nflw;
+    // an LDS atomic.  Columns below from(i) are known to agree and are not read.
+    auto lcp_pass = [&](int nflw, const short* lead_of, auto&& from) {
         const bool vec = (a.stride % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.bt) & 15) == 0);
         const int cpe = vec ? 4 : 1;                       // columns per element
         const int epr = cdiv(a.stride, cpe);               // elements per row
@@ -209,10 +212,10 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
                 if (e < total) {
                     const int f = by_epr.div(e);
                     const int i = w.flw[f];
-                    const int lead = s_lead[i];
+                    const int lead = lead_of[i];
                     const int c = (e - f * epr) * cpe;
                     const int cp = min(s_len[i], s_len[lead]) / kBlock;   // the starting value of lcp[i]
-                    if (c < cp) {
+                    if (c < cp && c + cpe > from(i)) {
                         who[q] = i; col[q] = c; cap[q] = cp;
                         const int32_t* ri = a.bt + (size_t)i * a.stride + c;
                         const int32_t* rl = a.bt + (size_t)lead * a.stride + c;
@@ -234,12 +237,152 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
                     if (xs[q].z != ys[q].z) first = col[q] + 2;
                     if (xs[q].y != ys[q].y) first = col[q] + 1;
                     if (xs[q].x != ys[q].x) first = col[q];
-                    if (first < cap[q]) atomicMin(&v.lcp[who[q]], first);
+                    if (first < cap[q]) atomicMin(&v.x.lcp[who[q]], first);
                 }
             }
         }
-    }
+    };
+    lcp_pass(s_nflw, s_lead, [](int) { return 0; });
     __syncthreads();
+
+    // A 32-token tile costs a wave more the more query rows ride on it: weights in
+    // sixteenths of a 16-row tile's sweep.
+    const int w32 = a.tune.weights & 255, w64 = (a.tune.weights >> 8) & 255;
+    auto tile_weight = [&](int rows) { return rows <= 16 ? 16 : (rows <= 32 ? w32 : w64); };
+    const FastDiv by_mpt(a.mpt);
+
+    // ---- nested prefixes.  Members of a group may go on sharing blocks past the group's
+    // run (a common system prompt, then a few conversations: the radix patterns of
+    // Section 3).  A second round finds, inside every group, the members that carry the
+    // same block in the first column after the run, and their common run from there.
+    // Such a subgroup becomes a group of its own (run measured from column 0, so it sweeps
+    // the outer run again) when that saves more sweep cost than it adds, by the tile weights;
+    // the members left behind keep the outer run under the smallest index among them.
+    //
+    // A follower agrees with its leader over lcp >= run columns.  If lcp > run it is in the
+    // leader's subgroup and its run there is lcp itself; if lcp == run, the block that
+    // tells its subgroup sits in column lcp - which is known before the run is, so that
+    // load is under way while the runs are reduced.
+    {
+        constexpr int kPer = kGroupReqMax / kPlanThreads;
+        int r1[kPer], lead1[kPer], lcp1[kPer];
+        bool in[kPer];
+#pragma unroll
+        for (int k = 0; k < kPer; ++k) {           // round-one runs and sizes
+            const int i = tid + k * kPlanThreads;
+            lead1[k] = i < nG ? (int)s_lead[i] : -1;
+            lcp1[k] = 0;
+            my_key[k] = -1;
+            if (lead1[k] >= 0) {
+                lcp1[k] = v.x.lcp[i];
+                if (lead1[k] != i && lcp1[k] < s_len[i] / kBlock) my_key[k] = a.bt[(size_t)i * a.stride + lcp1[k]];
+                atomicMin(&u.c.run[lead1[k]], lcp1[k]);
+                atomicAdd(&u.c.cnt[lead1[k]], 1);
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < kPer; ++k) {
+            in[k] = lead1[k] >= 0 && u.c.cnt[lead1[k]] >= 2 && u.c.run[lead1[k]] >= a.tune.min_run;
+            r1[k] = in[k] ? u.c.run[lead1[k]] : 0;
+            if (!in[k] || lcp1[k] > r1[k]) my_key[k] = -1;      // only the members that leave the leader at the run
+        }
+        __syncthreads();                           // run/cnt are read: their memory is the hash table again
+        for (int s = tid; s < kHashSlots; s += kPlanThreads) { u.h.keys[s] = -1; u.h.vals[s] = INT_MAX; }
+        if (tid == 0) { s_nflw = 0; s_nest = 0; }
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < kPer; ++k) {
+            const int key = my_key[k];
+            if (key >= 0) {
+                uint32_t s = slot_of(key);
+                for (;;) {
+                    const int old = atomicCAS(&u.h.keys[s], -1, key);
+                    if (old == -1 || old == key) { atomicMin(&u.h.vals[s], tid + k * kPlanThreads); break; }
+                    s = (s + 1) & (kHashSlots - 1);
+                }
+            }
+        }
+        __syncthreads();
+        int lead2[kPer];
+#pragma unroll
+        for (int k = 0; k < kPer; ++k) {
+            const int i = tid + k * kPlanThreads;
+            lead2[k] = -1;
+            const int key = my_key[k];
+            if (key >= 0) {
+                uint32_t s = slot_of(key);
+                while (u.h.keys[s] != key) s = (s + 1) & (kHashSlots - 1);
+                const int cand = u.h.vals[s];
+                lead2[k] = s_lead[cand] == lead1[k] ? cand : i;     // only within the same outer group
+                v.x.lcp[i] = min(s_len[i], s_len[lead2[k]]) / kBlock;
+                if (lead2[k] != i) w.flw[atomicAdd(&s_nflw, 1)] = (unsigned short)i;
+            } else if (in[k] && (lead1[k] == i || lcp1[k] > r1[k])) {
+                lead2[k] = lead1[k];                                // the leader's own subgroup: runs are known
+                if (lead1[k] != i) atomicAdd(&s_nest, 1);
+            }
+            if (i < nG) v.x.lead2[i] = (short)lead2[k];
+        }
+        __syncthreads();                           // the hash table is dead again
+        const int nflw2 = s_nflw;
+        if (nflw2 + s_nest > 0) {                  // uniform
+            if (nflw2 > 0) {
+#pragma unroll
+                for (int k = 0; k < kPer; ++k) {
+                    const int i = tid + k * kPlanThreads;
+                    if (i < nG) u.r1[i] = (unsigned short)min(r1[k], 65535);
+                }
+                __syncthreads();
+                lcp_pass(nflw2, v.x.lead2, [&](int i) { return (int)u.r1[i]; });
+                __syncthreads();
+            }
+            reset_groups(INT_MAX);
+            __syncthreads();
+#pragma unroll
+            for (int k = 0; k < kPer; ++k) {       // runs and sizes of the subgroups
+                const int i = tid + k * kPlanThreads;
+                if (lead2[k] >= 0) { atomicMin(&u.c.run[lead2[k]], v.x.lcp[i]); atomicAdd(&u.c.cnt[lead2[k]], 1); }
+            }
+            __syncthreads();
+            bool adopt[kPer];
+            int run2[kPer];
+#pragma unroll
+            for (int k = 0; k < kPer; ++k) {
+                adopt[k] = false;
+                run2[k] = 0;
+                if (lead2[k] >= 0) {
+                    const int c2 = u.c.cnt[lead2[k]];
+                    run2[k] = u.c.run[lead2[k]];
+                    // private sweeps saved plus the outer group's relief against the subgroup's own sweep
+                    const long long gain = 16ll * c2 * (run2[k] - r1[k]) + (long long)r1[k] * tile_weight(a.mpt * a.G) * by_mpt.div(c2);
+                    const long long cost = (long long)run2[k] * tile_weight(min(a.mpt, c2) * a.G) * by_mpt.cdiv(c2);
+                    adopt[k] = c2 >= 2 && gain > cost;
+                }
+                if (in[k] && !adopt[k]) atomicMin(&u.c.moff[lead1[k]], tid + k * kPlanThreads);   // who leads the rest
+            }
+            __syncthreads();
+            int lead_f[kPer];
+#pragma unroll
+            for (int k = 0; k < kPer; ++k) lead_f[k] = adopt[k] ? lead2[k] : (in[k] ? u.c.moff[lead1[k]] : lead1[k]);
+            __syncthreads();                       // every leader is read before any changes
+#pragma unroll
+            for (int k = 0; k < kPer; ++k) {
+                const int i = tid + k * kPlanThreads;
+                if (in[k]) {
+                    s_lead[i] = (short)lead_f[k];
+                    v.x.lcp[i] = adopt[k] ? run2[k] : r1[k];
+                }
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < kPer; ++k) {       // nothing nested: back to the round-one runs
+                const int i = tid + k * kPlanThreads;
+                if (my_key[k] >= 0) v.x.lcp[i] = r1[k];
+            }
+        }
+        reset_groups(0);   // every thread changed only its own requests' entries above
+        __syncthreads();
+    }
 
     // ---- group run = shortest common run over the members; rank = arrival at the counter
     int my_rank[kGroupReqMax / kPlanThreads];
@@ -250,14 +393,13 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
         if (i < nG) {
             const int lead = s_lead[i];
             if (lead >= 0) {
-                atomicMin(&u.c.run[lead], v.lcp[i]);
+                atomicMin(&u.c.run[lead], v.x.lcp[i]);
                 my_rank[k] = atomicAdd(&u.c.cnt[lead], 1);
             }
         }
     }
     __syncthreads();   // lcp[] and flw[] are dead from here on
     auto viable = [&](int i) { return s_lead[i] == i && u.c.cnt[i] >= 2 && u.c.run[i] >= a.tune.min_run; };
-    const FastDiv by_mpt(a.mpt);
 
     // ---- member-list offsets (exclusive scan over leaders) and the list of groups
     {
@@ -280,13 +422,10 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
     __syncthreads();
     const int n_groups = s_ngroups;
 
-    // ---- cost model.  A 32-token tile costs a wave more the more query rows ride on
-    // it; weights in sixteenths of a 16-row tile's sweep.  Shared runs are cut into
+    // ---- cost model (tile weights as above).  Shared runs are cut into
     // equal pieces per segment, one piece per wave (a "share"); the private columns of
     // all requests form one stream of tiles that is cut into equal shares for the
     // remaining waves.  Both kinds of share are sized to the same cost.
-    const int w32 = a.tune.weights & 255, w64 = (a.tune.weights >> 8) & 255;
-    auto tile_weight = [&](int rows) { return rows <= 16 ? 16 : (rows <= 32 ? w32 : w64); };
     auto run_of = [&](int i) {   // shared columns of request i (0 if ungrouped)
         if (i >= nG) return 0;
         const int lead = s_lead[i];

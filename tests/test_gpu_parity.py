@@ -255,3 +255,57 @@ def test_device_chunk_hashes_match_the_oracle():
     # the same values as the host function of the library
     from paper_2605_06046_amd import fea_chunk_hashes
     assert got[hoff[10]:hoff[11]].tolist() == fea_chunk_hashes(seqs[10]).tolist()
+
+
+def _radix_workload(dtype, top, subs, singles, Hq=32, Hkv=8, d=128, seed=31):
+    """Token streams with two sharing levels (the radix patterns of Section 3): every request starts
+    with the same `top` tokens; subs = [(members, extra shared tokens), ...]; `singles` requests share
+    only the top level.  Requests arrive interleaved.  Returns a Workload with drawn q/K/V."""
+    rng = np.random.default_rng(seed)
+    top_t = rng.integers(0, W.VOCAB, size=top, dtype=np.int32)
+    seqs = []
+    for m, extra in subs:
+        sub_t = rng.integers(0, W.VOCAB, size=extra, dtype=np.int32)
+        seqs += [np.concatenate([top_t, sub_t, rng.integers(0, W.VOCAB, size=int(rng.integers(1, 90)), dtype=np.int32)])
+                 for _ in range(m)]
+    seqs += [np.concatenate([top_t, rng.integers(0, W.VOCAB, size=int(rng.integers(1, 90)), dtype=np.int32)])
+             for _ in range(singles)]
+    order = rng.permutation(len(seqs))
+    seqs = [seqs[j] for j in order]
+    spec = W.Spec("radix", 41, dtype, Hq, Hkv, d, ((len(seqs), 0),), (1, 1))
+    base = W.generate(spec)                       # for q and the K/V pool's value distribution
+    toks = np.concatenate(seqs)
+    offs = np.zeros(len(seqs) + 1, dtype=np.int64)
+    offs[1:] = np.cumsum([len(s) for s in seqs])
+    nblk = int(sum(-(-len(s) // 16) for s in seqs))
+    rs = np.random.default_rng(seed + 1)
+    shape = (nblk, Hkv, 16, d)
+    k = rs.standard_normal(shape, dtype=np.float32)
+    v = rs.standard_normal(shape, dtype=np.float32)
+    if dtype == "bf16":
+        k, v = W.f32_to_bf16_bits(k), W.f32_to_bf16_bits(v)
+    return dataclasses.replace(base, tokens=toks, tok_offsets=offs, k_cache=k, v_cache=v, num_blocks=nblk,
+                               max_blocks_per_seq=max(-(-len(s) // 16) for s in seqs) + 1,
+                               group_of=np.zeros(len(seqs), dtype=np.int32))
+
+
+@pytest.mark.parametrize("dtype,Hq,Hkv,d", [("bf16", 32, 8, 128), ("f32", 8, 2, 64)])
+def test_two_level_prefix_sharing(dtype, Hq, Hkv, d):
+    """Nested prefixes: subgroups that go on sharing past the common run become groups of their own
+    when that pays; whatever the planner decides, every row must match the oracle."""
+    # 96 shared tokens (6 blocks); subgroups of 5 and 4 share 160 and 64 more; a pair shares 16 more
+    # (too little to pay for sweeping the top level again); three requests share the top level only
+    wl = _radix_workload(dtype, 96, [(5, 160), (4, 64), (2, 16)], 3, Hq, Hkv, d)
+    out, bt, lens, info = run_workload(wl)
+    assert_close(out, oracle_for(wl, bt, lens), dtype, what="two-level sharing")
+    # in sweep cost (a tile with <= 16 / <= 32 query rows weighs 16 / 20): the five save 16*5*10 = 800 for a
+    # run of 16 blocks at 20; the four save 16*4*4 = 256 for 10 blocks at 16; the pair would save 16*2*1 = 32
+    # for 7 blocks at 16.  Two subgroups split off, the pair and the singles keep the top run.
+    assert info["groups"] == 3 and info["grouped_requests"] == 14
+    assert info["shared_blocks"] == 16 + 10 + 6
+    # the same with a deep second level everywhere: all three subgroups split off, the singles keep the top run
+    wl = _radix_workload(dtype, 64, [(6, 320), (3, 480), (2, 640)], 4, Hq, Hkv, d, seed=32)
+    out, bt, lens, info = run_workload(wl)
+    assert_close(out, oracle_for(wl, bt, lens), dtype, what="two-level sharing, deep")
+    assert info["groups"] == 4 and info["grouped_requests"] == 15
+    assert info["shared_blocks"] == (4 + 20) + (4 + 30) + (4 + 40) + 4
