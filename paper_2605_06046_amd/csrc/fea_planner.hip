@@ -77,15 +77,16 @@ __device__ int block_scan_excl(int v, int* s_tmp, int& total) {
     if (lane == 63) s_tmp[wave] = x;
     __syncthreads();
     if (wave == 0) {
-        const int w = lane < 16 ? s_tmp[lane] : 0;
+        constexpr int kWaves = kPlanThreads / 64;
+        const int w = lane < kWaves ? s_tmp[lane] : 0;
         int xs = w;
 #pragma unroll
-        for (int o = 1; o < 16; o <<= 1) {
+        for (int o = 1; o < kWaves; o <<= 1) {
             const int y = __shfl_up(xs, o);
             if (lane >= o) xs += y;
         }
-        if (lane < 16) s_tmp[32 + lane] = xs - w;
-        if (lane == 15) s_tmp[31] = xs;
+        if (lane < kWaves) s_tmp[32 + lane] = xs - w;
+        if (lane == kWaves - 1) s_tmp[31] = xs;
     }
     __syncthreads();
     const int base = s_tmp[32 + wave];
