@@ -112,8 +112,10 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
         struct { int keys[kHashSlots]; int vals[kHashSlots]; } h;                     // leader finding only
         struct { int run[kGroupReqMax]; int cnt[kGroupReqMax]; int moff[kGroupReqMax];
                  int gseg[kGroupMax]; } c;                                            // afterwards
-        unsigned short r1[kGroupReqMax];                                              // between the two (nested runs)
     } u;
+    __shared__ struct { int keys[kHashSlots]; int vals[kHashSlots]; } h2;             // subgroup leaders (nested runs)
+    __shared__ unsigned short s_r1[kGroupReqMax];
+    __shared__ unsigned long long s_lcpv[kGroupReqMax];   // round one: (common run << 32) | the follower's block where it ends
     __shared__ short s_lead[kGroupReqMax];      // request ids fit 16 bits (kGroupReqMax <= 32767)
     __shared__ int s_len[kGroupReqMax];
     __shared__ union {
@@ -143,7 +145,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
     auto clampL = [&](int L) { return max(0, min(L, maxL)); };
 
     // ---- leaders: smallest request index among those with the same first block
-    for (int s = tid; s < kHashSlots; s += kPlanThreads) { u.h.keys[s] = -1; u.h.vals[s] = INT_MAX; }
+    for (int s = tid; s < kHashSlots; s += kPlanThreads) { u.h.keys[s] = -1; u.h.vals[s] = INT_MAX; h2.keys[s] = -1; h2.vals[s] = INT_MAX; }
     if (tid == 0) { s_ngroups = 0; s_ngrouped = 0; s_shared_blocks = 0; s_nflw = 0; }
     __syncthreads();
     int my_key[kGroupReqMax / kPlanThreads];
@@ -183,7 +185,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
                 if (lead != i) w.flw[atomicAdd(&s_nflw, 1)] = (unsigned short)i;
             }
             s_lead[i] = (short)lead;
-            v.x.lcp[i] = lcp;
+            s_lcpv[i] = ((unsigned long long)(uint32_t)lcp << 32) | 0xFFFFFFFFull;
         }
     }
     __syncthreads();   // the hash table is dead from here on; its memory becomes run/cnt/moff/...
@@ -196,7 +198,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
     // column group) pairs are spread flat over the threads, eight at a time so that
     // their loads are in flight together; a mismatch lowers the follower's run with
     // an LDS atomic.  Columns below from(i) are known to agree and are not read.
-    auto lcp_pass = [&](int nflw, const short* lead_of, auto&& from) {
+    auto lcp_pass = [&](int nflw, const short* lead_of, auto&& from, auto&& hit) {
         const bool vec = (a.stride % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.bt) & 15) == 0);
         const int cpe = vec ? 4 : 1;                       // columns per element
         const int epr = cdiv(a.stride, cpe);               // elements per row
@@ -233,17 +235,19 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
 #pragma unroll
             for (int q = 0; q < kBatch; ++q) {
                 if (who[q] >= 0) {
-                    int first = INT_MAX;
-                    if (xs[q].w != ys[q].w) first = col[q] + 3;
-                    if (xs[q].z != ys[q].z) first = col[q] + 2;
-                    if (xs[q].y != ys[q].y) first = col[q] + 1;
-                    if (xs[q].x != ys[q].x) first = col[q];
-                    if (first < cap[q]) atomicMin(&v.x.lcp[who[q]], first);
+                    int first = INT_MAX, mine = 0;
+                    if (xs[q].w != ys[q].w) { first = col[q] + 3; mine = xs[q].w; }
+                    if (xs[q].z != ys[q].z) { first = col[q] + 2; mine = xs[q].z; }
+                    if (xs[q].y != ys[q].y) { first = col[q] + 1; mine = xs[q].y; }
+                    if (xs[q].x != ys[q].x) { first = col[q]; mine = xs[q].x; }
+                    if (first < cap[q]) hit(who[q], first, mine);
                 }
             }
         }
     };
-    lcp_pass(s_nflw, s_lead, [](int) { return 0; });
+    lcp_pass(s_nflw, s_lead, [](int) { return 0; }, [&](int who, int first, int mine) {
+        atomicMin(&s_lcpv[who], ((unsigned long long)(uint32_t)first << 32) | (uint32_t)mine);   // the run and the block that ends it
+    });
     __syncthreads();
 
     // A 32-token tile costs a wave more the more query rows ride on it: weights in
@@ -262,23 +266,35 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
     //
     // A follower agrees with its leader over lcp >= run columns.  If lcp > run it is in the
     // leader's subgroup and its run there is lcp itself; if lcp == run, the block that
-    // tells its subgroup sits in column lcp - which is known before the run is, so that
-    // load is under way while the runs are reduced.
+    // tells its subgroup sits in column lcp - the very entry the run detection stopped at,
+    // which it hands over together with the column (no further memory round trip).
+    // Stage by stage: (1) round-one runs, sizes and ranks; (2) keys into a hash table of
+    // their own; (3) subgroup leaders.  With nothing nested that is all (two barriers more
+    // than without this round) and the round-one results stand.
+    constexpr int kPer = kGroupReqMax / kPlanThreads;
+    int my_rank[kPer];
     {
-        constexpr int kPer = kGroupReqMax / kPlanThreads;
         int r1[kPer], lead1[kPer], lcp1[kPer];
         bool in[kPer];
+        if (tid == 0) { s_nflw = 0; s_nest = 0; }
 #pragma unroll
-        for (int k = 0; k < kPer; ++k) {           // round-one runs and sizes
+        for (int k = 0; k < kPer; ++k) {
             const int i = tid + k * kPlanThreads;
             lead1[k] = i < nG ? (int)s_lead[i] : -1;
             lcp1[k] = 0;
             my_key[k] = -1;
+            my_rank[k] = 0;
             if (lead1[k] >= 0) {
-                lcp1[k] = v.x.lcp[i];
-                if (lead1[k] != i && lcp1[k] < s_len[i] / kBlock) my_key[k] = a.bt[(size_t)i * a.stride + lcp1[k]];
+                const unsigned long long lv = s_lcpv[i];
+                lcp1[k] = (int)(lv >> 32);
+                v.x.lcp[i] = lcp1[k];
+                if (lead1[k] != i && lcp1[k] < s_len[i] / kBlock) {
+                    // the block in the column where the follower left its leader: the run detection saw it,
+                    // unless the leader's row simply ended there
+                    my_key[k] = (uint32_t)lv != 0xFFFFFFFFu ? (int)(uint32_t)lv : a.bt[(size_t)i * a.stride + lcp1[k]];
+                }
                 atomicMin(&u.c.run[lead1[k]], lcp1[k]);
-                atomicAdd(&u.c.cnt[lead1[k]], 1);
+                my_rank[k] = atomicAdd(&u.c.cnt[lead1[k]], 1);
             }
         }
         __syncthreads();
@@ -287,19 +303,12 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
             in[k] = lead1[k] >= 0 && u.c.cnt[lead1[k]] >= 2 && u.c.run[lead1[k]] >= a.tune.min_run;
             r1[k] = in[k] ? u.c.run[lead1[k]] : 0;
             if (!in[k] || lcp1[k] > r1[k]) my_key[k] = -1;      // only the members that leave the leader at the run
-        }
-        __syncthreads();                           // run/cnt are read: their memory is the hash table again
-        for (int s = tid; s < kHashSlots; s += kPlanThreads) { u.h.keys[s] = -1; u.h.vals[s] = INT_MAX; }
-        if (tid == 0) { s_nflw = 0; s_nest = 0; }
-        __syncthreads();
-#pragma unroll
-        for (int k = 0; k < kPer; ++k) {
             const int key = my_key[k];
             if (key >= 0) {
                 uint32_t s = slot_of(key);
                 for (;;) {
-                    const int old = atomicCAS(&u.h.keys[s], -1, key);
-                    if (old == -1 || old == key) { atomicMin(&u.h.vals[s], tid + k * kPlanThreads); break; }
+                    const int old = atomicCAS(&h2.keys[s], -1, key);
+                    if (old == -1 || old == key) { atomicMin(&h2.vals[s], tid + k * kPlanThreads); break; }
                     s = (s + 1) & (kHashSlots - 1);
                 }
             }
@@ -313,8 +322,8 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
             const int key = my_key[k];
             if (key >= 0) {
                 uint32_t s = slot_of(key);
-                while (u.h.keys[s] != key) s = (s + 1) & (kHashSlots - 1);
-                const int cand = u.h.vals[s];
+                while (h2.keys[s] != key) s = (s + 1) & (kHashSlots - 1);
+                const int cand = h2.vals[s];
                 lead2[k] = s_lead[cand] == lead1[k] ? cand : i;     // only within the same outer group
                 v.x.lcp[i] = min(s_len[i], s_len[lead2[k]]) / kBlock;
                 if (lead2[k] != i) w.flw[atomicAdd(&s_nflw, 1)] = (unsigned short)i;
@@ -322,19 +331,14 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
                 lead2[k] = lead1[k];                                // the leader's own subgroup: runs are known
                 if (lead1[k] != i) atomicAdd(&s_nest, 1);
             }
-            if (i < nG) v.x.lead2[i] = (short)lead2[k];
+            if (i < nG) { v.x.lead2[i] = (short)lead2[k]; s_r1[i] = (unsigned short)min(r1[k], 65535); }
         }
-        __syncthreads();                           // the hash table is dead again
+        __syncthreads();
         const int nflw2 = s_nflw;
         if (nflw2 + s_nest > 0) {                  // uniform
             if (nflw2 > 0) {
-#pragma unroll
-                for (int k = 0; k < kPer; ++k) {
-                    const int i = tid + k * kPlanThreads;
-                    if (i < nG) u.r1[i] = (unsigned short)min(r1[k], 65535);
-                }
-                __syncthreads();
-                lcp_pass(nflw2, v.x.lead2, [&](int i) { return (int)u.r1[i]; });
+                lcp_pass(nflw2, v.x.lead2, [&](int i) { return (int)s_r1[i]; },
+                         [&](int who, int first, int) { atomicMin(&v.x.lcp[who], first); });
                 __syncthreads();
             }
             reset_groups(INT_MAX);
@@ -374,32 +378,26 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
                     v.x.lcp[i] = adopt[k] ? run2[k] : r1[k];
                 }
             }
-        } else {
+            reset_groups(0);   // every thread changed only its own requests' entries above
+            __syncthreads();
+            // runs, sizes and ranks of the groups as they are now
 #pragma unroll
-            for (int k = 0; k < kPer; ++k) {       // nothing nested: back to the round-one runs
+            for (int k = 0; k < kPer; ++k) {
                 const int i = tid + k * kPlanThreads;
-                if (my_key[k] >= 0) v.x.lcp[i] = r1[k];
+                my_rank[k] = 0;
+                if (i < nG) {
+                    const int lead = s_lead[i];
+                    if (lead >= 0) {
+                        atomicMin(&u.c.run[lead], v.x.lcp[i]);
+                        my_rank[k] = atomicAdd(&u.c.cnt[lead], 1);
+                    }
+                }
             }
-        }
-        reset_groups(0);   // every thread changed only its own requests' entries above
-        __syncthreads();
-    }
-
-    // ---- group run = shortest common run over the members; rank = arrival at the counter
-    int my_rank[kGroupReqMax / kPlanThreads];
-#pragma unroll
-    for (int k = 0; k < kGroupReqMax / kPlanThreads; ++k) {
-        const int i = tid + k * kPlanThreads;
-        my_rank[k] = 0;
-        if (i < nG) {
-            const int lead = s_lead[i];
-            if (lead >= 0) {
-                atomicMin(&u.c.run[lead], v.x.lcp[i]);
-                my_rank[k] = atomicAdd(&u.c.cnt[lead], 1);
-            }
+            __syncthreads();
         }
     }
-    __syncthreads();   // lcp[] and flw[] are dead from here on
+    // lcp[] and flw[] are dead from here on; run/cnt hold every group's run (the shortest
+    // common run over its members) and size, my_rank the arrival at the group's counter
     auto viable = [&](int i) { return s_lead[i] == i && u.c.cnt[i] >= 2 && u.c.run[i] >= a.tune.min_run; };
 
     // ---- member-list offsets (exclusive scan over leaders) and the list of groups
