@@ -248,25 +248,25 @@ __global__ __launch_bounds__(256) void merge_kernel(SweepArgs a) {
     const int sh_base = rd.sh_base0 + g * rd.sh_gstride + hh, pr_base = pd.pbase + hh;
     auto prow = [&](int s) { return s < ns_sh ? sh_base + s * rd.sh_pstride : pr_base + (s - ns_sh) * a.G; };
 
-    // reference exponent: the largest m over all partials (lanes over partials)
-    float M = -INFINITY;
-    for (int s = lane; s < ns; s += 64) M = fmaxf(M, ml[prow(s)].x);
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) M = fmaxf(M, __shfl_xor(M, o));
-
+    // Each lane group walks its partials kInFlight at a time: their (m, l) pairs and
+    // accumulator rows are requested together, so a row with up to kInFlight * SLOTS
+    // partials costs one memory round trip.  A group keeps its own reference exponent
+    // (raised batch by batch); the groups are brought to the common one when folded.
+    constexpr int kInFlight = 4;
     float num[8];
 #pragma unroll
     for (int k = 0; k < 8; ++k) num[k] = 0.f;
-    float den = 0.f;
-    for (int s0 = 0; s0 < ns; s0 += 2 * SLOTS) {   // two partial rows per lane group in flight
-        float4 x[2][2];
-        float2 v[2];
-        bool on[2];
+    float den = 0.f, M = -INFINITY;
+    for (int s0 = 0; s0 < ns; s0 += kInFlight * SLOTS) {
+        float4 x[kInFlight][2];
+        float2 v[kInFlight];
+        float mb = -INFINITY;
 #pragma unroll
-        for (int q = 0; q < 2; ++q) {
+        for (int q = 0; q < kInFlight; ++q) {
             const int s = s0 + q * SLOTS + slot;
-            on[q] = s < ns;
-            if (on[q]) {
+            v[q] = make_float2(-INFINITY, 0.f);
+            x[q][0] = x[q][1] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (s < ns) {
                 const int pr = prow(s);
                 v[q] = ml[pr];
                 const float4* src = reinterpret_cast<const float4*>(pacc + (size_t)pr * D + c * 8);
@@ -275,18 +275,35 @@ __global__ __launch_bounds__(256) void merge_kernel(SweepArgs a) {
             }
         }
 #pragma unroll
-        for (int q = 0; q < 2; ++q) {
-            if (on[q]) {
-                const float w = exp2f(v[q].x - M);
-                den = fmaf(w, v[q].y, den);
-                num[0] = fmaf(w, x[q][0].x, num[0]); num[1] = fmaf(w, x[q][0].y, num[1]);
-                num[2] = fmaf(w, x[q][0].z, num[2]); num[3] = fmaf(w, x[q][0].w, num[3]);
-                num[4] = fmaf(w, x[q][1].x, num[4]); num[5] = fmaf(w, x[q][1].y, num[5]);
-                num[6] = fmaf(w, x[q][1].z, num[6]); num[7] = fmaf(w, x[q][1].w, num[7]);
-            }
+        for (int q = 0; q < kInFlight; ++q) mb = fmaxf(mb, v[q].x);
+        const float Mn = fmaxf(M, mb);
+        if (Mn > M) {                                   // raise the group's reference (a no-op on empty sums)
+            const float f = M == -INFINITY ? 0.f : exp2f(M - Mn);
+            den *= f;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) num[k] *= f;
+            M = Mn;
+        }
+#pragma unroll
+        for (int q = 0; q < kInFlight; ++q) {
+            const float w = v[q].x == -INFINITY ? 0.f : exp2f(v[q].x - M);
+            den = fmaf(w, v[q].y, den);
+            num[0] = fmaf(w, x[q][0].x, num[0]); num[1] = fmaf(w, x[q][0].y, num[1]);
+            num[2] = fmaf(w, x[q][0].z, num[2]); num[3] = fmaf(w, x[q][0].w, num[3]);
+            num[4] = fmaf(w, x[q][1].x, num[4]); num[5] = fmaf(w, x[q][1].y, num[5]);
+            num[6] = fmaf(w, x[q][1].z, num[6]); num[7] = fmaf(w, x[q][1].w, num[7]);
         }
     }
-    // fold the lane groups (fixed order: deterministic)
+    // fold the lane groups (fixed order: deterministic) at the common reference
+    {
+        float Mg = M;
+#pragma unroll
+        for (int o = LPR; o < 64; o <<= 1) Mg = fmaxf(Mg, __shfl_xor(Mg, o));
+        const float f = M == -INFINITY ? 0.f : exp2f(M - Mg);
+        den *= f;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) num[k] *= f;
+    }
 #pragma unroll
     for (int o = LPR; o < 64; o <<= 1) {
         den += __shfl_xor(den, o);
@@ -294,7 +311,7 @@ __global__ __launch_bounds__(256) void merge_kernel(SweepArgs a) {
         for (int k = 0; k < 8; ++k) num[k] += __shfl_xor(num[k], o);
     }
     if (slot == 0) {
-        const float inv = ns > 0 ? 1.f / den : 0.f;
+        const float inv = den > 0.f ? 1.f / den : 0.f;
 #pragma unroll
         for (int k = 0; k < 8; ++k) num[k] *= inv;
         Elem<T>::store8(out + c * 8, num);
