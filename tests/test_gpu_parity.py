@@ -309,3 +309,55 @@ def test_two_level_prefix_sharing(dtype, Hq, Hkv, d):
     assert_close(out, oracle_for(wl, bt, lens), dtype, what="two-level sharing, deep")
     assert info["groups"] == 4 and info["grouped_requests"] == 15
     assert info["shared_blocks"] == (4 + 20) + (4 + 30) + (4 + 40) + 4
+
+
+def test_captured_graph_replays_match_eager_calls():
+    """The library neither allocates nor synchronises, so a decode step (append + attention) can be
+    captured into a HIP graph.  Every replay, with the inputs changed in place between replays and
+    eager work of the program in between, must give what the eager call gives on the same inputs."""
+    import torch
+    from paper_2605_06046_amd import (AttnParams, FEA_DTYPE_BF16, fea_decode_attention, fea_decode_workspace_bytes,
+                                      fea_kv_append)
+    from gpu_harness import to_device
+    wl = W.generate(W.scaled(W.CONFIGS["c3"], 4, 8, name="c3_graph"))
+    bt, lens = library_tables(wl)
+    s = wl.spec
+    params = AttnParams(s.num_q_heads, s.num_kv_heads, s.head_dim, FEA_DTYPE_BF16)
+    B, stride = bt.shape
+    q, k, v = to_device(wl.q), to_device(wl.k_cache), to_device(wl.v_cache)
+    dbt, dl = torch.from_numpy(bt).cuda(), torch.from_numpy(lens).cuda()
+    ws = torch.empty(fea_decode_workspace_bytes(params, B, stride), dtype=torch.uint8, device="cuda")
+    ws2 = torch.empty_like(ws)
+    out_g, out_e = torch.empty_like(q), torch.empty_like(q)
+    g = torch.Generator(device="cuda"); g.manual_seed(3)
+    k_new = torch.randn((B, s.num_kv_heads, s.head_dim), generator=g, device="cuda").to(torch.bfloat16)
+    v_new = torch.randn((B, s.num_kv_heads, s.head_dim), generator=g, device="cuda").to(torch.bfloat16)
+
+    def step(out, wsx, stream=None):
+        fea_kv_append(params, k_new, v_new, k, v, dbt, dl, stream=stream)     # rewrites position L-1 of every request
+        fea_decode_attention(params, q, k, v, dbt, dl, out, wsx, stream=stream)
+
+    side = torch.cuda.Stream()
+    gr = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        step(out_g, ws, side)
+        side.synchronize()
+        with torch.cuda.graph(gr, stream=side):
+            step(out_g, ws, side)
+    torch.cuda.synchronize()
+    for rep in range(4):
+        # change the inputs in place: new query, new rows to append
+        q.copy_(torch.randn(q.shape, generator=g, device="cuda").to(torch.bfloat16))
+        k_new.copy_(torch.randn(k_new.shape, generator=g, device="cuda").to(torch.bfloat16))
+        v_new.copy_(torch.randn(v_new.shape, generator=g, device="cuda").to(torch.bfloat16))
+        out_g.fill_(float("nan"))
+        torch.cuda.synchronize()
+        gr.replay()
+        torch.cuda.synchronize()
+        step(out_e, ws2)                       # eager, own workspace, same inputs (the append is idempotent)
+        _ = (out_e.float() * 2).sum().item()   # unrelated eager work and a synchronisation between replays
+        assert torch.equal(out_g, out_e), f"replay {rep} differs from the eager call"
+    # and the last replay against the oracle
+    kk, vv = k.float().cpu().numpy().astype(np.float64), v.float().cpu().numpy().astype(np.float64)
+    want = decode_attention(q.float().cpu().numpy().astype(np.float64), kk, vv, bt, lens)
+    assert_close(out_g.float().cpu().numpy().astype(np.float64), want, "bf16", what="graph replay")
