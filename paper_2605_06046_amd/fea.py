@@ -311,7 +311,7 @@ class Cht:
         self._h = h
 
     def close(self):
-        if self._h:
+        if getattr(self, "_h", None):
             self._lib.fea_cht_destroy(self._h)
             self._h = None
 
@@ -396,7 +396,7 @@ class Policy:
         self._h = h
 
     def close(self):
-        if self._h:
+        if getattr(self, "_h", None):
             self._lib.fea_policy_destroy(self._h)
             self._h = None
 

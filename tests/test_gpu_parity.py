@@ -361,3 +361,13 @@ def test_captured_graph_replays_match_eager_calls():
     kk, vv = k.float().cpu().numpy().astype(np.float64), v.float().cpu().numpy().astype(np.float64)
     want = decode_attention(q.float().cpu().numpy().astype(np.float64), kk, vv, bt, lens)
     assert_close(out_g.float().cpu().numpy().astype(np.float64), want, "bf16", what="graph replay")
+
+
+def test_more_requests_than_the_grouping_limit():
+    """Requests with index >= 2048 are never grouped (they sweep the prefix on their own); the rows of
+    all 2100 requests must still match the oracle, grouped or not."""
+    spec = W.Spec("many", 23, "bf16", 8, 2, 128, ((1400, 64), (700, 48)), (1, 40), interleave=True)
+    wl = W.generate(spec)
+    out, bt, lens, info = run_workload(wl)
+    assert info["overflow"] == 0 and info["groups"] == 2 and info["grouped_requests"] == 2048
+    assert_close(out, oracle_for(wl, bt, lens), "bf16", what="B=2100")
