@@ -41,6 +41,11 @@ extern "C" {
 #define FEA_FLAG_REUSE_PLAN 1  /* skip alias detection: the workspace still holds the plan
                                   of the previous call, and tables/lengths/B/params are
                                   unchanged since (e.g. the other layers of one step)    */
+#define FEA_FLAG_PLAN_ONLY 2   /* only alias detection: the plan is left in the workspace
+                                  for later FEA_FLAG_REUSE_PLAN calls.  It depends on the
+                                  tables and lengths alone, so the plan of the next decode
+                                  step can be made on another stream while this step's
+                                  attention runs (q, caches and out may be NULL)         */
 
 typedef struct fea_kv_pool fea_kv_pool;
 

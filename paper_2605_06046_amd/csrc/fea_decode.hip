@@ -62,7 +62,9 @@ static int32_t check_params(const fea_attn_params* p, const char* who) {
     if (!d_ok) return fail(FEA_EINVAL, "%s: head_dim=%d not supported for this dtype", who, d);
     if (!(p->scale >= 0.f) || !std::isfinite(p->scale)) return fail(FEA_EINVAL, "%s: scale must be finite and >= 0", who);
     if (p->split_blocks < 0 || p->max_group < 0) return fail(FEA_EINVAL, "%s: split_blocks and max_group must be >= 0", who);
-    if (p->flags & ~FEA_FLAG_REUSE_PLAN) return fail(FEA_EINVAL, "%s: unknown flag bits 0x%x", who, p->flags);
+    if (p->flags & ~(FEA_FLAG_REUSE_PLAN | FEA_FLAG_PLAN_ONLY)) return fail(FEA_EINVAL, "%s: unknown flag bits 0x%x", who, p->flags);
+    if ((p->flags & FEA_FLAG_REUSE_PLAN) && (p->flags & FEA_FLAG_PLAN_ONLY))
+        return fail(FEA_EINVAL, "%s: FEA_FLAG_REUSE_PLAN and FEA_FLAG_PLAN_ONLY exclude each other", who);
     if (p->reserved[0] || p->reserved[1] || p->reserved[2]) return fail(FEA_EINVAL, "%s: reserved fields must be 0", who);
     return FEA_OK;
 }
@@ -143,7 +145,8 @@ int32_t fea_decode_attention(const fea_attn_params* p, const void* q, const void
     rc = resolve(p, B, table_stride, r, "fea_decode_attention");
     if (rc != FEA_OK) return rc;
     if (B == 0) return FEA_OK;
-    if (!q || !k_cache || !v_cache || !block_tables || !seq_lens || !out || !workspace)
+    const bool plan_only = (p->flags & FEA_FLAG_PLAN_ONLY) != 0;
+    if (!block_tables || !seq_lens || !workspace || (!plan_only && (!q || !k_cache || !v_cache || !out)))
         return fail(FEA_EINVAL, "fea_decode_attention: NULL device pointer");
     if (((uintptr_t)workspace & 255) != 0) return fail(FEA_EINVAL, "fea_decode_attention: workspace must be 256-byte aligned");
     if (((uintptr_t)q & 15) || ((uintptr_t)k_cache & 15) || ((uintptr_t)v_cache & 15) || ((uintptr_t)out & 15))
@@ -160,6 +163,7 @@ int32_t fea_decode_attention(const fea_attn_params* p, const void* q, const void
         for (int k = 0; k < 3; ++k) {
             if (g_prof_which >= 0 && g_prof_which != k) continue;
             if (k == 0 && (p->flags & FEA_FLAG_REUSE_PLAN)) continue;
+            if (k > 0 && plan_only) continue;
             where[k].ev_start = ev[2 * k];
             where[k].ev_stop = ev[2 * k + 1];
             mask |= (unsigned char)(1u << k);
@@ -185,6 +189,11 @@ int32_t fea_decode_attention(const fea_attn_params* p, const void* q, const void
         pa.split_user = r.split_user;
         pa.variant = r.variant;
         launch_plan(pa, where[0]);
+    }
+    if (plan_only) {
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return fail(FEA_EHIP, "fea_decode_attention: launch failed: %s", hipGetErrorString(e));
+        return FEA_OK;
     }
     SweepArgs sa;
     std::memset(&sa, 0, sizeof sa);

@@ -10,6 +10,7 @@ import numpy as np
 FEA_DTYPE_F32 = 0
 FEA_DTYPE_BF16 = 1
 FEA_FLAG_REUSE_PLAN = 1
+FEA_FLAG_PLAN_ONLY = 2
 _CODES = {-1: "FEA_EINVAL", -2: "FEA_ENOMEM", -3: "FEA_ERANGE", -4: "FEA_EHIP"}
 
 _HERE = os.path.dirname(os.path.abspath(__file__))

@@ -371,3 +371,32 @@ def test_more_requests_than_the_grouping_limit():
     out, bt, lens, info = run_workload(wl)
     assert info["overflow"] == 0 and info["groups"] == 2 and info["grouped_requests"] == 2048
     assert_close(out, oracle_for(wl, bt, lens), "bf16", what="B=2100")
+
+
+def test_plan_only_then_reuse_equals_one_call():
+    """FEA_FLAG_PLAN_ONLY leaves in the workspace exactly the plan a full call would make: planning on
+    a side stream, then attending with FEA_FLAG_REUSE_PLAN, gives the full call's output bit for bit."""
+    import torch
+    from paper_2605_06046_amd import (AttnParams, FEA_DTYPE_BF16, FEA_FLAG_PLAN_ONLY, FEA_FLAG_REUSE_PLAN, FeaError,
+                                      fea_decode_attention, fea_decode_workspace_bytes)
+    from gpu_harness import to_device
+    wl = W.generate(W.scaled(W.CONFIGS["c2"], 2, 4, name="c2_plan_only"))
+    bt, lens = library_tables(wl)
+    s = wl.spec
+    mk = lambda flags: AttnParams(s.num_q_heads, s.num_kv_heads, s.head_dim, FEA_DTYPE_BF16, flags=flags)
+    q, k, v = to_device(wl.q), to_device(wl.k_cache), to_device(wl.v_cache)
+    dbt, dl = torch.from_numpy(bt).cuda(), torch.from_numpy(lens).cuda()
+    n = fea_decode_workspace_bytes(mk(0), *bt.shape)
+    ws_a, ws_b = (torch.zeros(n, dtype=torch.uint8, device="cuda") for _ in range(2))
+    out_a, out_b = torch.full_like(q, float("nan")), torch.full_like(q, float("nan"))
+    fea_decode_attention(mk(0), q, k, v, dbt, dl, out_a, ws_a)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    fea_decode_attention(mk(FEA_FLAG_PLAN_ONLY), q, k, v, dbt, dl, out_b, ws_b, stream=side)
+    torch.cuda.current_stream().wait_stream(side)
+    assert torch.isnan(out_b.float()).all()                      # planning alone writes no output
+    fea_decode_attention(mk(FEA_FLAG_REUSE_PLAN), q, k, v, dbt, dl, out_b, ws_b)
+    torch.cuda.synchronize()
+    assert torch.equal(out_a, out_b)
+    with pytest.raises(FeaError):
+        fea_decode_attention(mk(FEA_FLAG_PLAN_ONLY | FEA_FLAG_REUSE_PLAN), q, k, v, dbt, dl, out_b, ws_b)
