@@ -400,3 +400,27 @@ def test_plan_only_then_reuse_equals_one_call():
     assert torch.equal(out_a, out_b)
     with pytest.raises(FeaError):
         fea_decode_attention(mk(FEA_FLAG_PLAN_ONLY | FEA_FLAG_REUSE_PLAN), q, k, v, dbt, dl, out_b, ws_b)
+
+
+def test_very_long_contexts():
+    """Maximum sizes: two requests that share a 60 000-token prefix, and one request of 120 000
+    tokens (thousands of table columns, the block-id windows refilled many times)."""
+    pair = W.generate(W.Spec("long_pair", 24, "bf16", 32, 8, 128, ((2, 60000),), (17, 300)))
+    out, bt, lens, info = run_workload(pair)
+    assert info["groups"] == 1 and info["shared_blocks"] == 3750 and info["overflow"] == 0
+    assert_close(out, oracle_for(pair, bt, lens), "bf16", what="60k shared prefix")
+    lone = W.generate(W.Spec("long_one", 26, "bf16", 32, 8, 128, ((1, 0),), (120000, 120000)))
+    out, bt, lens, info = run_workload(lone)
+    assert bt.shape[1] >= 7500 and info["groups"] == 0 and info["overflow"] == 0
+    assert_close(out, oracle_for(lone, bt, lens), "bf16", what="120k tokens, one request")
+
+
+def test_many_small_groups():
+    """Hundreds of prefix groups of two or three requests in arrival order: the group lists, the
+    member offsets and the item emission by teams of waves all run at their widest."""
+    groups = tuple((2 + (i % 2), 32 + 16 * (i % 5)) for i in range(500))
+    spec = W.Spec("pairs", 25, "bf16", 16, 4, 128, groups, (1, 60), interleave=True)
+    wl = W.generate(spec)
+    out, bt, lens, info = run_workload(wl)
+    assert info["groups"] == 500 and info["grouped_requests"] == spec.batch and info["overflow"] == 0
+    assert_close(out, oracle_for(wl, bt, lens), "bf16", what="500 small groups")
