@@ -260,6 +260,9 @@ def main():
                     help="also compare first-come-first-served batches with batches formed by the Chunked Hash Tree")
     ap.add_argument("--batch-sweep", action="store_true",
                     help="also sweep the batch size on one shared 10K-token prefix vs five of them (Experiment 5's shape)")
+    ap.add_argument("--paper-shapes", action="store_true",
+                    help="also run the batch shapes of the paper's Experiments 2 (shared fraction), 4 (sharing levels) "
+                         "and 6 (batching strategies over eight prefix groups)")
     ap.add_argument("--policies", type=int, default=0, metavar="ROUNDS",
                     help="also form ROUNDS batches per stop policy (first-come-first-served, rule-based, bandit, "
                          "Q-learning) from a five-group queue, the measured decode throughput as the reward")
@@ -329,6 +332,7 @@ def main():
                 f.write(json.dumps(res) + "\n")
                 log(json.dumps(res))
     for flag, name, gen in ((args.batch_sweep, "batch_sweep.jsonl", lambda: batch_sweep(max(50, args.steps // 4), max(10, args.warmup // 2))),
+                            (args.paper_shapes, "paper_shapes.jsonl", lambda: paper_shapes(max(50, args.steps // 4), max(10, args.warmup // 2))),
                             (args.policies > 0, "policies.jsonl", lambda: policy_comparison(args.policies))):
         if flag:
             os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
@@ -555,6 +559,84 @@ def batch_sweep(steps, warm):
                    "logical_kv_MB": c.logical_bytes / 1e6, "kernel_us": m["kernel_us"]}
             del c
             torch.cuda.empty_cache()
+
+
+def _case_from_sequences(base, name, seqs, index):
+    """A Case over explicit token sequences (shape parameters and q from `base`'s layer)."""
+    import dataclasses
+    sp = W.Spec(name, index, "bf16", base.num_q_heads, base.num_kv_heads, base.head_dim, ((len(seqs), 0),), (1, 1))
+    wl = W.generate(sp, with_kv=False)
+    offs = np.zeros(len(seqs) + 1, dtype=np.int64)
+    offs[1:] = np.cumsum([len(x) for x in seqs])
+    nblk = int(sum(-(-len(x) // 16) for x in seqs))
+    wl = dataclasses.replace(wl, tokens=np.concatenate(seqs), tok_offsets=offs, num_blocks=nblk,
+                             max_blocks_per_seq=max(-(-len(x) // 16) for x in seqs) + 1,
+                             group_of=np.zeros(len(seqs), dtype=np.int32))
+    return Case(sp, tokens=wl, label=name)
+
+
+def paper_shapes(steps, warm):
+    """The batch shapes of Section 3 on a Llama-3-8B layer, decode attention only.
+    Experiment 2: 100 requests of 2 048 tokens sharing the first 2048 f tokens.
+    Experiment 4: 64 requests of 4 096 tokens in four 1 024-token levels, the first k levels shared
+    (level 1 by all, level 2 by 16, level 3 by 4 requests each), k = 0..3.
+    Experiment 6: eight prefix groups (10 240 tokens) of 100 requests served as 1x800 ... 32x25:
+    summed attention time of one decode step over all batches."""
+    import torch
+    base = W.CONFIGS["c2"]
+    rng = np.random.default_rng(W.SEED_BASE + 90)
+    draw = lambda n: rng.integers(0, W.VOCAB, size=n, dtype=np.int32)
+
+    def run(name, seqs, index, extra):
+        c = _case_from_sequences(base, name, seqs, index)
+        m = c.measure(steps, warm)
+        out = {"workload": name, "B": c.B, "ms_per_step": m["ms_per_step"], "tokens_per_s": m["tokens_per_s"],
+               "unique_kv_MB": c.unique_bytes / 1e6, "logical_kv_MB": c.logical_bytes / 1e6,
+               "kernel_us": m["kernel_us"], "groups": m["plan"]["groups"]}
+        out.update(extra)
+        del c
+        torch.cuda.empty_cache()
+        return out
+
+    for f in (0.0, 0.25, 0.5, 0.75, 1.0):
+        shared = draw(int(2048 * f) // 16 * 16)
+        seqs = [np.concatenate([shared, draw(2048 - len(shared))]) if len(shared) < 2048 else shared.copy()
+                for _ in range(100)]
+        yield run(f"exp2_shared_fraction_{f:g}", seqs, 70, {"f": f})
+    for k in range(4):
+        lv1 = draw(1024)
+        lv2 = [draw(1024) for _ in range(4)]
+        lv3 = [draw(1024) for _ in range(16)]
+        seqs = []
+        for i in range(64):
+            parts = [lv1 if k >= 1 else draw(1024), lv2[i % 4] if k >= 2 else draw(1024),
+                     lv3[i % 16] if k >= 3 else draw(1024), draw(1024)]
+            seqs.append(np.concatenate(parts))
+        yield run(f"exp4_levels_shared_{k}", seqs, 71, {"levels_shared": k})
+    prefixes = [draw(10240) for _ in range(8)]
+    reqs = [(g, np.concatenate([prefixes[g], draw(int(rng.integers(64, 257)))])) for g in range(8) for _ in range(100)]
+    for n_batches in (1, 2, 4, 8, 16, 32):
+        per_group = max(1, n_batches // 8)                  # batches per prefix group (homogeneous strategies)
+        groups_per_batch = max(1, 8 // n_batches)
+        total_ms, total_b, kus = 0.0, 0, [0.0, 0.0, 0.0]
+        for b in range(n_batches):
+            if n_batches <= 8:
+                gs = range(b * groups_per_batch, (b + 1) * groups_per_batch)
+                seqs = [x for g, x in reqs if g in gs]
+            else:
+                g, part = b // per_group, b % per_group
+                mine = [x for gg, x in reqs if gg == g]
+                size = len(mine) // per_group
+                seqs = mine[part * size:(part + 1) * size]
+            r = run(f"exp6_{n_batches}x{800 // n_batches}_batch{b}", seqs, 72, {})
+            total_ms += r["ms_per_step"]
+            total_b += r["B"]
+            for j, key in enumerate(("plan", "sweep", "merge")):
+                kus[j] += r["kernel_us"][key]
+        yield {"workload": f"exp6_{n_batches}x{800 // n_batches}", "batches": n_batches, "B": total_b,
+               "prefix_groups_per_batch": groups_per_batch if n_batches <= 8 else 1, "ms_per_decode_step": total_ms,
+               "tokens_per_s": total_b / (total_ms * 1e-3),
+               "kernel_us_summed": {"plan": kus[0], "sweep": kus[1], "merge": kus[2]}}
 
 
 def policy_comparison(rounds, max_batch=256, queue=320, n_groups=5, prefix=5120, ucb_c=0.1, q_every_step=True,
