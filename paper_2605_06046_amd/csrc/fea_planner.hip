@@ -127,7 +127,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
         unsigned short glist[kGroupMax];        // then the list of viable leaders
     } w;
     __shared__ int s_tmp[64];
-    __shared__ int s_ngroups, s_ngrouped, s_shared_blocks, s_nflw, s_nest;
+    __shared__ int s_ngroups, s_ngrouped, s_shared_blocks, s_nflw, s_nest, s_adopt;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -245,9 +245,10 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
             }
         }
     };
-    lcp_pass(s_nflw, s_lead, [](int) { return 0; }, [&](int who, int first, int mine) {
-        atomicMin(&s_lcpv[who], ((unsigned long long)(uint32_t)first << 32) | (uint32_t)mine);   // the run and the block that ends it
-    });
+    auto note_run_end = [&](int who, int first, int mine) {   // the run and the follower's block that ends it
+        atomicMin(&s_lcpv[who], ((unsigned long long)(uint32_t)first << 32) | (uint32_t)mine);
+    };
+    lcp_pass(s_nflw, s_lead, [](int) { return 0; }, note_run_end);
     __syncthreads();
 
     // A 32-token tile costs a wave more the more query rows ride on it: weights in
@@ -268,100 +269,118 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
     // leader's subgroup and its run there is lcp itself; if lcp == run, the block that
     // tells its subgroup sits in column lcp - the very entry the run detection stopped at,
     // which it hands over together with the column (no further memory round trip).
-    // Stage by stage: (1) round-one runs, sizes and ranks; (2) keys into a hash table of
-    // their own; (3) subgroup leaders.  With nothing nested that is all (two barriers more
-    // than without this round) and the round-one results stand.
+    // Stage by stage: (1) runs, sizes (and, the first time, ranks) of the groups as they
+    // are; (2) keys into a hash table of their own; (3) subgroup leaders.  With nothing
+    // nested that is all (two barriers more than without this round) and the results of
+    // (1) stand.  Otherwise the subgroups' runs are measured and the ones that pay split
+    // off; those are looked at again (a further level of sharing), kMaxLevels times at most.
+    // Members left behind, and subgroups that stay, are final.
     constexpr int kPer = kGroupReqMax / kPlanThreads;
+    constexpr int kMaxLevels = 4;
     int my_rank[kPer];
     {
-        int r1[kPer], lead1[kPer], lcp1[kPer];
-        bool in[kPer];
-        if (tid == 0) { s_nflw = 0; s_nest = 0; }
+        int lead1[kPer];
+        bool act[kPer];          // still part of a group that may split further
+        bool regroup = false;    // groups changed after the first stage (1): stats and ranks are redone
 #pragma unroll
         for (int k = 0; k < kPer; ++k) {
             const int i = tid + k * kPlanThreads;
             lead1[k] = i < nG ? (int)s_lead[i] : -1;
-            lcp1[k] = 0;
-            my_key[k] = -1;
+            act[k] = lead1[k] >= 0;
             my_rank[k] = 0;
-            if (lead1[k] >= 0) {
-                const unsigned long long lv = s_lcpv[i];
-                lcp1[k] = (int)(lv >> 32);
-                v.x.lcp[i] = lcp1[k];
-                if (lead1[k] != i && lcp1[k] < s_len[i] / kBlock) {
-                    // the block in the column where the follower left its leader: the run detection saw it,
-                    // unless the leader's row simply ended there
-                    my_key[k] = (uint32_t)lv != 0xFFFFFFFFu ? (int)(uint32_t)lv : a.bt[(size_t)i * a.stride + lcp1[k]];
-                }
-                atomicMin(&u.c.run[lead1[k]], lcp1[k]);
-                my_rank[k] = atomicAdd(&u.c.cnt[lead1[k]], 1);
-            }
         }
-        __syncthreads();
+        for (int level = 0; level < kMaxLevels; ++level) {
+            int r1[kPer], lcp1[kPer];
+            bool in[kPer];
+            if (tid == 0) { s_nflw = 0; s_nest = 0; s_adopt = 0; }
 #pragma unroll
-        for (int k = 0; k < kPer; ++k) {
-            in[k] = lead1[k] >= 0 && u.c.cnt[lead1[k]] >= 2 && u.c.run[lead1[k]] >= a.tune.min_run;
-            r1[k] = in[k] ? u.c.run[lead1[k]] : 0;
-            if (!in[k] || lcp1[k] > r1[k]) my_key[k] = -1;      // only the members that leave the leader at the run
-            const int key = my_key[k];
-            if (key >= 0) {
-                uint32_t s = slot_of(key);
-                for (;;) {
-                    const int old = atomicCAS(&h2.keys[s], -1, key);
-                    if (old == -1 || old == key) { atomicMin(&h2.vals[s], tid + k * kPlanThreads); break; }
-                    s = (s + 1) & (kHashSlots - 1);
+            for (int k = 0; k < kPer; ++k) {
+                const int i = tid + k * kPlanThreads;
+                lcp1[k] = 0;
+                my_key[k] = -1;
+                if (act[k]) {
+                    const unsigned long long lv = s_lcpv[i];
+                    lcp1[k] = (int)(lv >> 32);
+                    v.x.lcp[i] = lcp1[k];
+                    if (lead1[k] != i && lcp1[k] < s_len[i] / kBlock) {
+                        // the block in the column where the follower left its leader: the run detection saw
+                        // it, unless the leader's row simply ended there
+                        my_key[k] = (uint32_t)lv != 0xFFFFFFFFu ? (int)(uint32_t)lv : a.bt[(size_t)i * a.stride + lcp1[k]];
+                    }
+                    atomicMin(&u.c.run[lead1[k]], lcp1[k]);
+                    const int rank = atomicAdd(&u.c.cnt[lead1[k]], 1);
+                    if (level == 0) my_rank[k] = rank;
                 }
             }
-        }
-        __syncthreads();
-        int lead2[kPer];
+            __syncthreads();
 #pragma unroll
-        for (int k = 0; k < kPer; ++k) {
-            const int i = tid + k * kPlanThreads;
-            lead2[k] = -1;
-            const int key = my_key[k];
-            if (key >= 0) {
-                uint32_t s = slot_of(key);
-                while (h2.keys[s] != key) s = (s + 1) & (kHashSlots - 1);
-                const int cand = h2.vals[s];
-                lead2[k] = s_lead[cand] == lead1[k] ? cand : i;     // only within the same outer group
-                v.x.lcp[i] = min(s_len[i], s_len[lead2[k]]) / kBlock;
-                if (lead2[k] != i) w.flw[atomicAdd(&s_nflw, 1)] = (unsigned short)i;
-            } else if (in[k] && (lead1[k] == i || lcp1[k] > r1[k])) {
-                lead2[k] = lead1[k];                                // the leader's own subgroup: runs are known
-                if (lead1[k] != i) atomicAdd(&s_nest, 1);
+            for (int k = 0; k < kPer; ++k) {
+                in[k] = act[k] && u.c.cnt[lead1[k]] >= 2 && u.c.run[lead1[k]] >= a.tune.min_run;
+                r1[k] = in[k] ? u.c.run[lead1[k]] : 0;
+                if (!in[k] || lcp1[k] > r1[k]) my_key[k] = -1;      // only the members that leave the leader at the run
+                const int key = my_key[k];
+                if (key >= 0) {
+                    uint32_t s = slot_of(key);
+                    for (;;) {
+                        const int old = atomicCAS(&h2.keys[s], -1, key);
+                        if (old == -1 || old == key) { atomicMin(&h2.vals[s], tid + k * kPlanThreads); break; }
+                        s = (s + 1) & (kHashSlots - 1);
+                    }
+                }
             }
-            if (i < nG) { v.x.lead2[i] = (short)lead2[k]; s_r1[i] = (unsigned short)min(r1[k], 65535); }
-        }
-        __syncthreads();
-        const int nflw2 = s_nflw;
-        if (nflw2 + s_nest > 0) {                  // uniform
+            __syncthreads();
+            int lead2[kPer];
+#pragma unroll
+            for (int k = 0; k < kPer; ++k) {
+                const int i = tid + k * kPlanThreads;
+                lead2[k] = -1;
+                const int key = my_key[k];
+                if (key >= 0) {
+                    uint32_t s = slot_of(key);
+                    while (h2.keys[s] != key) s = (s + 1) & (kHashSlots - 1);
+                    const int cand = h2.vals[s];
+                    lead2[k] = s_lead[cand] == lead1[k] ? cand : i;     // only within the same outer group
+                    s_lcpv[i] = ((unsigned long long)(uint32_t)(min(s_len[i], s_len[lead2[k]]) / kBlock) << 32) | 0xFFFFFFFFull;
+                    if (lead2[k] != i) w.flw[atomicAdd(&s_nflw, 1)] = (unsigned short)i;
+                } else if (in[k] && (lead1[k] == i || lcp1[k] > r1[k])) {
+                    lead2[k] = lead1[k];                                // the leader's own subgroup: runs are known
+                    if (lead1[k] != i) atomicAdd(&s_nest, 1);
+                }
+                if (i < nG) { v.x.lead2[i] = (short)lead2[k]; s_r1[i] = (unsigned short)min(r1[k], 65535); }
+            }
+            __syncthreads();
+            const int nflw2 = s_nflw;
+            if (nflw2 + s_nest == 0) break;            // uniform: nothing (more) is nested
+            regroup = true;
             if (nflw2 > 0) {
-                lcp_pass(nflw2, v.x.lead2, [&](int i) { return (int)s_r1[i]; },
-                         [&](int who, int first, int) { atomicMin(&v.x.lcp[who], first); });
+                lcp_pass(nflw2, v.x.lead2, [&](int i) { return (int)s_r1[i]; }, note_run_end);
                 __syncthreads();
             }
             reset_groups(INT_MAX);
             __syncthreads();
+            int lcp2[kPer];
 #pragma unroll
-            for (int k = 0; k < kPer; ++k) {       // runs and sizes of the subgroups
+            for (int k = 0; k < kPer; ++k) {           // runs and sizes of the subgroups
                 const int i = tid + k * kPlanThreads;
-                if (lead2[k] >= 0) { atomicMin(&u.c.run[lead2[k]], v.x.lcp[i]); atomicAdd(&u.c.cnt[lead2[k]], 1); }
+                lcp2[k] = 0;
+                if (lead2[k] >= 0) {
+                    lcp2[k] = (int)(s_lcpv[i] >> 32);
+                    atomicMin(&u.c.run[lead2[k]], lcp2[k]);
+                    atomicAdd(&u.c.cnt[lead2[k]], 1);
+                }
             }
             __syncthreads();
             bool adopt[kPer];
-            int run2[kPer];
 #pragma unroll
             for (int k = 0; k < kPer; ++k) {
                 adopt[k] = false;
-                run2[k] = 0;
                 if (lead2[k] >= 0) {
-                    const int c2 = u.c.cnt[lead2[k]];
-                    run2[k] = u.c.run[lead2[k]];
+                    const int c2 = u.c.cnt[lead2[k]], run2 = u.c.run[lead2[k]];
                     // private sweeps saved plus the outer group's relief against the subgroup's own sweep
-                    const long long gain = 16ll * c2 * (run2[k] - r1[k]) + (long long)r1[k] * tile_weight(a.mpt * a.G) * by_mpt.div(c2);
-                    const long long cost = (long long)run2[k] * tile_weight(min(a.mpt, c2) * a.G) * by_mpt.cdiv(c2);
+                    const long long gain = 16ll * c2 * (run2 - r1[k]) + (long long)r1[k] * tile_weight(a.mpt * a.G) * by_mpt.div(c2);
+                    const long long cost = (long long)run2 * tile_weight(min(a.mpt, c2) * a.G) * by_mpt.cdiv(c2);
                     adopt[k] = c2 >= 2 && gain > cost;
+                    if (adopt[k] && lead2[k] == tid + k * kPlanThreads) atomicAdd(&s_adopt, 1);
                 }
                 if (in[k] && !adopt[k]) atomicMin(&u.c.moff[lead1[k]], tid + k * kPlanThreads);   // who leads the rest
             }
@@ -369,16 +388,27 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
             int lead_f[kPer];
 #pragma unroll
             for (int k = 0; k < kPer; ++k) lead_f[k] = adopt[k] ? lead2[k] : (in[k] ? u.c.moff[lead1[k]] : lead1[k]);
-            __syncthreads();                       // every leader is read before any changes
+            const bool again = s_adopt > 0 && level + 1 < kMaxLevels;
+            __syncthreads();                           // every leader is read before any changes
 #pragma unroll
             for (int k = 0; k < kPer; ++k) {
                 const int i = tid + k * kPlanThreads;
                 if (in[k]) {
                     s_lead[i] = (short)lead_f[k];
-                    v.x.lcp[i] = adopt[k] ? run2[k] : r1[k];
+                    v.x.lcp[i] = adopt[k] ? lcp2[k] : r1[k];
                 }
+                lead1[k] = lead_f[k];
+                act[k] = adopt[k];
             }
+            if (!again) break;                         // uniform
+            // the groups that split off are looked at again, with clean tables
+            for (int s = tid; s < kHashSlots; s += kPlanThreads) { h2.keys[s] = -1; h2.vals[s] = INT_MAX; }
             reset_groups(0);   // every thread changed only its own requests' entries above
+            __syncthreads();
+        }
+        if (regroup) {
+            __syncthreads();
+            reset_groups(0);
             __syncthreads();
             // runs, sizes and ranks of the groups as they are now
 #pragma unroll

@@ -424,3 +424,35 @@ def test_many_small_groups():
     out, bt, lens, info = run_workload(wl)
     assert info["groups"] == 500 and info["grouped_requests"] == spec.batch and info["overflow"] == 0
     assert_close(out, oracle_for(wl, bt, lens), "bf16", what="500 small groups")
+
+
+def test_three_level_prefix_sharing():
+    """A system prompt (64 tokens) shared by 16 requests, four conversations of four sharing 160 more,
+    and in each conversation two pairs sharing 320 more: the planner follows the sharing down level by
+    level (every split pays by the tile weights), ending with eight pairs whose run is 4 + 10 + 20 blocks."""
+    rng = np.random.default_rng(51)
+    draw = lambda n: rng.integers(0, W.VOCAB, size=n, dtype=np.int32)
+    top = draw(64)
+    seqs = []
+    for conv in range(4):
+        mid = draw(160)
+        for pair in range(2):
+            deep = draw(320)
+            for _ in range(2):
+                seqs.append(np.concatenate([top, mid, deep, draw(int(rng.integers(1, 60)))]))
+    order = rng.permutation(len(seqs))
+    seqs = [seqs[j] for j in order]
+    spec = W.Spec("three_levels", 43, "bf16", 32, 8, 128, ((len(seqs), 0),), (1, 1))
+    base = W.generate(spec)
+    offs = np.zeros(len(seqs) + 1, dtype=np.int64)
+    offs[1:] = np.cumsum([len(x) for x in seqs])
+    nblk = int(sum(-(-len(x) // 16) for x in seqs))
+    rs = np.random.default_rng(52)
+    k = W.f32_to_bf16_bits(rs.standard_normal((nblk, 8, 16, 128), dtype=np.float32))
+    v = W.f32_to_bf16_bits(rs.standard_normal((nblk, 8, 16, 128), dtype=np.float32))
+    wl = dataclasses.replace(base, tokens=np.concatenate(seqs), tok_offsets=offs, k_cache=k, v_cache=v, num_blocks=nblk,
+                             max_blocks_per_seq=max(-(-len(x) // 16) for x in seqs) + 1,
+                             group_of=np.zeros(len(seqs), dtype=np.int32))
+    out, bt, lens, info = run_workload(wl)
+    assert_close(out, oracle_for(wl, bt, lens), "bf16", what="three sharing levels")
+    assert info["groups"] == 8 and info["grouped_requests"] == 16 and info["shared_blocks"] == 8 * 34
