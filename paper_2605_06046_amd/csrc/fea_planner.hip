@@ -95,6 +95,9 @@ __device__ int block_scan_excl(int v, int* s_tmp, int& total) {
     return base + x - v;
 }
 
+// Four neighbouring table columns, loadable from any 4-byte boundary.
+struct __attribute__((packed, aligned(4))) Cols4 { int32_t c[4]; };
+
 __device__ __forceinline__ uint32_t slot_of(int key) { return ((uint32_t)key * 2654435761u) >> 20; }  // 12 bits
 
 __device__ __forceinline__ void write_item(Item* it, int who, int g, int nrows, int mlist_off, int c0, int c1,
@@ -195,16 +198,15 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
     reset_groups(0);
 
     // ---- longest common run of block ids with the leader's row.  All (follower,
-    // column group) pairs are spread flat over the threads, eight at a time so that
+    // column group) pairs are spread flat over the threads, six at a time so that
     // their loads are in flight together; a mismatch lowers the follower's run with
     // an LDS atomic.  Columns below from(i) are known to agree and are not read.
     auto lcp_pass = [&](int nflw, const short* lead_of, auto&& from, auto&& hit) {
-        const bool vec = (a.stride % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.bt) & 15) == 0);
-        const int cpe = vec ? 4 : 1;                       // columns per element
-        const int epr = cdiv(a.stride, cpe);               // elements per row
+        constexpr int cpe = 4;                             // columns per element
+        const int epr = cdiv(a.stride, cpe);               // elements per row (the last one may be short)
         const FastDiv by_epr(max(epr, 1));
         const int total = nflw * epr;
-        constexpr int kBatch = 8;
+        constexpr int kBatch = 6;
         for (int e0 = tid; e0 < total; e0 += kBatch * kPlanThreads) {
             int4 xs[kBatch], ys[kBatch];
             int who[kBatch], col[kBatch], cap[kBatch];
@@ -222,12 +224,14 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
                         who[q] = i; col[q] = c; cap[q] = cp;
                         const int32_t* ri = a.bt + (size_t)i * a.stride + c;
                         const int32_t* rl = a.bt + (size_t)lead * a.stride + c;
-                        if (vec) {
-                            xs[q] = *reinterpret_cast<const int4*>(ri);
-                            ys[q] = *reinterpret_cast<const int4*>(rl);
-                        } else {
-                            xs[q] = make_int4(*ri, 0, 0, 0);
-                            ys[q] = make_int4(*rl, 0, 0, 0);
+                        if (c + cpe <= a.stride) {          // rows need not start on 16-byte boundaries
+                            const Cols4 x = *reinterpret_cast<const Cols4*>(ri), y = *reinterpret_cast<const Cols4*>(rl);
+                            xs[q] = make_int4(x.c[0], x.c[1], x.c[2], x.c[3]);
+                            ys[q] = make_int4(y.c[0], y.c[1], y.c[2], y.c[3]);
+                        } else {                            // the row's last, short element
+                            const bool two = c + 1 < a.stride, three = c + 2 < a.stride;
+                            xs[q] = make_int4(ri[0], two ? ri[1] : 0, three ? ri[2] : 0, 0);
+                            ys[q] = make_int4(rl[0], two ? rl[1] : 0, three ? rl[2] : 0, 0);
                         }
                     }
                 }
