@@ -27,6 +27,7 @@ static bool is_pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
 struct Resolved {
     int variant;      // 0 generic, 1 MFMA
     int G, mpt, grouping, split_user, grid;
+    int pre, pre_grid;   // leaders and common runs on many workgroups first (large tables)
     PlanTuning tune;
     WsLayout lay;
 };
@@ -90,6 +91,14 @@ static int32_t resolve(const fea_attn_params* p, int32_t B, int32_t stride, Reso
     r.tune.min_piece = std::max(1, env_int("FEA_MIN_PIECE", 4));
     r.tune.min_run = std::max(1, env_int("FEA_MIN_RUN", 2));
     r.tune.weights = std::min(255, std::max(16, env_int("FEA_W32", 20))) | (std::min(255, std::max(16, env_int("FEA_W64", 24))) << 8);
+    // Large tables: the rows are compared on many workgroups before the planner's one workgroup
+    // takes over (a second launch, so only where the rows are long or many enough to pay for it).
+    const int64_t groupable = std::min(B, kGroupReqMax);
+    // (measured: 256 requests x 320 columns 30 -> 24 us, 800 x 657 105 -> 35 us; 32 x 2082 no gain, hence
+    // the request count; a batch that shares nothing pays about 3 us for it)
+    const int run_min = env_int("FEA_RUN_KERNEL_MIN", 49152);
+    r.pre = r.grouping && (run_min == 0 || (groupable >= 128 && groupable * stride >= run_min)) ? 1 : 0;
+    r.pre_grid = (int)std::max<int64_t>(1, std::min<int64_t>(2 * cu_count(), (groupable + 3) / 4));
     const int64_t rows = (int64_t)B * p->num_q_heads;
     const int64_t segs = 2ll * B * p->num_kv_heads;          // private segments + at most as many shared ones
     const int64_t rows_per_item = std::max(kTileRows, r.mpt * r.G);
@@ -113,6 +122,7 @@ static int32_t resolve(const fea_attn_params* p, int32_t B, int32_t stride, Reso
     l.items = off;    off += up256((size_t)max_items * sizeof(Item));
     l.ml = off;       off += up256((size_t)max_rows * 2 * sizeof(float));
     l.acc = off;      off += up256((size_t)max_rows * p->head_dim * sizeof(float));
+    l.pre = off;      off += up256((size_t)kGroupReqMax * (sizeof(uint64_t) + sizeof(int32_t)));
     l.total = off;
     l.max_items = (int32_t)max_items;
     l.max_rows = (int32_t)max_rows;
@@ -188,6 +198,8 @@ int32_t fea_decode_attention(const fea_attn_params* p, const void* q, const void
         pa.grouping = r.grouping;
         pa.split_user = r.split_user;
         pa.variant = r.variant;
+        pa.pre = r.pre;
+        pa.pre_grid = r.pre_grid;
         launch_plan(pa, where[0]);
     }
     if (plan_only) {

@@ -72,7 +72,7 @@ static_assert(sizeof(Item) == 32, "Item is read as two 16-byte words");
 
 // Byte offsets of the workspace sections (all multiples of 256).
 struct WsLayout {
-    size_t req, grp, members, segs, wave_first, items, ml, acc, total;
+    size_t req, grp, members, segs, wave_first, items, ml, acc, pre, total;
     int32_t max_items, max_rows;
 };
 
@@ -95,7 +95,14 @@ struct PlanArgs {
     int32_t grouping;    // 0: every request on its own
     int32_t split_user;  // 0: choose
     int32_t variant;
+    int32_t pre;         // leaders and common runs come from run_kernel (workspace section `pre`)
+    int32_t pre_grid;    // its grid
 };
+
+// What run_kernel leaves for the planner, per groupable request: the run it shares with its
+// leader and its own block in the column where that run ends (as one 64-bit word, run in the
+// upper half, 0xFFFFFFFF where no such block was seen), then the leaders as int32.
+constexpr int kRunThreads = 256;
 
 // Everything the sweep and merge kernels need besides the plan in the workspace.
 struct SweepArgs {

@@ -107,6 +107,112 @@ __device__ __forceinline__ void write_item(Item* it, int who, int g, int nrows, 
     p[1] = make_int4(c0, c1, pbase, tok_end);
 }
 
+// Leaders and common runs for large tables, on many workgroups (the planner's one
+// workgroup would pull every follower's and leader's row through a single CU: 71 of its
+// 105 us for 800 requests of 10K tokens).  Every workgroup finds the leaders for itself
+// (smallest request index per first block; a few thousand LDS operations), then its waves
+// take followers in turn: 64 lanes x 4 columns per step, the first differing column and the
+// follower's block there picked from the lowest lane that saw a difference.
+__global__ __launch_bounds__(kRunThreads) void run_kernel(PlanArgs a) {
+    __shared__ int keys[kHashSlots], vals[kHashSlots];
+    __shared__ int s_len[kGroupReqMax];
+    __shared__ short s_lead[kGroupReqMax];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int nG = a.grouping ? min(a.B, kGroupReqMax) : 0;
+    const int maxL = a.stride * kBlock;
+    constexpr int kPer = kGroupReqMax / kRunThreads;
+    for (int s = tid; s < kHashSlots; s += kRunThreads) { keys[s] = -1; vals[s] = INT_MAX; }
+    __syncthreads();
+    int my_key[kPer];
+#pragma unroll
+    for (int k = 0; k < kPer; ++k) {
+        const int i = tid + k * kRunThreads;
+        my_key[k] = -1;
+        if (i < nG) {
+            const int L = max(0, min(a.seq_lens[i], maxL));
+            s_len[i] = L;
+            if (L >= kBlock) {
+                const int key = a.bt[(size_t)i * a.stride];
+                my_key[k] = key;
+                if (key >= 0) {
+                    uint32_t s = slot_of(key);
+                    for (;;) {
+                        const int old = atomicCAS(&keys[s], -1, key);
+                        if (old == -1 || old == key) { atomicMin(&vals[s], i); break; }
+                        s = (s + 1) & (kHashSlots - 1);
+                    }
+                }
+            }
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < kPer; ++k) {
+        const int i = tid + k * kRunThreads;
+        if (i < nG) {
+            int lead = -1;
+            const int key = my_key[k];
+            if (key >= 0) {
+                uint32_t s = slot_of(key);
+                while (keys[s] != key) s = (s + 1) & (kHashSlots - 1);
+                lead = vals[s];
+            }
+            s_lead[i] = (short)lead;
+        }
+    }
+    __syncthreads();
+    unsigned long long* pre = reinterpret_cast<unsigned long long*>(a.ws + a.lay.pre);
+    int* pre_lead = reinterpret_cast<int*>(pre + kGroupReqMax);
+    const int waves = gridDim.x * (kRunThreads / 64);
+    for (int i = blockIdx.x * (kRunThreads / 64) + (tid >> 6); i < nG; i += waves) {
+        const int lead = s_lead[i];
+        const int cp = lead >= 0 ? min(s_len[i], s_len[lead]) / kBlock : 0;
+        unsigned long long res = ((unsigned long long)(uint32_t)cp << 32) | 0xFFFFFFFFull;
+        if (lead >= 0 && lead != i) {
+            const int32_t* ri = a.bt + (size_t)i * a.stride;
+            const int32_t* rl = a.bt + (size_t)lead * a.stride;
+            constexpr int kWin = 4;   // column windows (64 lanes x 4 columns) requested together
+            bool done = false;
+            for (int c0 = 0; c0 < cp && !done; c0 += 256 * kWin) {
+                int4 x[kWin], y[kWin];
+#pragma unroll
+                for (int u = 0; u < kWin; ++u) {
+                    const int c = c0 + u * 256 + lane * 4;
+                    x[u] = y[u] = make_int4(0, 0, 0, 0);
+                    if (c < cp) {
+                        if (c + 4 <= a.stride) {
+                            const Cols4 xv = *reinterpret_cast<const Cols4*>(ri + c), yv = *reinterpret_cast<const Cols4*>(rl + c);
+                            x[u] = make_int4(xv.c[0], xv.c[1], xv.c[2], xv.c[3]);
+                            y[u] = make_int4(yv.c[0], yv.c[1], yv.c[2], yv.c[3]);
+                        } else {
+                            const bool two = c + 1 < a.stride, three = c + 2 < a.stride;
+                            x[u] = make_int4(ri[c], two ? ri[c + 1] : 0, three ? ri[c + 2] : 0, 0);
+                            y[u] = make_int4(rl[c], two ? rl[c + 1] : 0, three ? rl[c + 2] : 0, 0);
+                        }
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < kWin; ++u) {
+                    const int c = c0 + u * 256 + lane * 4;
+                    int first = INT_MAX, mine = 0;
+                    if (x[u].w != y[u].w) { first = c + 3; mine = x[u].w; }
+                    if (x[u].z != y[u].z) { first = c + 2; mine = x[u].z; }
+                    if (x[u].y != y[u].y) { first = c + 1; mine = x[u].y; }
+                    if (x[u].x != y[u].x) { first = c; mine = x[u].x; }
+                    const unsigned long long seen = __ballot(!done && first < cp);
+                    if (seen) {   // lanes hold rising columns: the lowest lane has the first difference
+                        const int src = __ffsll((long long)seen) - 1;
+                        const int f0 = __shfl(first, src), m0 = __shfl(mine, src);
+                        res = ((unsigned long long)(uint32_t)f0 << 32) | (uint32_t)m0;
+                        done = true;
+                    }
+                }
+            }
+        }
+        if (lane == 0) { pre[i] = res; pre_lead[i] = lead; }
+    }
+}
+
 constexpr int kGroupMax = kGroupReqMax / 2;   // a group has at least two members
 
 __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
@@ -147,51 +253,64 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
     const int maxL = a.stride * kBlock;
     auto clampL = [&](int L) { return max(0, min(L, maxL)); };
 
-    // ---- leaders: smallest request index among those with the same first block
-    for (int s = tid; s < kHashSlots; s += kPlanThreads) { u.h.keys[s] = -1; u.h.vals[s] = INT_MAX; h2.keys[s] = -1; h2.vals[s] = INT_MAX; }
-    if (tid == 0) { s_ngroups = 0; s_ngrouped = 0; s_shared_blocks = 0; s_nflw = 0; }
-    __syncthreads();
     int my_key[kGroupReqMax / kPlanThreads];
+    for (int s = tid; s < kHashSlots; s += kPlanThreads) { h2.keys[s] = -1; h2.vals[s] = INT_MAX; }
+    if (tid == 0) { s_ngroups = 0; s_ngrouped = 0; s_shared_blocks = 0; s_nflw = 0; }
+    if (a.pre) {
+        // ---- leaders and common runs were found by run_kernel
+        const unsigned long long* pre = reinterpret_cast<const unsigned long long*>(a.ws + a.lay.pre);
+        const int* pre_lead = reinterpret_cast<const int*>(pre + kGroupReqMax);
+        for (int i = tid; i < nG; i += kPlanThreads) {
+            s_len[i] = clampL(a.seq_lens[i]);
+            s_lead[i] = (short)pre_lead[i];
+            s_lcpv[i] = pre[i];
+        }
+        __syncthreads();
+    } else {
+        // ---- leaders: smallest request index among those with the same first block
+        for (int s = tid; s < kHashSlots; s += kPlanThreads) { u.h.keys[s] = -1; u.h.vals[s] = INT_MAX; }
+        __syncthreads();
 #pragma unroll
-    for (int k = 0; k < kGroupReqMax / kPlanThreads; ++k) {
-        const int i = tid + k * kPlanThreads;
-        my_key[k] = -1;
-        if (i < nG) {
-            const int L = clampL(a.seq_lens[i]);
-            s_len[i] = L;
-            if (L >= kBlock) {
-                const int key = a.bt[(size_t)i * a.stride];
-                my_key[k] = key;
-                if (key >= 0) {
-                    uint32_t s = slot_of(key);
-                    for (;;) {
-                        const int old = atomicCAS(&u.h.keys[s], -1, key);
-                        if (old == -1 || old == key) { atomicMin(&u.h.vals[s], i); break; }
-                        s = (s + 1) & (kHashSlots - 1);
+        for (int k = 0; k < kGroupReqMax / kPlanThreads; ++k) {
+            const int i = tid + k * kPlanThreads;
+            my_key[k] = -1;
+            if (i < nG) {
+                const int L = clampL(a.seq_lens[i]);
+                s_len[i] = L;
+                if (L >= kBlock) {
+                    const int key = a.bt[(size_t)i * a.stride];
+                    my_key[k] = key;
+                    if (key >= 0) {
+                        uint32_t s = slot_of(key);
+                        for (;;) {
+                            const int old = atomicCAS(&u.h.keys[s], -1, key);
+                            if (old == -1 || old == key) { atomicMin(&u.h.vals[s], i); break; }
+                            s = (s + 1) & (kHashSlots - 1);
+                        }
                     }
                 }
             }
         }
-    }
-    __syncthreads();
+        __syncthreads();
 #pragma unroll
-    for (int k = 0; k < kGroupReqMax / kPlanThreads; ++k) {
-        const int i = tid + k * kPlanThreads;
-        if (i < nG) {
-            int lead = -1, lcp = 0;
-            const int key = my_key[k];
-            if (key >= 0) {
-                uint32_t s = slot_of(key);
-                while (u.h.keys[s] != key) s = (s + 1) & (kHashSlots - 1);
-                lead = u.h.vals[s];
-                lcp = min(s_len[i], s_len[lead]) / kBlock;
-                if (lead != i) w.flw[atomicAdd(&s_nflw, 1)] = (unsigned short)i;
+        for (int k = 0; k < kGroupReqMax / kPlanThreads; ++k) {
+            const int i = tid + k * kPlanThreads;
+            if (i < nG) {
+                int lead = -1, lcp = 0;
+                const int key = my_key[k];
+                if (key >= 0) {
+                    uint32_t s = slot_of(key);
+                    while (u.h.keys[s] != key) s = (s + 1) & (kHashSlots - 1);
+                    lead = u.h.vals[s];
+                    lcp = min(s_len[i], s_len[lead]) / kBlock;
+                    if (lead != i) w.flw[atomicAdd(&s_nflw, 1)] = (unsigned short)i;
+                }
+                s_lead[i] = (short)lead;
+                s_lcpv[i] = ((unsigned long long)(uint32_t)lcp << 32) | 0xFFFFFFFFull;
             }
-            s_lead[i] = (short)lead;
-            s_lcpv[i] = ((unsigned long long)(uint32_t)lcp << 32) | 0xFFFFFFFFull;
         }
+        __syncthreads();   // the hash table is dead from here on; its memory becomes run/cnt/moff/...
     }
-    __syncthreads();   // the hash table is dead from here on; its memory becomes run/cnt/moff/...
     auto reset_groups = [&](int moff0) {
         for (int i = tid; i < nG; i += kPlanThreads) { u.c.run[i] = INT_MAX; u.c.cnt[i] = 0; u.c.moff[i] = moff0; }
     };
@@ -252,8 +371,10 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
     auto note_run_end = [&](int who, int first, int mine) {   // the run and the follower's block that ends it
         atomicMin(&s_lcpv[who], ((unsigned long long)(uint32_t)first << 32) | (uint32_t)mine);
     };
-    lcp_pass(s_nflw, s_lead, [](int) { return 0; }, note_run_end);
-    __syncthreads();
+    if (!a.pre) {
+        lcp_pass(s_nflw, s_lead, [](int) { return 0; }, note_run_end);
+        __syncthreads();
+    }
 
     // A 32-token tile costs a wave more the more query rows ride on it: weights in
     // sixteenths of a 16-row tile's sweep.
@@ -743,8 +864,14 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
 }
 
 void launch_plan(const PlanArgs& a, const Launch& L) {
-    hipExtLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, static_cast<hipStream_t>(L.stream),
-                          static_cast<hipEvent_t>(L.ev_start), static_cast<hipEvent_t>(L.ev_stop), 0, a);
+    hipStream_t st = static_cast<hipStream_t>(L.stream);
+    hipEvent_t e0 = static_cast<hipEvent_t>(L.ev_start), e1 = static_cast<hipEvent_t>(L.ev_stop);
+    if (a.pre) {   // the pair of events brackets both kernels
+        hipExtLaunchKernelGGL(run_kernel, dim3(a.pre_grid), dim3(kRunThreads), 0, st, e0, nullptr, 0, a);
+        hipExtLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, st, nullptr, e1, 0, a);
+    } else {
+        hipExtLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, st, e0, e1, 0, a);
+    }
 }
 
 }  // namespace fea

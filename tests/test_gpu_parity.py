@@ -456,3 +456,34 @@ def test_three_level_prefix_sharing():
     out, bt, lens, info = run_workload(wl)
     assert_close(out, oracle_for(wl, bt, lens), "bf16", what="three sharing levels")
     assert info["groups"] == 8 and info["grouped_requests"] == 16 and info["shared_blocks"] == 8 * 34
+
+
+@pytest.mark.parametrize("case", ["c2_small", "c3_small", "two_level", "nested_tables", "random_tables", "odd_stride"])
+def test_runs_found_on_many_workgroups_give_the_same_plan(case, monkeypatch):
+    """Large tables have their leaders and common runs found by a kernel of many workgroups before the
+    planner; forced on here for small ones: same plan (group counts, items, rows), bitwise the same output."""
+    if case in ("c2_small", "c3_small"):
+        wl = W.generate(W.scaled(W.CONFIGS[case[:2]], **SMALL[case[:2]]))
+        bt, lens = library_tables(wl)
+        q, k, v, s = wl.q, wl.k_cache, wl.v_cache, wl.spec
+        shape = (s.num_q_heads, s.num_kv_heads, s.head_dim, s.dtype)
+    elif case == "two_level":
+        wl = _radix_workload("bf16", 96, [(5, 160), (4, 64), (2, 16)], 3)
+        bt, lens = library_tables(wl)
+        q, k, v, shape = wl.q, wl.k_cache, wl.v_cache, (32, 8, 128, "bf16")
+    else:
+        lens_l = [0, 160, 161, 500, 512, 100, 160, 160, 700, 48, 64, 49, 1000]
+        mode = {"nested_tables": "nested", "random_tables": "same_first_then_random", "odd_stride": "nested"}[case]
+        bt, k, v = _random_tables(7, len(lens_l), 8, 128, "bf16", lens_l, 40, mode)
+        if case == "odd_stride":
+            bt = np.ascontiguousarray(np.concatenate([bt, np.full((bt.shape[0], 3 - bt.shape[1] % 2), -1, np.int32)], axis=1))
+            assert bt.shape[1] % 4 != 0
+        lens = np.array(lens_l, dtype=np.int32)
+        q = W.f32_to_bf16_bits(np.random.default_rng(5).standard_normal((len(lens_l), 32, 128), dtype=np.float32))
+        shape = (32, 8, 128, "bf16")
+    base, info = run_hip(q, k, v, bt, lens, *shape)
+    monkeypatch.setenv("FEA_RUN_KERNEL_MIN", "0")
+    forced, info2 = run_hip(q, k, v, bt, lens, *shape)
+    assert info2 == info
+    assert np.array_equal(base, forced)
+    assert_close(forced, decode_attention(values(q), values(k), values(v), bt, lens), "bf16", what=case)
