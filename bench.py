@@ -227,22 +227,22 @@ def cpu_baseline(case, budget_s=12.0):
                       f"(all heads, full history each), {dt:.1f} s wall"}
 
 
-def traffic_from_profile(workload):
-    """HBM bytes per sweep launch from the committed counter summary, if it is current."""
+def traffic_from_profile(workload, plan):
+    """HBM bytes per sweep launch from the committed counter summary, if it is current: taken with
+    this sweep kernel source and with the plan (items, partial rows, groups, piece size) that the
+    kernel executes now."""
     path = os.path.join(ROOT, "profiles", f"sweep_mfma_{workload}_pmc.json")
     try:
         d = json.load(open(path))
-        return d.get("traffic_bytes_per_launch") if d.get("kernel_rev") == kernel_rev() else None
+        same = d.get("kernel_rev") == kernel_rev() and d.get("plan") == plan
+        return d.get("traffic_bytes_per_launch") if same else None
     except Exception:
         return None
 
 
 def kernel_rev():
-    import hashlib
-    h = hashlib.sha256()
-    for f in ("fea_sweep_mfma.hip", "fea_planner.hip", "fea_plan.h"):
-        h.update(open(os.path.join(ROOT, "paper_2605_06046_amd", "csrc", f), "rb").read())
-    return h.hexdigest()[:12]
+    from paper_2605_06046_amd.profile_summary import kernel_rev as rev
+    return rev(ROOT)
 
 
 def main():
@@ -309,7 +309,7 @@ def main():
                                      "tokens_per_s": case.B / (m["ms_per_call_plan_shared_by_32_layers"] * 1e-3)},
         "host_table_build": {"ms": m["table_build_ms"], "tokens_per_s": m["table_build_tokens_per_s"]},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic_from_profile(args.workload),
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic_from_profile(args.workload, m["plan"]),
                      "kernel": "sweep_mfma_kernel" if m["plan"]["variant"] == 1 else "sweep_generic_kernel",
                      "bytes_per_launch": case.unique_bytes},
     }

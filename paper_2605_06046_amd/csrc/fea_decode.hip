@@ -34,7 +34,7 @@ struct Resolved {
 
 // Optional per-kernel timing: each launch can carry a pair of library-owned events that
 // take the start and end time of that dispatch itself (no marker packets in between).
-constexpr int kEvPerCall = 6;               // (start, stop) for plan, sweep, merge
+constexpr int kEvPerCall = 8;               // (start, stop) for plan, sweep, merge, and the inner pair of a two-dispatch plan
 static bool g_prof_on = false;
 static std::vector<hipEvent_t> g_ev_pool;   // kEvPerCall events per recorded call
 static int g_prof_calls = 0;                // calls recorded since profiling was switched on
@@ -176,6 +176,7 @@ int32_t fea_decode_attention(const fea_attn_params* p, const void* q, const void
             if (k > 0 && plan_only) continue;
             where[k].ev_start = ev[2 * k];
             where[k].ev_stop = ev[2 * k + 1];
+            if (k == 0) { where[0].ev_mid[0] = ev[6]; where[0].ev_mid[1] = ev[7]; }
             mask |= (unsigned char)(1u << k);
         }
         g_prof_mask[slot] = mask;

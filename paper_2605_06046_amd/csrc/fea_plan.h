@@ -124,6 +124,7 @@ struct Launch {
     void* stream;
     void* ev_start;
     void* ev_stop;
+    void* ev_mid[2] = {nullptr, nullptr};   // where a step is two dispatches: end of the first, start of the second
 };
 
 void launch_plan(const PlanArgs& a, const Launch& L);

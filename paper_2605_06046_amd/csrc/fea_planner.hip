@@ -866,9 +866,10 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
 void launch_plan(const PlanArgs& a, const Launch& L) {
     hipStream_t st = static_cast<hipStream_t>(L.stream);
     hipEvent_t e0 = static_cast<hipEvent_t>(L.ev_start), e1 = static_cast<hipEvent_t>(L.ev_stop);
-    if (a.pre) {   // the pair of events brackets both kernels
-        hipExtLaunchKernelGGL(run_kernel, dim3(a.pre_grid), dim3(kRunThreads), 0, st, e0, nullptr, 0, a);
-        hipExtLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, st, nullptr, e1, 0, a);
+    if (a.pre) {   // each dispatch gets a whole pair of events; the step runs from the first start to the last stop
+        hipExtLaunchKernelGGL(run_kernel, dim3(a.pre_grid), dim3(kRunThreads), 0, st, e0,
+                              static_cast<hipEvent_t>(L.ev_mid[0]), 0, a);
+        hipExtLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, st, static_cast<hipEvent_t>(L.ev_mid[1]), e1, 0, a);
     } else {
         hipExtLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, st, e0, e1, 0, a);
     }

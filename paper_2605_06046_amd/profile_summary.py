@@ -32,9 +32,11 @@ GIB_KIB = 1 << 20   # a 1 GiB copy moves this many KiB each way
 
 
 def kernel_rev(root: str) -> str:
+    """Identifies the sweep kernel's code: its source file.  The counters of a summary stay valid for
+    a build whose sweep source is the same and whose plan for the workload (stored next to them) is the
+    same, since the kernel then does the same loads and stores."""
     h = hashlib.sha256()
-    for f in ("fea_sweep_mfma.hip", "fea_planner.hip", "fea_plan.h"):
-        h.update(open(os.path.join(root, "paper_2605_06046_amd", "csrc", f), "rb").read())
+    h.update(open(os.path.join(root, "paper_2605_06046_amd", "csrc", "fea_sweep_mfma.hip"), "rb").read())
     return h.hexdigest()[:12]
 
 
@@ -92,6 +94,7 @@ def main(raw: str, wl: str, out: str) -> None:
     res["traffic_bytes_per_launch"] = total
     bench = json.loads(open(f"{raw}/trace_{wl}.json").read().strip().splitlines()[-1])
     res["unique_kv_bytes"] = bench["roofline"]["bytes_per_launch"]
+    res["plan"] = bench["plan"]
     lines += [f"  total {total / 1e6:.2f} MB per launch; algorithmic (distinct live KV blocks, K and V): "
               f"{res['unique_kv_bytes'] / 1e6:.2f} MB; ratio {total / res['unique_kv_bytes']:.3f}",
               "", "bench.py line of the traced run (events inside bench.py, same command; the profiler's interception adds to them):",
