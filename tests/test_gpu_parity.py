@@ -212,7 +212,7 @@ def test_profiling_events_bracket_each_kernel():
 
 
 @pytest.mark.gpu
-@pytest.mark.parametrize("B,prefix,Hq,Hkv", [(300, 320, 32, 8), (500, 96, 32, 8), (130, 512, 64, 8)])
+@pytest.mark.parametrize("B,prefix,Hq,Hkv", [(300, 320, 32, 8), (500, 96, 32, 8), (130, 512, 64, 8), (300, 3200, 32, 8)])
 def test_wide_prefix_groups(B, prefix, Hq, Hkv):
     """One prefix group far wider than a workgroup's row tiles (the paper's large homogeneous
     batches, Experiment 5): every request's rows against the oracle."""
