@@ -9,8 +9,8 @@ memory-side cache cannot serve them ("cold", the headline); a warm figure on a
 single replica is reported next to it.
 
 Prints ONE JSON line on stdout.  --suite additionally measures all five batch
-shapes and the homogeneous-vs-heterogeneous comparisons and writes them to
-gpurun_out/suite.jsonl.
+shapes and the homogeneous-vs-heterogeneous comparisons; it and the other extra
+modes write their lines as .jsonl files into the folder given by --out.
 """
 from __future__ import annotations
 
@@ -29,6 +29,7 @@ sys.path.insert(0, ROOT)
 import workloads as W  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0
+OUT_DIR = os.path.join(ROOT, "gpurun_out")   # --out
 
 
 def log(*a):
@@ -253,6 +254,7 @@ def main():
     ap.add_argument("--workload", default="c2", choices=sorted(W.CONFIGS))
     ap.add_argument("--graph", action="store_true", help="replay the steps from a captured HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--out", default=OUT_DIR, help="folder for the .jsonl files of the extra modes")
     ap.add_argument("--suite", action="store_true", help="also run all shapes and the homogeneity comparisons")
     ap.add_argument("--decode-loop", type=int, default=0, metavar="N",
                     help="also run N decode steps (extend, append, attend over the KV replicas as layers)")
@@ -269,8 +271,10 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run a plain 1 GiB device-to-device copy three times (known traffic, for counter runs)")
     args = ap.parse_args()
+    global OUT_DIR
+    OUT_DIR = args.out
     if args.gpus != 1:
-        log("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
+        log("bench.py: this library runs on one GPU only (no collectives, no sharding); use --gpus 1")
         sys.exit(2)
     import torch
     if not torch.cuda.is_available():
@@ -319,13 +323,13 @@ def main():
         line["cpu_baseline"] = None
 
     if args.decode_loop > 0:
-        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+        os.makedirs(OUT_DIR, exist_ok=True)
         res = decode_loop(args.decode_loop)
-        open(os.path.join(ROOT, "gpurun_out", "decode_loop.json"), "w").write(json.dumps(res) + "\n")
+        open(os.path.join(OUT_DIR, "decode_loop.json"), "w").write(json.dumps(res) + "\n")
         log(json.dumps(res))
     if args.scheduler and not args.suite:
-        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
-        with open(os.path.join(ROOT, "gpurun_out", "scheduler.jsonl"), "w") as f:
+        os.makedirs(OUT_DIR, exist_ok=True)
+        with open(os.path.join(OUT_DIR, "scheduler.jsonl"), "w") as f:
             del case
             torch.cuda.empty_cache()
             for res in scheduler_comparison(max(50, args.steps // 4), max(10, args.warmup // 2), args.graph):
@@ -335,17 +339,17 @@ def main():
                             (args.paper_shapes, "paper_shapes.jsonl", lambda: paper_shapes(max(50, args.steps // 4), max(10, args.warmup // 2))),
                             (args.policies > 0, "policies.jsonl", lambda: policy_comparison(args.policies))):
         if flag:
-            os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+            os.makedirs(OUT_DIR, exist_ok=True)
             case = None
             torch.cuda.empty_cache()
-            with open(os.path.join(ROOT, "gpurun_out", name), "w") as f:
+            with open(os.path.join(OUT_DIR, name), "w") as f:
                 for res in gen():
                     f.write(json.dumps(res) + "\n")
                     f.flush()
                     log(json.dumps(res))
     if args.suite:
-        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
-        with open(os.path.join(ROOT, "gpurun_out", "suite.jsonl"), "w") as f:
+        os.makedirs(OUT_DIR, exist_ok=True)
+        with open(os.path.join(OUT_DIR, "suite.jsonl"), "w") as f:
             f.write(json.dumps(m) + "\n")
             del case
             torch.cuda.empty_cache()

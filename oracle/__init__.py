@@ -20,7 +20,7 @@ What pins each function (see the tests that do not need a GPU):
 * hashing.chunk_hashes - count, cumulativity and the prefix-consistency
   property ("equal at level l iff equal first l*K tokens") follow the paper's
   worked example and Algorithm 2's structure.  The paper prints no hash values
-  and leaves Hash/InitConst open, so the *values* follow this build's written
+  and leaves Hash/InitConst open, so the *values* follow this library's written
   specification only: parity of hash values is "parity unpinned" beyond two
   independently written implementations agreeing bit for bit.
 * cht.ChunkedHashTree - the scheduler's sets and queries written out from their

@@ -6,7 +6,7 @@ hashed on its own into a leaf value, and the leaves are chained, h_c =
 Hash(h_{c-1} || leaf_c) with h_0 a fixed constant, so that h_c depends on
 exactly the first c*K tokens.  A trailing partial chunk also gets a hash.
 
-The paper leaves Hash and the initial constant open.  This build fixes them
+The paper leaves Hash and the initial constant open.  They are fixed here
 (all arithmetic modulo 2**64):
 
   mix(x):  x ^= x >> 30; x *= 0xBF58476D1CE4E5B9;

@@ -396,7 +396,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
     // which it hands over together with the column (no further memory round trip).
     // Stage by stage: (1) runs, sizes (and, the first time, ranks) of the groups as they
     // are; (2) keys into a hash table of their own; (3) subgroup leaders.  With nothing
-    // nested that is all (two barriers more than without this round) and the results of
+    // nested that is all (two barriers more than without this stage) and the results of
     // (1) stand.  Otherwise the subgroups' runs are measured and the ones that pay split
     // off; those are looked at again (a further level of sharing), kMaxLevels times at most.
     // Members left behind, and subgroups that stay, are final.
