@@ -247,6 +247,7 @@ def kernel_rev():
 
 
 def main():
+    global OUT_DIR
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=400)
@@ -271,7 +272,6 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run a plain 1 GiB device-to-device copy three times (known traffic, for counter runs)")
     args = ap.parse_args()
-    global OUT_DIR
     OUT_DIR = args.out
     if args.gpus != 1:
         log("bench.py: this library runs on one GPU only (no collectives, no sharding); use --gpus 1")
