@@ -459,17 +459,39 @@ def decode_loop(n_steps, layers=None):
     k_new = torch.randn(shape_new, generator=g, device="cuda").to(c.k.dtype)
     v_new = torch.randn(shape_new, generator=g, device="cuda").to(c.k.dtype)
     bt, lens = c.bt, c.lens
-    pin_l = torch.from_numpy(lens.copy()).pin_memory()
-    pin_t = torch.from_numpy(bt.copy()).pin_memory()
+    # One pinned staging slot per step: the device runs behind the host, and a slot that were written
+    # again before its copy has run would hand the device lengths that are ahead of its tables.
+    n_slots = n_steps + 5
+    pin_l = torch.empty((n_slots,) + lens.shape, dtype=torch.int32).pin_memory()
+    pin_t = torch.empty((n_slots,) + bt.shape, dtype=torch.int32).pin_memory()
+    slot = [0]
+
+    # the foreign calls with their arguments marshalled once: the loop is meant to show the device's
+    # pace, and a Python driver that converts tensors on every call would set it instead
+    lib = fea.load_library()
+    vp = C.c_void_p
+    sp = vp(torch.cuda.current_stream().cuda_stream)
+    n_new = C.c_int32()
+    ext_args = (c.pool.handle, vp(bt.ctypes.data), bt.shape[1], vp(lens.ctypes.data), c.B, C.byref(n_new))
+    app_args = [(C.byref(p_plan), vp(k_new.data_ptr()), vp(v_new.data_ptr()), vp(c.k[l].data_ptr()), vp(c.v[l].data_ptr()),
+                 vp(c.dbt.data_ptr()), bt.shape[1], vp(c.dl.data_ptr()), c.B, sp) for l in range(L)]
+    att_args = [(C.byref(p_plan if l == 0 else p_reuse),) + c._args[l][1:] + (sp,) for l in range(L)]
+    t_lens, t_bt = torch.from_numpy(lens), torch.from_numpy(bt)      # views of the host arrays the library updates
+
+    def check(rc):
+        if rc != 0:
+            raise RuntimeError(lib.fea_last_error().decode())
 
     def step():
-        n_new = fea.fea_kv_extend(c.pool, bt, lens)
-        pin_l.copy_(torch.from_numpy(lens)); c.dl.copy_(pin_l, non_blocking=True)
-        if n_new:
-            pin_t.copy_(torch.from_numpy(bt)); c.dbt.copy_(pin_t, non_blocking=True)
+        check(lib.fea_kv_extend(*ext_args))
+        j = slot[0]
+        slot[0] += 1
+        if n_new.value:      # tables first: lengths never get ahead of them on the device
+            pin_t[j].copy_(t_bt); c.dbt.copy_(pin_t[j], non_blocking=True)
+        pin_l[j].copy_(t_lens); c.dl.copy_(pin_l[j], non_blocking=True)
         for l in range(L):
-            fea.fea_kv_append(p_plan, k_new, v_new, c.k[l], c.v[l], c.dbt, c.dl)
-            fea.fea_decode_attention(p_plan if l == 0 else p_reuse, c.q, c.k[l], c.v[l], c.dbt, c.dl, c.out, c.ws)
+            check(lib.fea_kv_append(*app_args[l]))
+            check(lib.fea_decode_attention(*att_args[l]))
 
     for _ in range(5):
         step()
