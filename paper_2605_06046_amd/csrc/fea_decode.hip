@@ -28,6 +28,7 @@ struct Resolved {
     int variant;      // 0 generic, 1 MFMA
     int G, mpt, grouping, split_user, grid;
     int pre, pre_grid;   // leaders and common runs on many workgroups first (large tables)
+    int merge_by_rows;   // very many output rows: the merge takes several rows per wave
     PlanTuning tune;
     WsLayout lay;
 };
@@ -100,6 +101,9 @@ static int32_t resolve(const fea_attn_params* p, int32_t B, int32_t stride, Reso
     r.pre = r.grouping && (run_min == 0 || (groupable >= 128 && groupable * stride >= run_min)) ? 1 : 0;
     r.pre_grid = (int)std::max<int64_t>(1, std::min<int64_t>(2 * cu_count(), (groupable + 3) / 4));
     const int64_t rows = (int64_t)B * p->num_q_heads;
+    // Very many rows mean many requests and hence few pieces per row: there a wave of the merge takes
+    // several rows (a long shared run cut into many pieces comes with few rows, and keeps a wave per row).
+    r.merge_by_rows = rows >= env_int("FEA_MERGE_BY_ROWS_MIN", 8192) ? 1 : 0;
     const int64_t segs = 2ll * B * p->num_kv_heads;          // private segments + at most as many shared ones
     const int64_t rows_per_item = std::max(kTileRows, r.mpt * r.G);
     int64_t max_items, max_rows;
@@ -226,7 +230,7 @@ int32_t fea_decode_attention(const fea_attn_params* p, const void* q, const void
     sa.mpt = r.mpt;
     if (r.variant == 1) launch_sweep_mfma(sa, r.grid, where[1]);
     else launch_sweep_generic(sa, p->dtype, p->head_dim, r.grid, where[1]);
-    launch_merge(sa, p->dtype, p->head_dim, where[2]);
+    launch_merge(sa, p->dtype, p->head_dim, r.merge_by_rows != 0, where[2]);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(FEA_EHIP, "fea_decode_attention: launch failed: %s", hipGetErrorString(e));
     return FEA_OK;

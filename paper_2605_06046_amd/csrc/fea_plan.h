@@ -130,6 +130,6 @@ struct Launch {
 void launch_plan(const PlanArgs& a, const Launch& L);
 void launch_sweep_generic(const SweepArgs& a, int dtype, int head_dim, int grid, const Launch& L);
 void launch_sweep_mfma(const SweepArgs& a, int grid, const Launch& L);
-void launch_merge(const SweepArgs& a, int dtype, int head_dim, const Launch& L);
+void launch_merge(const SweepArgs& a, int dtype, int head_dim, bool by_rows, const Launch& L);
 
 }  // namespace fea

@@ -318,6 +318,80 @@ __global__ __launch_bounds__(256) void merge_kernel(SweepArgs a) {
     }
 }
 
+// The same merge for batches of very many rows with few partials each (hundreds of requests
+// that share nothing: one or two pieces per row): a wave takes 64 / (D/8) rows, one per lane
+// group, each group walking its own row's partials four at a time.  A quarter (D = 128) of the
+// waves of merge_kernel, which there spends its time starting waves that fetch one partial.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void merge_rows_kernel(SweepArgs a) {
+    constexpr int LPR = D / 8;           // lanes per row
+    constexpr int SLOTS = 64 / LPR;      // rows per wave
+    const int lane = threadIdx.x & 63, c = lane % LPR;
+    const int rowid = (blockIdx.x * 4 + (threadIdx.x >> 6)) * SLOTS + lane / LPR;
+    const int* hdr = reinterpret_cast<const int*>(a.ws);
+    if (rowid >= a.B * a.Hq) return;     // nothing below crosses lane groups
+    const int i = rowid / a.Hq, h = rowid - i * a.Hq;
+    const int g = h / a.G, hh = h - g * a.G;
+    const ReqDesc rd = reinterpret_cast<const ReqDesc*>(a.ws + a.lay.req)[i];
+    const SegDesc pd = reinterpret_cast<const SegDesc*>(a.ws + a.lay.segs)[(size_t)i * a.Hkv + g];
+    const float2* ml = reinterpret_cast<const float2*>(a.ws + a.lay.ml);
+    const float* pacc = reinterpret_cast<const float*>(a.ws + a.lay.acc);
+    T* out = static_cast<T*>(a.out) + (size_t)rowid * D;
+    if (hdr[H_OVERFLOW]) {   // the plan did not fit its buffers: make it loud
+        for (int e = c; e < D; e += LPR) Elem<T>::store(out + e, __uint_as_float(0x7FC00000u));
+        return;
+    }
+    const int ns_sh = rd.ns_sh, ns = ns_sh + pd.npieces;
+    const int sh_base = rd.sh_base0 + g * rd.sh_gstride + hh, pr_base = pd.pbase + hh;
+    auto prow = [&](int s) { return s < ns_sh ? sh_base + s * rd.sh_pstride : pr_base + (s - ns_sh) * a.G; };
+    constexpr int kInFlight = 4;
+    float num[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) num[k] = 0.f;
+    float den = 0.f, M = -INFINITY;
+    for (int s0 = 0; s0 < ns; s0 += kInFlight) {
+        float4 x[kInFlight][2];
+        float2 v[kInFlight];
+        float mb = -INFINITY;
+#pragma unroll
+        for (int q = 0; q < kInFlight; ++q) {
+            const int s = s0 + q;
+            v[q] = make_float2(-INFINITY, 0.f);
+            x[q][0] = x[q][1] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (s < ns) {
+                const int pr = prow(s);
+                v[q] = ml[pr];
+                const float4* src = reinterpret_cast<const float4*>(pacc + (size_t)pr * D + c * 8);
+                x[q][0] = src[0];
+                x[q][1] = src[1];
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < kInFlight; ++q) mb = fmaxf(mb, v[q].x);
+        const float Mn = fmaxf(M, mb);
+        if (Mn > M) {
+            const float f = M == -INFINITY ? 0.f : exp2f(M - Mn);
+            den *= f;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) num[k] *= f;
+            M = Mn;
+        }
+#pragma unroll
+        for (int q = 0; q < kInFlight; ++q) {
+            const float w = v[q].x == -INFINITY ? 0.f : exp2f(v[q].x - M);
+            den = fmaf(w, v[q].y, den);
+            num[0] = fmaf(w, x[q][0].x, num[0]); num[1] = fmaf(w, x[q][0].y, num[1]);
+            num[2] = fmaf(w, x[q][0].z, num[2]); num[3] = fmaf(w, x[q][0].w, num[3]);
+            num[4] = fmaf(w, x[q][1].x, num[4]); num[5] = fmaf(w, x[q][1].y, num[5]);
+            num[6] = fmaf(w, x[q][1].z, num[6]); num[7] = fmaf(w, x[q][1].w, num[7]);
+        }
+    }
+    const float inv = den > 0.f ? 1.f / den : 0.f;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) num[k] *= inv;
+    Elem<T>::store8(out + c * 8, num);
+}
+
 template <typename T>
 static void launch_generic_t(const SweepArgs& a, int head_dim, int grid, const Launch& L) {
     hipStream_t st = static_cast<hipStream_t>(L.stream);
@@ -337,10 +411,23 @@ void launch_sweep_generic(const SweepArgs& a, int dtype, int head_dim, int grid,
 }
 
 template <typename T>
-static void launch_merge_t(const SweepArgs& a, int head_dim, const Launch& L) {
+static void launch_merge_t(const SweepArgs& a, int head_dim, bool by_rows, const Launch& L) {
     hipStream_t st = static_cast<hipStream_t>(L.stream);
     hipEvent_t e0 = static_cast<hipEvent_t>(L.ev_start), e1 = static_cast<hipEvent_t>(L.ev_stop);
-    const int grid = (a.B * a.Hq + 3) / 4;
+    const int rows = a.B * a.Hq;
+    if (by_rows) {
+        const int per_wg = 4 * (64 / (head_dim / 8));
+        const int grid = (rows + per_wg - 1) / per_wg;
+        switch (head_dim) {
+            case 32: hipExtLaunchKernelGGL((merge_rows_kernel<T, 32>), dim3(grid), dim3(256), 0, st, e0, e1, 0, a); break;
+            case 64: hipExtLaunchKernelGGL((merge_rows_kernel<T, 64>), dim3(grid), dim3(256), 0, st, e0, e1, 0, a); break;
+            case 128: hipExtLaunchKernelGGL((merge_rows_kernel<T, 128>), dim3(grid), dim3(256), 0, st, e0, e1, 0, a); break;
+            case 256: hipExtLaunchKernelGGL((merge_rows_kernel<T, 256>), dim3(grid), dim3(256), 0, st, e0, e1, 0, a); break;
+            default: break;
+        }
+        return;
+    }
+    const int grid = (rows + 3) / 4;
     switch (head_dim) {
         case 32: hipExtLaunchKernelGGL((merge_kernel<T, 32>), dim3(grid), dim3(256), 0, st, e0, e1, 0, a); break;
         case 64: hipExtLaunchKernelGGL((merge_kernel<T, 64>), dim3(grid), dim3(256), 0, st, e0, e1, 0, a); break;
@@ -350,9 +437,9 @@ static void launch_merge_t(const SweepArgs& a, int head_dim, const Launch& L) {
     }
 }
 
-void launch_merge(const SweepArgs& a, int dtype, int head_dim, const Launch& L) {
-    if (dtype == FEA_DTYPE_F32) launch_merge_t<float>(a, head_dim, L);
-    else launch_merge_t<bf16_t>(a, head_dim, L);
+void launch_merge(const SweepArgs& a, int dtype, int head_dim, bool by_rows, const Launch& L) {
+    if (dtype == FEA_DTYPE_F32) launch_merge_t<float>(a, head_dim, by_rows, L);
+    else launch_merge_t<bf16_t>(a, head_dim, by_rows, L);
 }
 
 }  // namespace fea

@@ -487,3 +487,18 @@ def test_runs_found_on_many_workgroups_give_the_same_plan(case, monkeypatch):
     assert info2 == info
     assert np.array_equal(base, forced)
     assert_close(forced, decode_attention(values(q), values(k), values(v), bt, lens), "bf16", what=case)
+
+
+@pytest.mark.parametrize("dtype,Hq,Hkv,d", [("f32", 4, 4, 32), ("f32", 6, 2, 128), ("f32", 2, 1, 256), ("bf16", 12, 4, 64),
+                                            ("bf16", 8, 8, 256), ("bf16", 32, 8, 128), ("bf16", 64, 8, 128)])
+def test_merge_with_several_rows_per_wave(dtype, Hq, Hkv, d, monkeypatch):
+    """Batches of very many rows are merged several rows to a wave; forced on here for small ones,
+    including rows with many partials, rows of zero length and a ragged last wave."""
+    spec = W.Spec("rows", 27, dtype, Hq, Hkv, d, ((5, 96), (3, 0), (1, 1200)), (1, 200))
+    wl = W.generate(spec)
+    want = None
+    for forced in ("1000000000", "0"):
+        monkeypatch.setenv("FEA_MERGE_BY_ROWS_MIN", forced)
+        out, bt, lens, info = run_workload(wl, split_blocks=2 if forced == "0" else 0)   # many pieces per row
+        want = oracle_for(wl, bt, lens) if want is None else want
+        assert_close(out, want, dtype, what=f"merge rows {forced} {dtype} {Hq}/{Hkv}/{d}")
