@@ -22,8 +22,6 @@ static int env_int(const char* name, int dflt) {
     return std::atoi(v);
 }
 
-static bool is_pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
-
 struct Resolved {
     int variant;      // 0 generic, 1 MFMA
     int G, mpt, grouping, split_user, grid;
@@ -76,7 +74,7 @@ static int32_t resolve(const fea_attn_params* p, int32_t B, int32_t stride, Reso
     if ((int64_t)B * p->num_q_heads > 0x3FFFFFFF || (int64_t)stride * kBlock > 0x3FFFFFFF)
         return fail(FEA_EINVAL, "%s: problem too large (B*Hq or sequence length overflows)", who);
     r.G = p->num_q_heads / p->num_kv_heads;
-    const bool mfma_ok = p->dtype == FEA_DTYPE_BF16 && p->head_dim == 128 && is_pow2(r.G) && r.G <= 16;
+    const bool mfma_ok = p->dtype == FEA_DTYPE_BF16 && p->head_dim == 128 && r.G <= 16;
     r.variant = (mfma_ok && !env_int("FEA_FORCE_GENERIC", 0)) ? 1 : 0;
     r.mpt = r.G >= kTileRows ? 1 : kTileRows / r.G;
     r.grouping = p->max_group == 1 ? 0 : 1;

@@ -1,5 +1,5 @@
-// KV sweep on the matrix cores: bf16 caches, head_dim 128, query group size a
-// power of two up to 16.
+// KV sweep on the matrix cores: bf16 caches, head_dim 128, query groups of up to
+// 16 heads per KV head (any ratio: 7 as in 28/4, 5 as in 40/8, ...).
 //
 // One single-wave workgroup per SIMD; the planner has cut the stream of 32-token
 // tiles into equal shares, and wave w sweeps the consecutive work items of share w.
@@ -214,7 +214,7 @@ __device__ __forceinline__ void wait_all(Stream& sm) {
 
 template <int NT>
 __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item, const Item& next, bool has_next,
-                                           int log2G, char* s_stage, const int* s_cols, const char* s_q, uint32_t lds_base,
+                                           int g_rcp, char* s_stage, const int* s_cols, const char* s_q, uint32_t lds_base,
                                            uint32_t cols_base, uint32_t q_base, const Lanes& L, int lane, Stream& sm) {
     const int n = L.n, kg = L.kg;
     const uint16_t* Q = static_cast<const uint16_t*>(a.q);
@@ -291,7 +291,7 @@ __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item,
         for (int nt = 0; nt < NT; ++nt) {
             const int row = nt * 16 + n;
             const bool ok = row < item.nrows;
-            const int mem = row >> log2G, hh = row & ((1 << log2G) - 1);
+            const int mem = (row * g_rcp) >> 16, hh = row - mem * a.G;   // row / G and row % G (rows < 64, G <= 16)
             const int req = ok ? (item.mlist_off < 0 ? item.who : mlist[mem]) : 0;
             const uint16_t* qp = Q + ((size_t)req * a.Hq + item.g * a.G + hh) * kD + kg * 8;
 #pragma unroll
@@ -538,7 +538,7 @@ __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item,
     sm.q_ready = q_next;
 }
 
-__global__ __launch_bounds__(64) void sweep_mfma_kernel(SweepArgs a, int log2G, int xcd_aware) {
+__global__ __launch_bounds__(64) void sweep_mfma_kernel(SweepArgs a, int g_rcp, int xcd_aware) {
     __shared__ __attribute__((aligned(1024))) char s_stage[kStages * kStageBytes];
     __shared__ __attribute__((aligned(256))) int s_cols[3 * 64];
     __shared__ __attribute__((aligned(256))) int s_desc[kDescWindow * 8];      // the next few item descriptors
@@ -624,9 +624,9 @@ __global__ __launch_bounds__(64) void sweep_mfma_kernel(SweepArgs a, int log2G, 
                 wait_all(sm);
             }
             const Item next = has_next ? read_desc(it + 1 - win_first) : item;
-            if (item.nrows <= 16) sweep_item<1>(a, item, next, has_next, log2G, s_stage, s_cols, s_q, lds_base, cols_base, q_base, L, lane, sm);
-            else if (item.nrows <= 32) sweep_item<2>(a, item, next, has_next, log2G, s_stage, s_cols, s_q, lds_base, cols_base, q_base, L, lane, sm);
-            else sweep_item<4>(a, item, next, has_next, log2G, s_stage, s_cols, s_q, lds_base, cols_base, q_base, L, lane, sm);
+            if (item.nrows <= 16) sweep_item<1>(a, item, next, has_next, g_rcp, s_stage, s_cols, s_q, lds_base, cols_base, q_base, L, lane, sm);
+            else if (item.nrows <= 32) sweep_item<2>(a, item, next, has_next, g_rcp, s_stage, s_cols, s_q, lds_base, cols_base, q_base, L, lane, sm);
+            else sweep_item<4>(a, item, next, has_next, g_rcp, s_stage, s_cols, s_q, lds_base, cols_base, q_base, L, lane, sm);
             if (!has_next) break;
             ++it;
             item = next;
@@ -635,11 +635,10 @@ __global__ __launch_bounds__(64) void sweep_mfma_kernel(SweepArgs a, int log2G, 
 }
 
 void launch_sweep_mfma(const SweepArgs& a, int grid, const Launch& L) {
-    int log2G = 0;
-    while ((1 << log2G) < a.G) ++log2G;
+    const int g_rcp = (65536 + a.G - 1) / a.G;   // (row * g_rcp) >> 16 == row / G for the 64 rows of an item
     static const int xcd_aware = [] { const char* v = std::getenv("FEA_XCD_AWARE"); return v && *v ? std::atoi(v) : 1; }();
     hipExtLaunchKernelGGL(sweep_mfma_kernel, dim3(grid), dim3(64), 0, static_cast<hipStream_t>(L.stream),
-                          static_cast<hipEvent_t>(L.ev_start), static_cast<hipEvent_t>(L.ev_stop), 0, a, log2G, xcd_aware);
+                          static_cast<hipEvent_t>(L.ev_start), static_cast<hipEvent_t>(L.ev_stop), 0, a, g_rcp, xcd_aware);
 }
 
 }  // namespace fea

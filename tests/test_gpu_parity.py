@@ -119,7 +119,9 @@ def test_any_block_table_is_handled(mode, dtype, Hq, Hkv, d, lens):
 
 @pytest.mark.parametrize("dtype,Hq,Hkv,d", [("f32", 4, 4, 32), ("f32", 6, 2, 128), ("f32", 2, 1, 256),
                                             ("bf16", 12, 4, 64), ("bf16", 8, 8, 256), ("bf16", 24, 8, 128),
-                                            ("bf16", 64, 8, 128), ("bf16", 8, 8, 128), ("bf16", 32, 2, 128)])
+                                            ("bf16", 64, 8, 128), ("bf16", 8, 8, 128), ("bf16", 32, 2, 128),
+                                            ("bf16", 28, 4, 128), ("bf16", 40, 8, 128), ("bf16", 12, 1, 128),
+                                            ("bf16", 6, 1, 128), ("bf16", 34, 2, 128)])
 def test_other_shapes(dtype, Hq, Hkv, d):
     spec = W.Spec("shape", 11, dtype, Hq, Hkv, d, ((5, 96), (3, 0)), (1, 200))
     wl = W.generate(spec)
@@ -212,7 +214,8 @@ def test_profiling_events_bracket_each_kernel():
 
 
 @pytest.mark.gpu
-@pytest.mark.parametrize("B,prefix,Hq,Hkv", [(300, 320, 32, 8), (500, 96, 32, 8), (130, 512, 64, 8), (300, 3200, 32, 8)])
+@pytest.mark.parametrize("B,prefix,Hq,Hkv", [(300, 320, 32, 8), (500, 96, 32, 8), (130, 512, 64, 8), (300, 3200, 32, 8),
+                                          (100, 640, 28, 4), (70, 320, 40, 8)])
 def test_wide_prefix_groups(B, prefix, Hq, Hkv):
     """One prefix group far wider than a workgroup's row tiles (the paper's large homogeneous
     batches, Experiment 5): every request's rows against the oracle."""
