@@ -215,6 +215,10 @@ int32_t fea_validate_block_tables(const int32_t* block_tables, int32_t table_str
  *   seq_lens      int32 [B], each <= 16 * table_stride
  * The result is correct for ANY table whose read entries are valid block ids:
  * blocks may repeat inside a row and alias between rows at any position.
+ * The device cannot check ids against the cache size: an id beyond the cache is
+ * the caller's error and reads outside it; a negative entry inside a request's
+ * length (e.g. lengths uploaded ahead of their tables) is read as block 0, so
+ * the output of that request is wrong but no address before the cache is formed.
  * Requests whose rows start with the same run of block ids are detected on the
  * device and that run is swept once for all of them.
  *

@@ -126,7 +126,7 @@ __global__ __launch_bounds__(kGenThreads) void sweep_generic_kernel(SweepArgs a)
                 // scores
                 for (int tt = wave * TPW + r; tt < np; tt += kGenWaves * TPW) {
                     const int t = p0 + tt;
-                    const int blk = row[t / kBlock];
+                    const int blk = max(row[t / kBlock], 0);   // a -1 inside a request's length (the caller's error) must not become a read before the cache
                     float kf[EPL];
                     Elem<T>::load(K + (((size_t)blk * a.Hkv + item.g) * kBlock + (t % kBlock)) * D + c * EPL, kf);
                     float dot[kHB];
@@ -178,7 +178,7 @@ __global__ __launch_bounds__(kGenThreads) void sweep_generic_kernel(SweepArgs a)
                 }
                 for (int tt = wave * TPW + r; tt < np; tt += kGenWaves * TPW) {
                     const int t = p0 + tt;
-                    const int blk = row[t / kBlock];
+                    const int blk = max(row[t / kBlock], 0);   // a -1 inside a request's length (the caller's error) must not become a read before the cache
                     float vf[EPL];
                     Elem<T>::load(V + (((size_t)blk * a.Hkv + item.g) * kBlock + (t % kBlock)) * D + c * EPL, vf);
 #pragma unroll

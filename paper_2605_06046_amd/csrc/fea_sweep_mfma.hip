@@ -255,8 +255,10 @@ __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item,
         }
         wait_for(sm, pick3(buf, sm.cmark0, sm.cmark1, sm.cmark2));   // the window's block ids must have landed
         const int* sc = s_cols + buf * 64 + at;
-        const int b0 = __builtin_amdgcn_readfirstlane(sc[0]);
-        const int b1 = __builtin_amdgcn_readfirstlane(sc[1]);
+        // (a table entry of -1 inside a request's length is the caller's error; it must not become a
+        // read before the cache)
+        const int b0 = max(__builtin_amdgcn_readfirstlane(sc[0]), 0);
+        const int b1 = max(__builtin_amdgcn_readfirstlane(sc[1]), 0);
         const int stg = (sm.phase + idx) & 1;
         fetch_tile(a, g, b0, b1, lds_base + stg * kStageBytes, L);
         sm.seq += 16;
