@@ -505,3 +505,56 @@ def test_merge_with_several_rows_per_wave(dtype, Hq, Hkv, d, monkeypatch):
         out, bt, lens, info = run_workload(wl, split_blocks=2 if forced == "0" else 0)   # many pieces per row
         want = oracle_for(wl, bt, lens) if want is None else want
         assert_close(out, want, dtype, what=f"merge rows {forced} {dtype} {Hq}/{Hkv}/{d}")
+
+
+def _random_prefix_tree_batch(seed, dtype, Hq, Hkv, d):
+    """A batch whose token streams come from a random prefix tree (depth up to 4, random fan-out and
+    segment lengths, some requests ending exactly on a node, some empty or shorter than a block)."""
+    rng = np.random.default_rng(seed)
+    draw = lambda n: rng.integers(0, W.VOCAB, size=int(n), dtype=np.int32)
+    seqs = []
+
+    def grow(prefix, depth):
+        for _ in range(int(rng.integers(2, 5))):
+            seg = draw(rng.choice([16, 32, 48, 80, 160, 7, 100]))
+            node = np.concatenate([prefix, seg])
+            for _ in range(int(rng.integers(0, 5))):       # requests hanging off this node
+                tail = draw(rng.choice([0, 1, 5, 16, 33, 70]))
+                seqs.append(np.concatenate([node, tail]))
+            if depth < 4 and rng.random() < 0.8:
+                grow(node, depth + 1)
+
+    grow(np.zeros(0, dtype=np.int32), 1)
+    seqs += [np.zeros(0, dtype=np.int32), draw(3), draw(16)]
+    order = rng.permutation(len(seqs))
+    seqs = [seqs[j] for j in order][:220]
+    spec = W.Spec("tree", 44, dtype, Hq, Hkv, d, ((len(seqs), 0),), (1, 1))
+    base = W.generate(spec)
+    offs = np.zeros(len(seqs) + 1, dtype=np.int64)
+    offs[1:] = np.cumsum([len(x) for x in seqs])
+    nblk = max(1, int(sum(-(-len(x) // 16) for x in seqs)))
+    rs = np.random.default_rng(seed + 1000)
+    k = rs.standard_normal((nblk, Hkv, 16, d), dtype=np.float32)
+    v = rs.standard_normal((nblk, Hkv, 16, d), dtype=np.float32)
+    if dtype == "bf16":
+        k, v = W.f32_to_bf16_bits(k), W.f32_to_bf16_bits(v)
+    toks = np.concatenate(seqs) if sum(len(x) for x in seqs) else np.zeros(0, dtype=np.int32)
+    return dataclasses.replace(base, tokens=toks, tok_offsets=offs, k_cache=k, v_cache=v, num_blocks=nblk,
+                               max_blocks_per_seq=max(1, max(-(-len(x) // 16) for x in seqs)) + int(rng.integers(0, 4)),
+                               group_of=np.zeros(len(seqs), dtype=np.int32))
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_random_prefix_trees(seed, monkeypatch):
+    """Random prefix trees through every path of the alias detection (nested runs, several levels,
+    odd table strides, the many-workgroup run kernel forced on and off) against the oracle."""
+    dtype, Hq, Hkv, d = [("bf16", 32, 8, 128), ("bf16", 28, 4, 128), ("bf16", 8, 8, 128), ("f32", 8, 2, 64),
+                         ("bf16", 12, 2, 128)][seed % 5]
+    wl = _random_prefix_tree_batch(100 + seed, dtype, Hq, Hkv, d)
+    out, bt, lens, info = run_workload(wl)
+    want = oracle_for(wl, bt, lens)
+    assert info["overflow"] == 0
+    assert_close(out, want, dtype, what=f"tree {seed}")
+    monkeypatch.setenv("FEA_RUN_KERNEL_MIN", "0")
+    out2, _, _, info2 = run_workload(wl)
+    assert info2 == info and np.array_equal(out, out2)
