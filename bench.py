@@ -146,6 +146,8 @@ class Case:
         """Average (plan, sweep, merge) durations in ms over `steps` back-to-back calls (no
         host sync between), from HIP events attached to each dispatch on the launch stream."""
         torch, fea = self.torch, self.fea
+        if profiler_attached():          # the tool times the dispatches itself; the library refuses its own events then
+            return None
         R = self.R if cold else 1
         sp = C.c_void_p(torch.cuda.current_stream().cuda_stream)
         for s in range(4):
@@ -183,11 +185,13 @@ class Case:
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / (reps * layers)
 
-    def measure(self, steps, warmup, graph=False):
+    def measure(self, steps, warmup, graph=False, light=False):
         ms_cold = self.time_steps(steps, warmup, cold=True, graph=graph)
         ms_warm = self.time_steps(steps, warmup, cold=False, graph=graph)
         kt = self.kernel_times(min(steps, 200))
         info = self.fea.fea_decode_plan_info(self.ws)
+        if kt is None:
+            kt = [float("nan")] * 3
         return {
             "workload": self.label, "B": self.B, "ms_per_step": ms_cold, "ms_per_step_warm": ms_warm,
             "tokens_per_s": self.B / (ms_cold * 1e-3), "tokens_per_s_warm": self.B / (ms_warm * 1e-3),
@@ -198,34 +202,105 @@ class Case:
             "frac_hbm_peak_step": self.unique_bytes / (ms_cold * 1e-3) / 1e9 / HBM_PEAK_GBS,
             "kernel_us": {"plan": kt[0] * 1e3, "sweep": kt[1] * 1e3, "merge": kt[2] * 1e3},
             "sweep_gbs": self.unique_bytes / (kt[1] * 1e-3) / 1e9,
-            "ms_per_call_plan_shared_by_32_layers": self.time_model_step(),
+            "ms_per_call_plan_shared_by_32_layers": None if light else self.time_model_step(),
             "replicas": self.R, "plan": info, "table_build_ms": self.table_build_s * 1e3,
             "table_build_tokens_per_s": len(self.wl.tokens) / self.table_build_s,
         }
 
 
-def cpu_baseline(case, budget_s=12.0):
-    """The float64 oracle, as it stands, on the host cores: whole requests of the
-    same batch until about `budget_s` seconds of work are done."""
+def profiler_attached():
+    """rocprofv3 (and tools like it) announce themselves through this variable."""
+    return bool(os.environ.get("ROCP_TOOL_LIBRARIES"))
+
+
+def cpu_baseline(case, budget_s=14.0):
+    """The float64 oracle, as it stands, on the host cores: whole requests of the same batch, for
+    about half of `budget_s` with the numerical library's threads as they come (all cores) and for
+    the other half limited to one thread."""
     from oracle.attention import decode_attention
     try:
-        from threadpoolctl import threadpool_info
+        from threadpoolctl import threadpool_info, threadpool_limits
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
-        threads = os.cpu_count() or 1
-    torch = case.torch
+        threadpool_limits, threads = None, os.cpu_count() or 1
     q = case.q.float().cpu().numpy()
     k = case.k[0].float().cpu().numpy()
     v = case.v[0].float().cpu().numpy()
     decode_attention(q, k, v, case.bt, case.lens, requests=[0])          # warm
-    done, t0 = 0, time.perf_counter()
-    while time.perf_counter() - t0 < budget_s:
-        decode_attention(q, k, v, case.bt, case.lens, requests=[done % case.B])
-        done += 1
-    dt = time.perf_counter() - t0
-    return {"value": done / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"{done} request-steps cycling over the {case.B} requests of {case.label} "
-                      f"(all heads, full history each), {dt:.1f} s wall"}
+
+    def leg(seconds):
+        done, t0 = 0, time.perf_counter()
+        while time.perf_counter() - t0 < seconds:
+            decode_attention(q, k, v, case.bt, case.lens, requests=[done % case.B])
+            done += 1
+        return done, time.perf_counter() - t0
+
+    done, dt = leg(budget_s / 2)
+    res = {"value": done / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+           "nproc": os.cpu_count(),
+           "sample": f"{done} request-steps cycling over the {case.B} requests of {case.label} "
+                     f"(all heads, full history each), {dt:.1f} s wall, numerical library threads as configured"}
+    if threadpool_limits is not None:
+        with threadpool_limits(limits=1):
+            done1, dt1 = leg(budget_s / 2)
+        res["one_thread"] = {"value": done1 / dt1, "unit": "tokens/s", "cores": 1,
+                             "sample": f"{done1} request-steps of the same batch, {dt1:.1f} s wall"}
+    return res
+
+
+def hbm_calibration(gib=2):
+    """What the box streams through the sweep's own fetch path (no computation): GB/s over a buffer
+    far larger than the memory-side cache, blocks in order and scattered."""
+    import torch
+    import paper_2605_06046_amd as fea
+    buf = torch.empty(gib << 30, dtype=torch.uint8, device="cuda")
+    buf.view(torch.int32).fill_(0x3F803F80)
+    res = {"buffer_GiB": gib, "linear_gbs": fea.fea_stream_read_gbs(buf, scattered=False, repeats=5),
+           "scattered_gbs": fea.fea_stream_read_gbs(buf, scattered=True, repeats=5)}
+    del buf
+    torch.cuda.empty_cache()
+    return res
+
+
+def compact(case, m):
+    """One entry of the default line's `configs` block."""
+    sweep_us = m["kernel_us"]["sweep"]
+    return {"B": case.B, "ms_per_step": m["ms_per_step"], "ms_per_step_warm": m["ms_per_step_warm"],
+            "tokens_per_s": m["tokens_per_s"],
+            "unique_kv_MB": case.unique_bytes / 1e6, "logical_kv_MB": case.logical_bytes / 1e6,
+            "kernel_us": m["kernel_us"],
+            "sweep_frac_of_hbm_peak": case.unique_bytes / (sweep_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
+            "step_frac_of_hbm_peak": m["frac_hbm_peak_step"],
+            "groups": m["plan"]["groups"], "variant": m["plan"]["variant"], "kv_replicas_rotated": case.R,
+            "traffic_over_unique": (lambda t: None if t is None else t / case.unique_bytes)(
+                traffic_from_profile(case.label, m["plan"]))}
+
+
+def config_cases():
+    """(label, Case factory) for the other batch shapes of the measurement and the equal-size
+    homogeneous-vs-mixed comparisons (H2: 32 requests from one prefix group vs 4 from each of 8;
+    H3: the one-prefix batch vs the same lengths with nothing shared)."""
+    import dataclasses
+    base = W.CONFIGS["c3"]
+    yield "c1", lambda: Case(W.CONFIGS["c1"])
+    yield "c3", lambda: Case(W.CONFIGS["c3"])
+    yield "c4", lambda: Case(W.CONFIGS["c4"])
+    yield "c5", lambda: Case(W.CONFIGS["c5"])
+    homo = dataclasses.replace(base, name="H2_homogeneous", groups=((32, 4096),), interleave=False)
+    mixed = dataclasses.replace(base, name="H2_mixed", groups=tuple((4, 4096) for _ in range(8)))
+    yield "H2_homogeneous", lambda: Case(homo, label=homo.name)
+    yield "H2_mixed", lambda: Case(mixed, label=mixed.name)
+
+    def unshared():
+        c2 = W.CONFIGS["c2"]
+        wl = W.generate(c2, with_kv=False)
+        rng = np.random.default_rng(7)
+        toks = wl.tokens.copy()
+        for i in range(c2.batch):                     # re-draw every prefix: same lengths, no common tokens
+            toks[wl.tok_offsets[i]:wl.tok_offsets[i] + 4096] = rng.integers(0, W.VOCAB, size=4096, dtype=np.int32)
+        wl_u = dataclasses.replace(wl, tokens=toks, num_blocks=int(sum(-(-int(L) // 16) for L in wl.seq_lens)))
+        return Case(dataclasses.replace(c2, name="H3_unshared"), tokens=wl_u, label="H3_unshared")
+    yield "H3_unshared", unshared
 
 
 def traffic_from_profile(workload, plan):
@@ -255,6 +330,10 @@ def main():
     ap.add_argument("--workload", default="c2", choices=sorted(W.CONFIGS))
     ap.add_argument("--graph", action="store_true", help="replay the steps from a captured HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-configs", action="store_true",
+                    help="measure only --workload (skip the other batch shapes and the homogeneous-vs-mixed comparisons)")
+    ap.add_argument("--no-hbm-calibration", action="store_true",
+                    help="skip the streaming-read measurement of what the box delivers to the sweep's fetch path")
     ap.add_argument("--out", default=OUT_DIR, help="folder for the .jsonl files of the extra modes")
     ap.add_argument("--suite", action="store_true", help="also run all shapes and the homogeneity comparisons")
     ap.add_argument("--decode-loop", type=int, default=0, metavar="N",
@@ -290,12 +369,16 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+    calib = None if args.no_hbm_calibration else hbm_calibration()
+    if calib:
+        log(json.dumps({"hbm_calibration": calib}))
     spec = W.CONFIGS[args.workload]
     case = Case(spec)
     m = case.measure(args.steps, args.warmup, graph=args.graph)
     log(json.dumps(m))
     sweep_s = m["kernel_us"]["sweep"] * 1e-6
-    achieved = case.unique_bytes / sweep_s / 1e9
+    achieved = case.unique_bytes / sweep_s / 1e9          # nan under a profiler (it times the kernels itself)
+    nn = lambda x: None if x != x else x                  # NaN -> null
     line = {
         "metric": "decode-attn tokens/s (unique-KV HBM GB/s vs peak in roofline)",
         "value": m["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -308,19 +391,51 @@ def main():
                    "unique_kv_MB": case.unique_bytes / 1e6, "logical_kv_MB": case.logical_bytes / 1e6},
         "unique_kv_gbs": m["unique_kv_gbs"], "frac_hbm_peak_whole_step": m["frac_hbm_peak_step"],
         "warm": {"tokens_per_s": m["tokens_per_s_warm"], "unique_kv_gbs": m["unique_kv_gbs_warm"]},
-        "kernel_us": m["kernel_us"], "plan": m["plan"],
+        "kernel_us": {k: nn(v) for k, v in m["kernel_us"].items()}, "plan": m["plan"],
         "plan_shared_by_32_layers": {"ms_per_call": m["ms_per_call_plan_shared_by_32_layers"],
                                      "tokens_per_s": case.B / (m["ms_per_call_plan_shared_by_32_layers"] * 1e-3)},
         "host_table_build": {"ms": m["table_build_ms"], "tokens_per_s": m["table_build_tokens_per_s"]},
-        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic_from_profile(args.workload, m["plan"]),
+        "roofline": {"bound": "hbm", "achieved": nn(achieved), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": nn(achieved / HBM_PEAK_GBS), "traffic": traffic_from_profile(args.workload, m["plan"]),
                      "kernel": "sweep_mfma_kernel" if m["plan"]["variant"] == 1 else "sweep_generic_kernel",
-                     "bytes_per_launch": case.unique_bytes},
+                     "bytes_per_launch": case.unique_bytes,
+                     "achievable_gbs": None if calib is None else calib["scattered_gbs"],
+                     "frac_of_achievable": None if calib is None else nn(achieved / calib["scattered_gbs"])},
+        "hbm_calibration": calib, "profiler_attached": profiler_attached(),
     }
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(case)
     else:
         line["cpu_baseline"] = None
+
+    if not args.no_configs:
+        # every batch shape of the measurement in the same line, the headline workload included
+        configs = {args.workload: compact(case, m)}
+        del case
+        case = None
+        torch.cuda.empty_cache()
+        for label, make in config_cases():
+            if label == args.workload:
+                continue
+            c = make()
+            heavy = label == "c5"
+            mm = c.measure(40 if heavy else max(50, args.steps // 4), 5 if heavy else max(10, args.warmup // 4),
+                           graph=args.graph, light=True)
+            configs[label] = compact(c, mm)
+            log(json.dumps({label: configs[label]}))
+            del c
+            torch.cuda.empty_cache()
+        line["configs"] = {k: {kk: (nn(vv) if isinstance(vv, float) else vv) for kk, vv in v.items()} for k, v in configs.items()}
+        ratio = lambda slow, fast: configs[slow]["ms_per_step"] / configs[fast]["ms_per_step"]
+        line["homogeneous_vs_mixed"] = {
+            "H2_equal_size_equal_logical_kv": {"homogeneous_ms": configs["H2_homogeneous"]["ms_per_step"],
+                                               "mixed_ms": configs["H2_mixed"]["ms_per_step"],
+                                               "speedup": ratio("H2_mixed", "H2_homogeneous")},
+        }
+        if "c2" in configs:
+            line["homogeneous_vs_mixed"]["H3_shared_vs_unshared_same_lengths"] = {
+                "shared_ms": configs["c2"]["ms_per_step"], "unshared_ms": configs["H3_unshared"]["ms_per_step"],
+                "speedup": ratio("H3_unshared", "c2")}
 
     if args.decode_loop > 0:
         os.makedirs(OUT_DIR, exist_ok=True)
@@ -330,7 +445,7 @@ def main():
     if args.scheduler and not args.suite:
         os.makedirs(OUT_DIR, exist_ok=True)
         with open(os.path.join(OUT_DIR, "scheduler.jsonl"), "w") as f:
-            del case
+            case = None
             torch.cuda.empty_cache()
             for res in scheduler_comparison(max(50, args.steps // 4), max(10, args.warmup // 2), args.graph):
                 f.write(json.dumps(res) + "\n")
@@ -351,7 +466,7 @@ def main():
         os.makedirs(OUT_DIR, exist_ok=True)
         with open(os.path.join(OUT_DIR, "suite.jsonl"), "w") as f:
             f.write(json.dumps(m) + "\n")
-            del case
+            case = None
             torch.cuda.empty_cache()
             for res in run_suite(args):
                 f.write(json.dumps(res) + "\n")

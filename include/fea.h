@@ -9,7 +9,10 @@
  * Every call returns a status: FEA_OK (0) or a negative code.  After a failure
  * fea_last_error() returns a thread-local, human-readable message, and no
  * output argument has been written (fea_build_block_tables additionally rolls
- * the pool back to its state before the call).  Nothing throws or aborts.
+ * the pool back to its state before the call).  Nothing throws or aborts: no
+ * C++ exception leaves the library; if the host itself runs out of memory a call
+ * returns FEA_ENOMEM, and a handle (pool, tree, policy) that was being changed
+ * by that call should be destroyed, its contents are then unspecified.
  *
  * Device work is enqueued on the caller's HIP stream and the call returns
  * without synchronising.  Contents of device buffers are never inspected on
@@ -27,12 +30,15 @@ extern "C" {
 
 #define FEA_OK       0
 #define FEA_EINVAL  (-1)   /* bad argument (null pointer, unsupported shape, ...)        */
-#define FEA_ENOMEM  (-2)   /* the KV pool has too few free blocks                        */
+#define FEA_ENOMEM  (-2)   /* the KV pool has too few free blocks (or the host no memory) */
 #define FEA_ERANGE  (-3)   /* a caller-provided table or workspace is too small          */
 #define FEA_EHIP    (-4)   /* the HIP runtime reported an error (message has the detail) */
 
 #define FEA_DTYPE_F32   0  /* q, caches, out are float32; arithmetic float32             */
 #define FEA_DTYPE_BF16  1  /* q, caches, out are bfloat16; products/accumulation float32 */
+
+#define FEA_GROUPABLE_REQUESTS 2048  /* requests with a batch index at or beyond this are
+                                        never grouped with others (see fea_decode_attention) */
 
 #define FEA_BLOCK_TOKENS 16  /* tokens per KV block (the paper's Section 3 setup; also the
                                 chunk size K of the prefix hashes, Section 4.2)          */
@@ -62,7 +68,14 @@ typedef struct fea_attn_params {
     int32_t max_group;      /* 0: group any number of requests that alias a leading run
                                of blocks; 1: treat every request on its own              */
     int32_t flags;          /* FEA_FLAG_*                                                */
-    int32_t reserved[3];    /* must be 0                                                 */
+    int32_t run_kernel_min; /* alias detection compares the table rows on many workgroups
+                               ahead of the planner's one workgroup when the batch has at
+                               least 128 requests and this many table entries.  0: the
+                               library's default (49152); < 0: always; > 0: that many    */
+    int32_t merge_rows_min; /* the merge takes several output rows per wave from this
+                               many rows (B * num_q_heads) on.  0: the library's default
+                               (8192); < 0: always; > 0: that many                       */
+    int32_t reserved;       /* must be 0                                                 */
 } fea_attn_params;
 
 /* Message of the last failure on this thread ("" if none).  HOST string owned
@@ -220,7 +233,10 @@ int32_t fea_validate_block_tables(const int32_t* block_tables, int32_t table_str
  * length (e.g. lengths uploaded ahead of their tables) is read as block 0, so
  * the output of that request is wrong but no address before the cache is formed.
  * Requests whose rows start with the same run of block ids are detected on the
- * device and that run is swept once for all of them.
+ * device and that run is swept once for all of them.  Only the first
+ * FEA_GROUPABLE_REQUESTS requests of a batch take part in that detection: a
+ * request with a higher index sweeps its whole history on its own (same result,
+ * more KV reads); fea_decode_plan_info reports how many requests were grouped.
  *
  *   workspace     DEVICE scratch of at least fea_decode_workspace_bytes() bytes,
  *                 256-byte aligned; contents are overwritten.  Calls that share
@@ -431,11 +447,28 @@ int32_t fea_cht_build_batch_learned(fea_cht* t, fea_policy* policy, int32_t max_
  * call since enabling (0-based) and returns the durations in milliseconds (HOST
  * float[3], zero where not timed, e.g. the first under FEA_FLAG_REUSE_PLAN).
  * fea_profile_enable(0, -1) switches recording off.  Process-wide, not thread-safe;
- * leave it off in production.
+ * leave it off in production.  Under a profiler that intercepts the launches
+ * (rocprofv3 and other tools loaded through ROCP_TOOL_LIBRARIES) recording is
+ * refused with FEA_EINVAL: the tool times the dispatches itself, and the two ways
+ * of attaching to a dispatch are not combined.
  * Errors: FEA_EHIP if events cannot be created or read; FEA_EINVAL for NULL, bad
- * arguments, or a call that was not recorded. */
+ * arguments, a call that was not recorded, or a profiler being attached. */
 int32_t fea_profile_enable(int32_t max_calls, int32_t which);
 int32_t fea_profile_read(int32_t call, float* ms);
+
+/* Measurement aid: the rate at which this GPU streams memory through the KV sweep's
+ * own fetch path (one single-wave workgroup per SIMD, 16 KB tiles of four 4 KB chunks
+ * fetched global -> LDS, two tiles in flight), nothing computed.  Reads the largest
+ * power-of-two number of 4 KB chunks that fits `bytes` exactly once per repeat -
+ * chunk after chunk (scattered == 0) or in a fixed pseudo-random order, like KV blocks
+ * scattered over a pool (scattered != 0) - and writes bytes read per second, in
+ * GB/s (1e9), to *gbs.  Use a buffer well beyond the 256 MB memory-side cache.
+ * DEVICE buffer (16-byte aligned, contents irrelevant, not modified); HOST gbs.
+ * Times with events on hip_stream and synchronises it.
+ * Errors: FEA_EINVAL (NULL, alignment, fewer than 4 MiB, repeats outside 1..1000),
+ * FEA_EHIP. */
+int32_t fea_stream_read_gbs(const void* buffer, size_t bytes, int32_t scattered, int32_t repeats,
+                            void* hip_stream, double* gbs);
 
 #ifdef __cplusplus
 }

@@ -22,6 +22,20 @@ static int env_int(const char* name, int dflt) {
     return std::atoi(v);
 }
 
+// Development knobs for tuning sweeps.  The environment is read once, the first time
+// a call needs them, and never again: a variable that changes later (or a stale one a
+// second thread sets) cannot switch kernels or move the workspace layout between the
+// sizing call and the attention call.  What tests need to steer is in fea_attn_params.
+struct Knobs {
+    int force_generic, sweep_grid, spare_waves, min_piece, min_run, w32, w64;
+};
+static const Knobs& knobs() {
+    static const Knobs k = {env_int("FEA_FORCE_GENERIC", 0), env_int("FEA_SWEEP_GRID", 0), env_int("FEA_SPARE_WAVES", 16),
+                            env_int("FEA_MIN_PIECE", 4),     env_int("FEA_MIN_RUN", 2),    env_int("FEA_W32", 20),
+                            env_int("FEA_W64", 24)};
+    return k;
+}
+
 struct Resolved {
     int variant;      // 0 generic, 1 MFMA
     int G, mpt, grouping, split_user, grid;
@@ -65,7 +79,7 @@ static int32_t check_params(const fea_attn_params* p, const char* who) {
     if (p->flags & ~(FEA_FLAG_REUSE_PLAN | FEA_FLAG_PLAN_ONLY)) return fail(FEA_EINVAL, "%s: unknown flag bits 0x%x", who, p->flags);
     if ((p->flags & FEA_FLAG_REUSE_PLAN) && (p->flags & FEA_FLAG_PLAN_ONLY))
         return fail(FEA_EINVAL, "%s: FEA_FLAG_REUSE_PLAN and FEA_FLAG_PLAN_ONLY exclude each other", who);
-    if (p->reserved[0] || p->reserved[1] || p->reserved[2]) return fail(FEA_EINVAL, "%s: reserved fields must be 0", who);
+    if (p->reserved) return fail(FEA_EINVAL, "%s: the reserved field must be 0", who);
     return FEA_OK;
 }
 
@@ -73,35 +87,39 @@ static int32_t resolve(const fea_attn_params* p, int32_t B, int32_t stride, Reso
     if (B < 0 || stride < 0) return fail(FEA_EINVAL, "%s: negative B or table_stride", who);
     if ((int64_t)B * p->num_q_heads > 0x3FFFFFFF || (int64_t)stride * kBlock > 0x3FFFFFFF)
         return fail(FEA_EINVAL, "%s: problem too large (B*Hq or sequence length overflows)", who);
+    // the planner counts 32-token tiles of the whole batch in 32-bit integers
+    if ((int64_t)B * p->num_kv_heads * ((stride + 1) / 2) > 0x3FFFFFFF)
+        return fail(FEA_EINVAL, "%s: problem too large (B * num_kv_heads * table_stride / 2 exceeds 2^30 tiles)", who);
+    const Knobs& kn = knobs();
     r.G = p->num_q_heads / p->num_kv_heads;
     const bool mfma_ok = p->dtype == FEA_DTYPE_BF16 && p->head_dim == 128 && r.G <= 16;
-    r.variant = (mfma_ok && !env_int("FEA_FORCE_GENERIC", 0)) ? 1 : 0;
+    r.variant = (mfma_ok && !kn.force_generic) ? 1 : 0;
     r.mpt = r.G >= kTileRows ? 1 : kTileRows / r.G;
     r.grouping = p->max_group == 1 ? 0 : 1;
     r.split_user = p->split_blocks > 0 ? ((p->split_blocks + 1) & ~1) : 0;
     // the sweep grid the plan is cut for: one single-wave workgroup per SIMD on the
     // matrix-core path, a few workgroups per CU on the generic path
-    r.grid = std::max(1, env_int("FEA_SWEEP_GRID", (r.variant == 1 ? 4 : 8) * cu_count()));
+    r.grid = kn.sweep_grid > 0 ? kn.sweep_grid : (r.variant == 1 ? 4 : 8) * cu_count();
     // The plan is cut for a few waves fewer than the grid has.  With every one of the
     // 4 x CUs single-wave workgroups busy from start to end, a handful of them (the first
     // ones dispatched) were measured to run about 1.5x longer than the rest, whatever
     // their work; with some workgroups exiting at once this does not happen.
-    r.tune.n_waves = std::max(1, r.grid - std::min(r.grid / 2, std::max(0, env_int("FEA_SPARE_WAVES", 16))));
-    r.tune.min_piece = std::max(1, env_int("FEA_MIN_PIECE", 4));
-    r.tune.min_run = std::max(1, env_int("FEA_MIN_RUN", 2));
-    r.tune.weights = std::min(255, std::max(16, env_int("FEA_W32", 20))) | (std::min(255, std::max(16, env_int("FEA_W64", 24))) << 8);
+    r.tune.n_waves = std::max(1, r.grid - std::min(r.grid / 2, std::max(0, kn.spare_waves)));
+    r.tune.min_piece = std::max(1, kn.min_piece);
+    r.tune.min_run = std::max(1, kn.min_run);
+    r.tune.weights = std::min(255, std::max(16, kn.w32)) | (std::min(255, std::max(16, kn.w64)) << 8);
     // Large tables: the rows are compared on many workgroups before the planner's one workgroup
     // takes over (a second launch, so only where the rows are long or many enough to pay for it).
     const int64_t groupable = std::min(B, kGroupReqMax);
     // (measured: 256 requests x 320 columns 30 -> 24 us, 800 x 657 105 -> 35 us; 32 x 2082 no gain, hence
     // the request count; a batch that shares nothing pays about 3 us for it)
-    const int run_min = env_int("FEA_RUN_KERNEL_MIN", 49152);
-    r.pre = r.grouping && (run_min == 0 || (groupable >= 128 && groupable * stride >= run_min)) ? 1 : 0;
+    const int run_min = p->run_kernel_min == 0 ? 49152 : p->run_kernel_min;
+    r.pre = r.grouping && (run_min < 0 || (groupable >= 128 && groupable * stride >= run_min)) ? 1 : 0;
     r.pre_grid = (int)std::max<int64_t>(1, std::min<int64_t>(2 * cu_count(), (groupable + 3) / 4));
     const int64_t rows = (int64_t)B * p->num_q_heads;
     // Very many rows mean many requests and hence few pieces per row: there a wave of the merge takes
     // several rows (a long shared run cut into many pieces comes with few rows, and keeps a wave per row).
-    r.merge_by_rows = rows >= env_int("FEA_MERGE_BY_ROWS_MIN", 8192) ? 1 : 0;
+    r.merge_by_rows = (p->merge_rows_min < 0 || rows >= (p->merge_rows_min == 0 ? 8192 : p->merge_rows_min)) ? 1 : 0;
     const int64_t segs = 2ll * B * p->num_kv_heads;          // private segments + at most as many shared ones
     const int64_t rows_per_item = std::max(kTileRows, r.mpt * r.G);
     int64_t max_items, max_rows;
@@ -139,18 +157,26 @@ extern "C" {
 
 int32_t fea_decode_workspace_bytes(const fea_attn_params* p, int32_t B, int32_t table_stride, size_t* out_bytes) {
     if (!out_bytes) return fail(FEA_EINVAL, "fea_decode_workspace_bytes: out_bytes is NULL");
-    int32_t rc = check_params(p, "fea_decode_workspace_bytes");
+    return decode_workspace_bytes(p, B, table_stride, out_bytes, "fea_decode_workspace_bytes");
+}
+
+}  // extern "C"
+
+namespace fea {
+
+int32_t decode_workspace_bytes(const fea_attn_params* p, int32_t B, int32_t table_stride, size_t* out_bytes, const char* who) {
+    int32_t rc = check_params(p, who);
     if (rc != FEA_OK) return rc;
     Resolved r;
-    rc = resolve(p, B, table_stride, r, "fea_decode_workspace_bytes");
+    rc = resolve(p, B, table_stride, r, who);
     if (rc != FEA_OK) return rc;
     *out_bytes = r.lay.total;
     return FEA_OK;
 }
 
-int32_t fea_decode_attention(const fea_attn_params* p, const void* q, const void* k_cache, const void* v_cache,
-                             const int32_t* block_tables, int32_t table_stride, const int32_t* seq_lens, int32_t B,
-                             void* out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+int32_t decode_impl(const fea_attn_params* p, const void* q, const void* k_cache, const void* v_cache,
+                    const int32_t* block_tables, int32_t table_stride, const int32_t* seq_lens, int32_t B,
+                    void* out, void* workspace, size_t workspace_bytes, void* hip_stream) {
     int32_t rc = check_params(p, "fea_decode_attention");
     if (rc != FEA_OK) return rc;
     Resolved r;
@@ -216,6 +242,7 @@ int32_t fea_decode_attention(const fea_attn_params* p, const void* q, const void
     sa.k_cache = k_cache;
     sa.v_cache = v_cache;
     sa.bt = block_tables;
+    sa.seq_lens = seq_lens;
     sa.out = out;
     sa.ws = static_cast<char*>(workspace);
     sa.lay = r.lay;
@@ -234,9 +261,31 @@ int32_t fea_decode_attention(const fea_attn_params* p, const void* q, const void
     return FEA_OK;
 }
 
+}  // namespace fea
+
+extern "C" {
+
+int32_t fea_decode_attention(const fea_attn_params* p, const void* q, const void* k_cache, const void* v_cache,
+                             const int32_t* block_tables, int32_t table_stride, const int32_t* seq_lens, int32_t B,
+                             void* out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return decode_impl(p, q, k_cache, v_cache, block_tables, table_stride, seq_lens, B, out, workspace, workspace_bytes,
+                       hip_stream);
+}
+
+// A tool that intercepts the launches (rocprofv3 loads its library through this variable)
+// times every dispatch itself; the library's own per-dispatch events are not attached then.
+static bool profiler_attached() {
+    const char* v = std::getenv("ROCP_TOOL_LIBRARIES");
+    return v && *v;
+}
+
 int32_t fea_profile_enable(int32_t max_calls, int32_t which) {
     if (max_calls < 0 || max_calls > 65536) return fail(FEA_EINVAL, "fea_profile_enable: max_calls=%d out of range", max_calls);
     if (which < -1 || which > 2) return fail(FEA_EINVAL, "fea_profile_enable: which=%d, expected -1, 0, 1 or 2", which);
+    if (max_calls > 0 && profiler_attached())
+        return fail(FEA_EINVAL, "fea_profile_enable: a profiling tool is attached to this process (ROCP_TOOL_LIBRARIES); "
+                                "it times the dispatches itself, the library's events stay off");
+    return guarded("fea_profile_enable", [&]() -> int32_t {
     g_prof_which = which;
     while ((int)g_ev_pool.size() < kEvPerCall * max_calls) {
         hipEvent_t ev;
@@ -248,6 +297,7 @@ int32_t fea_profile_enable(int32_t max_calls, int32_t which) {
     g_prof_on = max_calls > 0;
     g_prof_calls = 0;
     return FEA_OK;
+    });
 }
 
 int32_t fea_profile_read(int32_t call, float* ms) {

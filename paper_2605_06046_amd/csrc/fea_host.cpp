@@ -230,29 +230,35 @@ int32_t fea_kv_stats(const fea_kv_pool* pool, uint32_t* num_blocks, uint32_t* fr
 }
 
 int32_t fea_chunk_hashes(const int32_t* tokens, int64_t T, uint64_t* hashes) {
-    if (T < 0) return fail(FEA_EINVAL, "fea_chunk_hashes: T=%lld is negative", (long long)T);
-    if (T == 0) return FEA_OK;
-    if (!tokens || !hashes) return fail(FEA_EINVAL, "fea_chunk_hashes: NULL pointer");
-    chunk_hashes(tokens, T, hashes);
-    return FEA_OK;
+    return fea::guarded("fea_chunk_hashes", [&]() -> int32_t {
+        if (T < 0) return fail(FEA_EINVAL, "fea_chunk_hashes: T=%lld is negative", (long long)T);
+        if (T == 0) return FEA_OK;
+        if (!tokens || !hashes) return fail(FEA_EINVAL, "fea_chunk_hashes: NULL pointer");
+        chunk_hashes(tokens, T, hashes);
+        return FEA_OK;
+    });
 }
 
 int32_t fea_chunk_hashes_xxh64(const int32_t* tokens, int64_t T, uint64_t seed, uint64_t* hashes) {
-    if (T < 0) return fail(FEA_EINVAL, "fea_chunk_hashes_xxh64: T=%lld is negative", (long long)T);
-    if (T == 0) return FEA_OK;
-    if (!tokens || !hashes) return fail(FEA_EINVAL, "fea_chunk_hashes_xxh64: NULL pointer");
-    chunk_hashes_xxh64(tokens, T, seed, hashes);
-    return FEA_OK;
+    return fea::guarded("fea_chunk_hashes_xxh64", [&]() -> int32_t {
+        if (T < 0) return fail(FEA_EINVAL, "fea_chunk_hashes_xxh64: T=%lld is negative", (long long)T);
+        if (T == 0) return FEA_OK;
+        if (!tokens || !hashes) return fail(FEA_EINVAL, "fea_chunk_hashes_xxh64: NULL pointer");
+        chunk_hashes_xxh64(tokens, T, seed, hashes);
+        return FEA_OK;
+    });
 }
 
 int32_t fea_kv_set_hash(fea_kv_pool* pool, int32_t kind, uint64_t seed) {
-    if (!pool) return fail(FEA_EINVAL, "fea_kv_set_hash: pool is NULL");
-    if (kind != FEA_HASH_CHAINED && kind != FEA_HASH_XXH64) return fail(FEA_EINVAL, "fea_kv_set_hash: unknown kind %d", kind);
-    if (!pool->index.empty())
-        return fail(FEA_EINVAL, "fea_kv_set_hash: the pool holds registered prefixes; set the hash before the first table is built");
-    pool->hash_kind = kind;
-    pool->hash_seed = seed;
-    return FEA_OK;
+    return fea::guarded("fea_kv_set_hash", [&]() -> int32_t {
+        if (!pool) return fail(FEA_EINVAL, "fea_kv_set_hash: pool is NULL");
+        if (kind != FEA_HASH_CHAINED && kind != FEA_HASH_XXH64) return fail(FEA_EINVAL, "fea_kv_set_hash: unknown kind %d", kind);
+        if (!pool->index.empty())
+            return fail(FEA_EINVAL, "fea_kv_set_hash: the pool holds registered prefixes; set the hash before the first table is built");
+        pool->hash_kind = kind;
+        pool->hash_seed = seed;
+        return FEA_OK;
+    });
 }
 
 int32_t fea_build_block_tables(fea_kv_pool* pool, const int32_t* tokens, const int64_t* tok_offsets, int32_t B,
@@ -362,55 +368,59 @@ int32_t fea_build_block_tables(fea_kv_pool* pool, const int32_t* tokens, const i
 }
 
 int32_t fea_release(fea_kv_pool* pool, const int32_t* row, int32_t nb) {
-    if (!pool) return fail(FEA_EINVAL, "fea_release: pool is NULL");
-    if (nb < 0 || (nb > 0 && !row)) return fail(FEA_EINVAL, "fea_release: bad row");
-    // validate first (a block may legally appear several times in one row)
-    std::unordered_map<int32_t, int32_t> uses;
-    for (int32_t c = 0; c < nb; ++c) {
-        const int32_t b = row[c];
-        if (b < 0 || (uint32_t)b >= pool->num_blocks) return fail(FEA_EINVAL, "fea_release: block id %d out of range in column %d", b, c);
-        if (++uses[b] > pool->meta[b].refcount) return fail(FEA_EINVAL, "fea_release: block %d holds fewer references than the row drops", b);
-    }
-    for (int32_t c = 0; c < nb; ++c) {
-        const int32_t b = row[c];
-        if (--pool->meta[b].refcount == 0) {
-            pool->unindex(b);
-            pool->free_list.push_back(b);
+    return fea::guarded("fea_release", [&]() -> int32_t {
+        if (!pool) return fail(FEA_EINVAL, "fea_release: pool is NULL");
+        if (nb < 0 || (nb > 0 && !row)) return fail(FEA_EINVAL, "fea_release: bad row");
+        // validate first (a block may legally appear several times in one row)
+        std::unordered_map<int32_t, int32_t> uses;
+        for (int32_t c = 0; c < nb; ++c) {
+            const int32_t b = row[c];
+            if (b < 0 || (uint32_t)b >= pool->num_blocks) return fail(FEA_EINVAL, "fea_release: block id %d out of range in column %d", b, c);
+            if (++uses[b] > pool->meta[b].refcount) return fail(FEA_EINVAL, "fea_release: block %d holds fewer references than the row drops", b);
         }
-    }
-    return FEA_OK;
+        for (int32_t c = 0; c < nb; ++c) {
+            const int32_t b = row[c];
+            if (--pool->meta[b].refcount == 0) {
+                pool->unindex(b);
+                pool->free_list.push_back(b);
+            }
+        }
+        return FEA_OK;
+    });
 }
 
 int32_t fea_kv_extend(fea_kv_pool* pool, int32_t* bt, int32_t stride, int32_t* seq_lens, int32_t B, int32_t* n_new_blocks) {
-    if (!pool) return fail(FEA_EINVAL, "fea_kv_extend: pool is NULL");
-    if (B < 0 || stride < 0 || (B > 0 && (!bt || !seq_lens))) return fail(FEA_EINVAL, "fea_kv_extend: bad arguments");
-    // validate everything and count the blocks needed before touching anything
-    size_t need = 0;
-    for (int32_t i = 0; i < B; ++i) {
-        const int32_t L = seq_lens[i];
-        if (L < 0 || L == INT32_MAX) return fail(FEA_EINVAL, "fea_kv_extend: seq_lens[%d]=%d out of range", i, L);
-        if (L % kK == 0) {
-            if (L / kK >= stride) return fail(FEA_ERANGE, "fea_kv_extend: request %d needs column %d, the table has %d", i, L / kK, stride);
-            ++need;
+    return fea::guarded("fea_kv_extend", [&]() -> int32_t {
+        if (!pool) return fail(FEA_EINVAL, "fea_kv_extend: pool is NULL");
+        if (B < 0 || stride < 0 || (B > 0 && (!bt || !seq_lens))) return fail(FEA_EINVAL, "fea_kv_extend: bad arguments");
+        // validate everything and count the blocks needed before touching anything
+        size_t need = 0;
+        for (int32_t i = 0; i < B; ++i) {
+            const int32_t L = seq_lens[i];
+            if (L < 0 || L == INT32_MAX) return fail(FEA_EINVAL, "fea_kv_extend: seq_lens[%d]=%d out of range", i, L);
+            if (L % kK == 0) {
+                if (L / kK >= stride) return fail(FEA_ERANGE, "fea_kv_extend: request %d needs column %d, the table has %d", i, L / kK, stride);
+                ++need;
+            }
         }
-    }
-    if (need > pool->free_list.size())
-        return fail(FEA_ENOMEM, "fea_kv_extend: %zu blocks needed, %zu free", need, pool->free_list.size());
-    for (int32_t i = 0; i < B; ++i) {
-        const int32_t L = seq_lens[i];
-        if (L % kK == 0) {   // the new token opens a block: a private one, it holds no registered prefix
-            const int32_t b = pool->free_list.front();
-            pool->free_list.pop_front();
-            fea::BlockMeta& m = pool->meta[b];
-            m.refcount = 1;
-            m.parent = -1;
-            m.level = -1;
-            bt[(size_t)i * stride + L / kK] = b;
+        if (need > pool->free_list.size())
+            return fail(FEA_ENOMEM, "fea_kv_extend: %zu blocks needed, %zu free", need, pool->free_list.size());
+        for (int32_t i = 0; i < B; ++i) {
+            const int32_t L = seq_lens[i];
+            if (L % kK == 0) {   // the new token opens a block: a private one, it holds no registered prefix
+                const int32_t b = pool->free_list.front();
+                pool->free_list.pop_front();
+                fea::BlockMeta& m = pool->meta[b];
+                m.refcount = 1;
+                m.parent = -1;
+                m.level = -1;
+                bt[(size_t)i * stride + L / kK] = b;
+            }
+            seq_lens[i] = L + 1;
         }
-        seq_lens[i] = L + 1;
-    }
-    if (n_new_blocks) *n_new_blocks = (int32_t)need;
-    return FEA_OK;
+        if (n_new_blocks) *n_new_blocks = (int32_t)need;
+        return FEA_OK;
+    });
 }
 
 int32_t fea_validate_block_tables(const int32_t* bt, int32_t stride, const int32_t* seq_lens, int32_t B, uint32_t num_blocks) {

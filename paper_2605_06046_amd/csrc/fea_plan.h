@@ -110,6 +110,7 @@ struct SweepArgs {
     const void* k_cache;
     const void* v_cache;
     const int32_t* bt;
+    const int32_t* seq_lens;
     void* out;
     char* ws;
     WsLayout lay;

@@ -27,12 +27,12 @@ class AttnParams(C.Structure):
     _fields_ = [("num_q_heads", C.c_int32), ("num_kv_heads", C.c_int32), ("head_dim", C.c_int32),
                 ("block_size", C.c_int32), ("dtype", C.c_int32), ("scale", C.c_float),
                 ("split_blocks", C.c_int32), ("max_group", C.c_int32), ("flags", C.c_int32),
-                ("reserved", C.c_int32 * 3)]
+                ("run_kernel_min", C.c_int32), ("merge_rows_min", C.c_int32), ("reserved", C.c_int32)]
 
     def __init__(self, num_q_heads, num_kv_heads, head_dim, dtype, scale=0.0, split_blocks=0,
-                 max_group=0, flags=0, block_size=16):
+                 max_group=0, flags=0, block_size=16, run_kernel_min=0, merge_rows_min=0):
         super().__init__(num_q_heads, num_kv_heads, head_dim, block_size, dtype, scale,
-                         split_blocks, max_group, flags)
+                         split_blocks, max_group, flags, run_kernel_min, merge_rows_min, 0)
 
 
 def library_path() -> str:
@@ -93,6 +93,7 @@ def load_library() -> C.CDLL:
         "fea_decode_workspace_bytes": (i32, [C.POINTER(AttnParams), i32, i32, C.POINTER(C.c_size_t)]),
         "fea_decode_attention": (i32, [C.POINTER(AttnParams), vp, vp, vp, vp, i32, vp, i32, vp, vp, C.c_size_t, vp]),
         "fea_decode_plan_info": (i32, [vp, vp, vp]),
+        "fea_stream_read_gbs": (i32, [vp, C.c_size_t, i32, i32, vp, C.POINTER(C.c_double)]),
         "fea_profile_enable": (i32, [i32, i32]),
         "fea_profile_read": (i32, [i32, vp]),
         "fea_kv_extend": (i32, [vp, vp, i32, vp, i32, C.POINTER(i32)]),
@@ -288,6 +289,16 @@ def fea_kv_append(params: AttnParams, k_new, v_new, k_cache, v_cache, block_tabl
     _check(load_library().fea_kv_append(C.byref(params), _dev_ptr(k_new), _dev_ptr(v_new), _dev_ptr(k_cache),
                                         _dev_ptr(v_cache), _dev_ptr(block_tables), block_tables.shape[1],
                                         _dev_ptr(seq_lens), block_tables.shape[0], C.c_void_p(st.cuda_stream)))
+
+
+def fea_stream_read_gbs(buffer, scattered: bool = True, repeats: int = 5, stream=None) -> float:
+    """GB/s at which the GPU streams the contiguous GPU tensor `buffer` through the sweep's fetch path."""
+    import torch
+    st = stream if stream is not None else torch.cuda.current_stream()
+    out = C.c_double()
+    _check(load_library().fea_stream_read_gbs(_dev_ptr(buffer), buffer.numel() * buffer.element_size(), int(bool(scattered)),
+                                              int(repeats), C.c_void_p(st.cuda_stream), C.byref(out)))
+    return out.value
 
 
 def fea_profile_enable(max_calls: int, which: int = -1) -> None:

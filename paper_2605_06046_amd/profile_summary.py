@@ -6,15 +6,17 @@
 (run from /tmp with TMPDIR=/tmp; bench.py by absolute path):
 
     rocprofv3 --kernel-trace --stats -d <raw_dir>/trace_W -o t --output-format csv -- \\
-        python3 bench.py --workload W --no-cpu-baseline --steps 200 --warmup 20
+        python3 bench.py --workload W --no-cpu-baseline --no-configs --no-hbm-calibration --steps 200 --warmup 20
     rocprofv3 --pmc FETCH_SIZE --kernel-trace -d <raw_dir>/pmc_FETCH_SIZE_W -o p --output-format csv -- \\
-        python3 bench.py --workload W --no-cpu-baseline --steps 40 --warmup 4 --copy-calibration
+        python3 bench.py --workload W --no-cpu-baseline --no-configs --no-hbm-calibration --steps 40 --warmup 4 --copy-calibration
     rocprofv3 --pmc WRITE_SIZE --kernel-trace -d <raw_dir>/pmc_WRITE_SIZE_W -o p --output-format csv -- \\
-        python3 bench.py --workload W --no-cpu-baseline --steps 40 --warmup 4 --copy-calibration
+        python3 bench.py --workload W --no-cpu-baseline --no-configs --no-hbm-calibration --steps 40 --warmup 4 --copy-calibration
 
 and, optionally, <raw_dir>/untraced_W.json: the output line of the first command run
-without the profiler (the library's own per-dispatch events read longer while the
-profiler intercepts the launches, so this is the line to compare with).
+without the profiler.  Under the profiler the library's own per-dispatch events are
+off (fea_profile_enable refuses while a profiling tool is attached, and bench.py then
+reports no kernel durations of its own), so that line is the one whose live-measured
+kernel duration is set against the profiler's.
 
 --copy-calibration makes bench.py start with three plain 1 GiB device-to-device
 copies; what the counters read for them fixes the scale of each counter.
@@ -36,7 +38,8 @@ def kernel_rev(root: str) -> str:
     a build whose sweep source is the same and whose plan for the workload (stored next to them) is the
     same, since the kernel then does the same loads and stores."""
     h = hashlib.sha256()
-    h.update(open(os.path.join(root, "paper_2605_06046_amd", "csrc", "fea_sweep_mfma.hip"), "rb").read())
+    for name in ("fea_sweep_mfma.hip", "fea_plan.h"):
+        h.update(open(os.path.join(root, "paper_2605_06046_amd", "csrc", name), "rb").read())
     return h.hexdigest()[:12]
 
 
@@ -64,17 +67,17 @@ def main(raw: str, wl: str, out: str) -> None:
     stats = list(csv.DictReader(open(_one(f"{raw}/trace_{wl}/**/*kernel_stats.csv"))))
     ours = [r for r in stats if r["Name"].startswith(("fea::", "void fea::"))]
     lines = ["Commands (from /tmp with TMPDIR=/tmp, bench.py by its absolute path; raw output in <raw>):",
-             f"  rocprofv3 --kernel-trace --stats -d <raw>/trace_{wl} -o t --output-format csv -- python3 bench.py --workload {wl} --no-cpu-baseline --steps 200 --warmup 20",
-             f"  rocprofv3 --pmc FETCH_SIZE --kernel-trace -d <raw>/pmc_FETCH_SIZE_{wl} -o p --output-format csv -- python3 bench.py --workload {wl} --no-cpu-baseline --steps 40 --warmup 4 --copy-calibration",
-             f"  rocprofv3 --pmc WRITE_SIZE --kernel-trace -d <raw>/pmc_WRITE_SIZE_{wl} -o p --output-format csv -- python3 bench.py --workload {wl} --no-cpu-baseline --steps 40 --warmup 4 --copy-calibration",
-             f"  python3 bench.py --workload {wl} --no-cpu-baseline --steps 200 --warmup 20    (no profiler)",
+             f"  rocprofv3 --kernel-trace --stats -d <raw>/trace_{wl} -o t --output-format csv -- python3 bench.py --workload {wl} --no-cpu-baseline --no-configs --no-hbm-calibration --steps 200 --warmup 20",
+             f"  rocprofv3 --pmc FETCH_SIZE --kernel-trace -d <raw>/pmc_FETCH_SIZE_{wl} -o p --output-format csv -- python3 bench.py --workload {wl} --no-cpu-baseline --no-configs --no-hbm-calibration --steps 40 --warmup 4 --copy-calibration",
+             f"  rocprofv3 --pmc WRITE_SIZE --kernel-trace -d <raw>/pmc_WRITE_SIZE_{wl} -o p --output-format csv -- python3 bench.py --workload {wl} --no-cpu-baseline --no-configs --no-hbm-calibration --steps 40 --warmup 4 --copy-calibration",
+             f"  python3 bench.py --workload {wl} --no-cpu-baseline --no-configs --no-hbm-calibration --steps 200 --warmup 20    (no profiler)",
              f"  python3 -m paper_2605_06046_amd.profile_summary <raw> {wl} profiles",
              "", "Kernel trace (library kernels only; durations in microseconds)", "",
              f"{'kernel':58s} {'calls':>6s} {'avg':>9s} {'min':>9s} {'max':>9s} {'share':>7s}"]
     for r in ours:
         lines.append(f"{r['Name'][:58]:58s} {r['Calls']:>6s} {float(r['AverageNs']) / 1e3:9.2f} "
                      f"{float(r['MinNs']) / 1e3:9.2f} {float(r['MaxNs']) / 1e3:9.2f} {float(r['Percentage']):6.2f}%")
-    sweep = next(r for r in ours if "sweep" in r["Name"])
+    sweep = max((r for r in ours if "sweep" in r["Name"]), key=lambda r: float(r["TotalDurationNs"]))
     res = {"workload": wl, "kernel": sweep["Name"], "avg_us": float(sweep["AverageNs"]) / 1e3,
            "kernel_rev": kernel_rev(root)}
     lines += ["", "HBM traffic of the sweep kernel per launch (rocprofv3 --pmc, one counter per run):"]
@@ -97,8 +100,7 @@ def main(raw: str, wl: str, out: str) -> None:
     res["plan"] = bench["plan"]
     lines += [f"  total {total / 1e6:.2f} MB per launch; algorithmic (distinct live KV blocks, K and V): "
               f"{res['unique_kv_bytes'] / 1e6:.2f} MB; ratio {total / res['unique_kv_bytes']:.3f}",
-              "", "bench.py line of the traced run (events inside bench.py, same command; the profiler's interception adds to them):",
-              f"  sweep avg {bench['kernel_us']['sweep']:.2f} us by HIP events vs {res['avg_us']:.2f} us by rocprofv3"]
+              ""]
     un = f"{raw}/untraced_{wl}.json"
     if os.path.exists(un):
         b2 = json.loads(open(un).read().strip().splitlines()[-1])

@@ -58,17 +58,21 @@ def test_peaked_softmax_variant(name):
     assert_close(out, want, "bf16", what=name + " peaked")
 
 
-@pytest.mark.parametrize("name,sample", [("c2", 6), ("c3", 8), ("c4", 2), ("c5", 8)])
-def test_full_size_configs_sampled(name, sample):
+@pytest.mark.parametrize("name", ["c2", "c3", "c4", "c5"])
+def test_full_size_configs_every_row(name):
+    """The full-size batches in the launch configuration the benchmark times: every output row of
+    every request against the oracle (tables bit-exact first)."""
     wl = W.generate(W.CONFIGS[name])
     out, bt, lens, info = run_workload(wl)
-    rng = np.random.default_rng(wl.spec.seed)
-    rows = sorted(set(rng.choice(wl.spec.batch, size=sample, replace=False).tolist()) | {0, wl.spec.batch - 1})
-    want = oracle_for(wl, bt, lens, requests=rows)
-    print(name, info, assert_close(out, want, "bf16", rows=rows, what=name + " full"))
-    assert np.isfinite(out).all()
-    # identical histories would give identical outputs; here: every row is finite and bounded by max |v|
-    assert np.abs(out).max() <= np.nanmax(np.abs(values(wl.v_cache)[np.unique(bt[bt >= 0])])) + 1e-3
+    _check_tables(wl, bt, lens)
+    assert info["overflow"] == 0 and info["variant"] == 1
+    want = oracle_for(wl, bt, lens)
+    print(name, info, assert_close(out, want, "bf16", what=name + " full size, all rows"))
+    # row by row as well: no single request may hide behind the batch-wide relative error
+    err = np.abs(out - want).reshape(wl.spec.batch, -1).max(axis=1)
+    rl2 = (np.linalg.norm((out - want).reshape(wl.spec.batch, -1), axis=1)
+           / np.maximum(np.linalg.norm(want.reshape(wl.spec.batch, -1), axis=1), 1e-30))
+    assert err.max() <= 2e-2 and rl2.max() <= 6e-3, (int(err.argmax()), float(err.max()), int(rl2.argmax()), float(rl2.max()))
 
 
 def _random_tables(seed, B, Hkv, d, dtype, lens, num_blocks, mode):
@@ -105,7 +109,8 @@ def _random_tables(seed, B, Hkv, d, dtype, lens, num_blocks, mode):
                                   [0, 160, 161, 500, 512, 100, 160, 160, 700, 48, 64, 49, 1000]])
 def test_any_block_table_is_handled(mode, dtype, Hq, Hkv, d, lens):
     B = len(lens)
-    bt, k, v = _random_tables(hash(mode) % 1000, B, Hkv, d, dtype, lens, 40, mode)
+    seed = {"random": 101, "same_first_then_random": 202, "nested": 303, "all_same_block": 404, "identical_rows": 505}[mode]
+    bt, k, v = _random_tables(seed, B, Hkv, d, dtype, lens, 40, mode)
     rng = np.random.default_rng(5)
     q = rng.standard_normal((B, Hq, d), dtype=np.float32)
     if dtype == "bf16":
@@ -462,7 +467,7 @@ def test_three_level_prefix_sharing():
 
 
 @pytest.mark.parametrize("case", ["c2_small", "c3_small", "two_level", "nested_tables", "random_tables", "odd_stride"])
-def test_runs_found_on_many_workgroups_give_the_same_plan(case, monkeypatch):
+def test_runs_found_on_many_workgroups_give_the_same_plan(case):
     """Large tables have their leaders and common runs found by a kernel of many workgroups before the
     planner; forced on here for small ones: same plan (group counts, items, rows), bitwise the same output."""
     if case in ("c2_small", "c3_small"):
@@ -485,8 +490,7 @@ def test_runs_found_on_many_workgroups_give_the_same_plan(case, monkeypatch):
         q = W.f32_to_bf16_bits(np.random.default_rng(5).standard_normal((len(lens_l), 32, 128), dtype=np.float32))
         shape = (32, 8, 128, "bf16")
     base, info = run_hip(q, k, v, bt, lens, *shape)
-    monkeypatch.setenv("FEA_RUN_KERNEL_MIN", "0")
-    forced, info2 = run_hip(q, k, v, bt, lens, *shape)
+    forced, info2 = run_hip(q, k, v, bt, lens, *shape, run_kernel_min=-1)
     assert info2 == info
     assert np.array_equal(base, forced)
     assert_close(forced, decode_attention(values(q), values(k), values(v), bt, lens), "bf16", what=case)
@@ -494,15 +498,14 @@ def test_runs_found_on_many_workgroups_give_the_same_plan(case, monkeypatch):
 
 @pytest.mark.parametrize("dtype,Hq,Hkv,d", [("f32", 4, 4, 32), ("f32", 6, 2, 128), ("f32", 2, 1, 256), ("bf16", 12, 4, 64),
                                             ("bf16", 8, 8, 256), ("bf16", 32, 8, 128), ("bf16", 64, 8, 128)])
-def test_merge_with_several_rows_per_wave(dtype, Hq, Hkv, d, monkeypatch):
+def test_merge_with_several_rows_per_wave(dtype, Hq, Hkv, d):
     """Batches of very many rows are merged several rows to a wave; forced on here for small ones,
     including rows with many partials, rows of zero length and a ragged last wave."""
     spec = W.Spec("rows", 27, dtype, Hq, Hkv, d, ((5, 96), (3, 0), (1, 1200)), (1, 200))
     wl = W.generate(spec)
     want = None
-    for forced in ("1000000000", "0"):
-        monkeypatch.setenv("FEA_MERGE_BY_ROWS_MIN", forced)
-        out, bt, lens, info = run_workload(wl, split_blocks=2 if forced == "0" else 0)   # many pieces per row
+    for forced in (1000000000, -1):                    # never / always several rows per wave
+        out, bt, lens, info = run_workload(wl, split_blocks=2 if forced < 0 else 0, merge_rows_min=forced)   # many pieces per row
         want = oracle_for(wl, bt, lens) if want is None else want
         assert_close(out, want, dtype, what=f"merge rows {forced} {dtype} {Hq}/{Hkv}/{d}")
 
@@ -545,7 +548,7 @@ def _random_prefix_tree_batch(seed, dtype, Hq, Hkv, d):
 
 
 @pytest.mark.parametrize("seed", range(10))
-def test_random_prefix_trees(seed, monkeypatch):
+def test_random_prefix_trees(seed):
     """Random prefix trees through every path of the alias detection (nested runs, several levels,
     odd table strides, the many-workgroup run kernel forced on and off) against the oracle."""
     dtype, Hq, Hkv, d = [("bf16", 32, 8, 128), ("bf16", 28, 4, 128), ("bf16", 8, 8, 128), ("f32", 8, 2, 64),
@@ -555,6 +558,5 @@ def test_random_prefix_trees(seed, monkeypatch):
     want = oracle_for(wl, bt, lens)
     assert info["overflow"] == 0
     assert_close(out, want, dtype, what=f"tree {seed}")
-    monkeypatch.setenv("FEA_RUN_KERNEL_MIN", "0")
-    out2, _, _, info2 = run_workload(wl)
+    out2, _, _, info2 = run_workload(wl, run_kernel_min=-1)
     assert info2 == info and np.array_equal(out, out2)
