@@ -257,6 +257,28 @@ int32_t fea_decode_attention(const fea_attn_params* p,
                              void* workspace, size_t workspace_bytes,
                              void* hip_stream);
 
+/* fea_decode_attention for callers that cannot allocate device memory and have no
+ * workspace to pass: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid allocation.  Same arguments, same result, bit for bit; the plan and the
+ * partial results live in a buffer of FEA_STATIC_WORKSPACE_BYTES that is part of the
+ * library's device image (every GPU the library runs on holds its own copy until
+ * the process ends).  The call allocates nothing, on the host or on the device
+ * (the buffer's device address is looked up once per GPU, at the first call on it).
+ * A batch whose fea_decode_workspace_bytes() exceeds FEA_STATIC_WORKSPACE_BYTES is
+ * refused with FEA_ERANGE (use fea_decode_attention with a workspace of your own).
+ * All calls on one GPU share the buffer: it keeps the previous call's contents
+ * (nothing in it has to start at zero - every call writes its plan before reading
+ * it), and calls that overlap in time on one GPU - different streams, different
+ * threads - race on it and give undefined results; order them on one stream.
+ * FEA_FLAG_REUSE_PLAN and FEA_FLAG_PLAN_ONLY are refused (FEA_EINVAL): another
+ * caller may have used the buffer in between.  Other errors as fea_decode_attention. */
+#define FEA_STATIC_WORKSPACE_BYTES (48u << 20)
+int32_t fea_decode_attention_static(const fea_attn_params* p,
+                                    const void* q, const void* k_cache, const void* v_cache,
+                                    const int32_t* block_tables, int32_t table_stride,
+                                    const int32_t* seq_lens, int32_t B,
+                                    void* out, void* hip_stream);
+
 /* Summary of the plan the last fea_decode_attention call left in `workspace`
  * (synchronises hip_stream; for tests, tuning and the benchmark's reporting).
  * info: HOST int32[8] = { work items, prefix groups, requests in groups,

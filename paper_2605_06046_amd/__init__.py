@@ -12,5 +12,5 @@ from .fea import (  # noqa: F401
     fea_validate_block_tables, fea_profile_enable, fea_profile_read, library_path, load_library,
     Cht, StopPolicy, fea_kv_extend, fea_kv_append, Policy, PolicyParams,
     FEA_ADD, FEA_STOP, FEA_POLICY_UCB, FEA_POLICY_QLEARN, FEA_HASH_CHAINED, FEA_HASH_XXH64,
-    fea_chunk_hashes_xxh64, fea_kv_set_hash, fea_chunk_hashes_device, fea_stream_read_gbs,
+    fea_chunk_hashes_xxh64, fea_kv_set_hash, fea_chunk_hashes_device, fea_decode_attention_static, fea_stream_read_gbs,
 )

@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfea.so")
-SOURCES = ["fea_host.cpp", "fea_cht.cpp", "fea_policy.cpp", "fea_planner.hip", "fea_sweep_generic.hip", "fea_sweep_mfma.hip", "fea_append.hip", "fea_hash.hip", "fea_decode.hip", "fea_calibrate.hip"]
+SOURCES = ["fea_host.cpp", "fea_cht.cpp", "fea_policy.cpp", "fea_planner.hip", "fea_sweep_generic.hip", "fea_sweep_mfma.hip", "fea_append.hip", "fea_hash.hip", "fea_decode.hip", "fea_decode_static.hip", "fea_calibrate.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -92,6 +92,7 @@ def load_library() -> C.CDLL:
         "fea_validate_block_tables": (i32, [vp, i32, vp, i32, u32]),
         "fea_decode_workspace_bytes": (i32, [C.POINTER(AttnParams), i32, i32, C.POINTER(C.c_size_t)]),
         "fea_decode_attention": (i32, [C.POINTER(AttnParams), vp, vp, vp, vp, i32, vp, i32, vp, vp, C.c_size_t, vp]),
+        "fea_decode_attention_static": (i32, [C.POINTER(AttnParams), vp, vp, vp, vp, i32, vp, i32, vp, vp]),
         "fea_decode_plan_info": (i32, [vp, vp, vp]),
         "fea_stream_read_gbs": (i32, [vp, C.c_size_t, i32, i32, vp, C.POINTER(C.c_double)]),
         "fea_profile_enable": (i32, [i32, i32]),
@@ -254,6 +255,21 @@ def fea_decode_attention(params: AttnParams, q, k_cache, v_cache, block_tables, 
         C.byref(params), _dev_ptr(q), _dev_ptr(k_cache), _dev_ptr(v_cache), _dev_ptr(block_tables),
         block_tables.shape[1], _dev_ptr(seq_lens), q.shape[0], _dev_ptr(out), _dev_ptr(workspace),
         workspace.numel() * workspace.element_size(), C.c_void_p(st.cuda_stream)))
+
+
+def fea_decode_attention_static(params: AttnParams, q, k_cache, v_cache, block_tables, seq_lens, out, stream=None) -> None:
+    """fea_decode_attention on the library's built-in workspace (allocates nothing).  Asynchronous."""
+    import torch
+    for name, t in (("q", q), ("k_cache", k_cache), ("v_cache", v_cache), ("block_tables", block_tables),
+                    ("seq_lens", seq_lens), ("out", out)):
+        if not t.is_cuda or not t.is_contiguous():
+            raise ValueError(f"{name} must be a contiguous GPU tensor")
+    if block_tables.dtype != torch.int32 or seq_lens.dtype != torch.int32:
+        raise ValueError("block_tables and seq_lens must be int32")
+    st = stream if stream is not None else torch.cuda.current_stream()
+    _check(load_library().fea_decode_attention_static(
+        C.byref(params), _dev_ptr(q), _dev_ptr(k_cache), _dev_ptr(v_cache), _dev_ptr(block_tables),
+        block_tables.shape[1], _dev_ptr(seq_lens), q.shape[0], _dev_ptr(out), C.c_void_p(st.cuda_stream)))
 
 
 def fea_chunk_hashes_device(tokens, tok_offsets, hash_offsets, hashes, stream=None) -> None:
