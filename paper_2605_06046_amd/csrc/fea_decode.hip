@@ -27,12 +27,12 @@ static int env_int(const char* name, int dflt) {
 // second thread sets) cannot switch kernels or move the workspace layout between the
 // sizing call and the attention call.  What tests need to steer is in fea_attn_params.
 struct Knobs {
-    int force_generic, sweep_grid, spare_waves, min_piece, min_run, w32, w64;
+    int force_generic, sweep_grid, spare_waves, min_piece, min_run, w32, w64, no_fast_shared, w_team;
 };
 static const Knobs& knobs() {
     static const Knobs k = {env_int("FEA_FORCE_GENERIC", 0), env_int("FEA_SWEEP_GRID", 0), env_int("FEA_SPARE_WAVES", 16),
                             env_int("FEA_MIN_PIECE", 4),     env_int("FEA_MIN_RUN", 2),    env_int("FEA_W32", 20),
-                            env_int("FEA_W64", 24)};
+                            env_int("FEA_W64", 24), env_int("FEA_NO_FAST_SHARED", 0), env_int("FEA_WTEAM", 12)};
     return k;
 }
 
@@ -99,7 +99,7 @@ static int32_t resolve(const fea_attn_params* p, int32_t B, int32_t stride, Reso
     r.split_user = p->split_blocks > 0 ? ((p->split_blocks + 1) & ~1) : 0;
     // the sweep grid the plan is cut for: one single-wave workgroup per SIMD on the
     // matrix-core path, a few workgroups per CU on the generic path
-    r.grid = kn.sweep_grid > 0 ? kn.sweep_grid : (r.variant == 1 ? 4 : 8) * cu_count();
+    r.grid = kn.sweep_grid > 0 ? std::max(4, kn.sweep_grid & ~3) : (r.variant == 1 ? 4 : 8) * cu_count();   // waves; four to a workgroup on the matrix-core path
     // The plan is cut for a few waves fewer than the grid has.  With every one of the
     // 4 x CUs single-wave workgroups busy from start to end, a handful of them (the first
     // ones dispatched) were measured to run about 1.5x longer than the rest, whatever
@@ -107,7 +107,8 @@ static int32_t resolve(const fea_attn_params* p, int32_t B, int32_t stride, Reso
     r.tune.n_waves = std::max(1, r.grid - std::min(r.grid / 2, std::max(0, kn.spare_waves)));
     r.tune.min_piece = std::max(1, kn.min_piece);
     r.tune.min_run = std::max(1, kn.min_run);
-    r.tune.weights = std::min(255, std::max(16, kn.w32)) | (std::min(255, std::max(16, kn.w64)) << 8);
+    r.tune.weights = std::min(255, std::max(16, kn.w32)) | (std::min(255, std::max(16, kn.w64)) << 8) |
+                     (std::min(255, std::max(1, kn.w_team)) << 16);
     // Large tables: the rows are compared on many workgroups before the planner's one workgroup
     // takes over (a second launch, so only where the rows are long or many enough to pay for it).
     const int64_t groupable = std::min(B, kGroupReqMax);
@@ -128,7 +129,7 @@ static int32_t resolve(const fea_attn_params* p, int32_t B, int32_t stride, Reso
         max_items = segs * per + 64;
         max_rows = 2 * rows * per + 64;
     } else {
-        max_items = segs + 3ll * r.grid + 64;                // pieces of shared runs + cuts of the private stream
+        max_items = segs + 5ll * r.grid + 2ll * B + 64;      // pieces of shared runs (with team slots) + cuts of the private stream
         max_rows = 2 * rows + (int64_t)r.grid * (rows_per_item + 2 * r.G) + 64;
     }
     if (max_items > 0x3FFFFFFF || max_rows > 0x3FFFFFFF) return fail(FEA_EINVAL, "%s: split_blocks too small for this problem size", who);
@@ -253,6 +254,7 @@ int32_t decode_impl(const fea_attn_params* p, const void* q, const void* k_cache
     sa.Hkv = p->num_kv_heads;
     sa.G = r.G;
     sa.mpt = r.mpt;
+    sa.fast_shared = ((int64_t)B * p->num_q_heads < (1 << 23) && !knobs().no_fast_shared) ? 1 : 0;
     if (r.variant == 1) launch_sweep_mfma(sa, r.grid, where[1]);
     else launch_sweep_generic(sa, p->dtype, p->head_dim, r.grid, where[1]);
     launch_merge(sa, p->dtype, p->head_dim, r.merge_by_rows != 0, where[2]);

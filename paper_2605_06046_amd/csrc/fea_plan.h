@@ -61,7 +61,7 @@ struct SegDesc {
 
 struct Item {          // one KV sweep: a row set x one KV head x a column range (32 bytes)
     int32_t who;       // request whose table row is read (the group's leader for a shared run)
-    int32_t g;         // KV head
+    int32_t g;         // KV head (bits 0-15); pieces of shared runs swept by a team of waves: team size (bits 16-19), rank (bits 20-23)
     int32_t nrows;     // query rows: (requests in the row set) x (group heads)
     int32_t mlist_off; // the row set's request ids start at members[mlist_off]; -1: just `who`
     int32_t c0, c1;    // table columns [c0, c1) of `who`'s row
@@ -116,6 +116,7 @@ struct SweepArgs {
     WsLayout lay;
     float scale_log2;    // softmax scale times log2(e): scores live in the base-2 domain
     int32_t stride, B, Hq, Hkv, G, mpt;
+    int32_t fast_shared;   // q is small enough for 32-bit byte offsets: the hand-scheduled shared-run sequence may be used
 };
 
 // launchers (defined next to their kernels); stream is a hipStream_t

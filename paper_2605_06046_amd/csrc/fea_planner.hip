@@ -381,6 +381,18 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
     const int w32 = a.tune.weights & 255, w64 = (a.tune.weights >> 8) & 255;
     auto tile_weight = [&](int rows) { return rows <= 16 ? 16 : (rows <= 32 ? w32 : w64); };
     const FastDiv by_mpt(a.mpt);
+    // Row tiles of one piece of a shared run read the same KV bytes.  On the matrix-core path the sweep
+    // runs them as a team of 2 or 4 waves of one workgroup that fetches every tile once; for that the
+    // row tiles of a piece sit on neighbouring shares, in slots of 1, 2 or a multiple of 4 (the slots
+    // past the last row tile hold waves that only help fetching), and every group starts on a multiple of 4.
+    const bool teams = a.variant == 1 && a.split_user == 0;   // (with a fixed split a share holds several items: no teams)
+    auto tiles_padded = [&](int tiles_r) { return (!teams || tiles_r <= 2) ? tiles_r : ((tiles_r + 3) & ~3); };
+    auto items_padded = [&](int n) { return teams ? ((n + 3) & ~3) : n; };
+    // cost of one 32-token tile of a shared run per wave that sweeps it, for a group of cnt members: a team
+    // fetches the tile once for all its row tiles and overlaps the two products, which makes the tile far
+    // cheaper for a wave than a tile it streams and sweeps alone
+    const int w_team = (a.tune.weights >> 16) & 255;
+    auto group_weight = [&](int cnt) { return (teams && by_mpt.cdiv(cnt) >= 2) ? w_team : tile_weight(min(a.mpt, cnt) * a.G); };
 
     // ---- nested prefixes.  Members of a group may go on sharing blocks past the group's
     // run (a common system prompt, then a few conversations: the radix patterns of
@@ -502,8 +514,8 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
                 if (lead2[k] >= 0) {
                     const int c2 = u.c.cnt[lead2[k]], run2 = u.c.run[lead2[k]];
                     // private sweeps saved plus the outer group's relief against the subgroup's own sweep
-                    const long long gain = 16ll * c2 * (run2 - r1[k]) + (long long)r1[k] * tile_weight(a.mpt * a.G) * by_mpt.div(c2);
-                    const long long cost = (long long)run2 * tile_weight(min(a.mpt, c2) * a.G) * by_mpt.cdiv(c2);
+                    const long long gain = 16ll * c2 * (run2 - r1[k]) + (long long)r1[k] * group_weight(2 * a.mpt) * by_mpt.div(c2);
+                    const long long cost = (long long)run2 * group_weight(c2) * by_mpt.cdiv(c2);
                     adopt[k] = c2 >= 2 && gain > cost;
                     if (adopt[k] && lead2[k] == tid + k * kPlanThreads) atomicAdd(&s_adopt, 1);
                 }
@@ -644,7 +656,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
             int ld, cnt, run;
             group(gi, ld, cnt, run);
             const long long t = (long long)Hkv * by_mpt.cdiv(cnt) * ((run + 1) >> 1);
-            u_loc += t * tile_weight(min(a.mpt, cnt) * a.G);
+            u_loc += t * group_weight(cnt);
             t_loc += t;
         }
         const long long U = wsum(u_loc) + 16ll * T_pr, total_tiles = wsum(t_loc) + T_pr;
@@ -660,10 +672,10 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
                 int ld, cnt, run;
                 group(gi, ld, cnt, run);
                 const int T_seg = (run + 1) >> 1;
-                const int want = fixed_tiles > 0 ? fixed_tiles : max(1, idiv(Q, tile_weight(min(a.mpt, cnt) * a.G)));
+                const int want = fixed_tiles > 0 ? fixed_tiles : max(1, idiv(Q, group_weight(cnt)));
                 const int n_pc = idiv(T_seg + want - 1, want);
                 v.g.npc[gi] = n_pc;
-                loc += Hkv * by_mpt.cdiv(cnt) * n_pc;
+                loc += items_padded(Hkv * tiles_padded(by_mpt.cdiv(cnt)) * n_pc);
             }
             n_sh = (int)wsum(loc);
             if (fixed_tiles > 0) break;
@@ -682,7 +694,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
                 int ld, cnt, run;
                 group(gi, ld, cnt, run);
                 nsg = Hkv * by_mpt.cdiv(cnt);
-                ni = nsg * v.g.npc[gi];
+                ni = items_padded(Hkv * tiles_padded(by_mpt.cdiv(cnt)) * v.g.npc[gi]);
                 nr = Hkv * v.g.npc[gi] * cnt * a.G;
             }
             int ti, ts, tr;
@@ -815,19 +827,30 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
                 gd.pad[0] = gd.pad[1] = 0;
                 grp[ld] = gd;
             }
-            const FastDiv by_tr(tiles_r), by_pc(n_pc);
-            const int n = Hkv * n_pc * tiles_r;
+            const int tiles_p = tiles_padded(tiles_r);
+            const int team = (teams && tiles_r >= 2) ? (tiles_r == 2 ? 2 : 4) : 0;
+            const FastDiv by_tp(tiles_p), by_pc(n_pc);
+            const int n = Hkv * n_pc * tiles_p, n_slots = items_padded(n);
             const int full_rows = a.mpt * a.G, last_rows = (cnt - (tiles_r - 1) * a.mpt) * a.G;
             // partial rows of segment (g, tau): pieces p = 0 .. n_pc-1, rows(tau) each; segments in (g, tau) order
             const int rows_per_head = cnt * a.G;
-            for (int k = l0; k < n; k += lstep) {
-                const int rest = by_tr.div(k), tau = k - rest * tiles_r;
+            for (int k = l0; k < n_slots; k += lstep) {
+                Item* dst = &items[v.g.ibase[gi] + k];
+                if (k >= n) {                          // filler up to the next multiple of 4: nothing to sweep
+                    write_item(dst, 0, 0, 0, -1, 0, 0, 0, 0);
+                    continue;
+                }
+                const int rest = by_tp.div(k), tau = k - rest * tiles_p;
                 const int g = by_pc.div(rest), pc = rest - g * n_pc;
+                const int cs = 2 * pc * ps, ce = min(run, 2 * (pc + 1) * ps);
+                const int g_team = g | (team << 16) | ((team ? (tau & (team - 1)) : 0) << 20);   // KV head, team size, rank in the team
+                if (tau >= tiles_r) {                  // no rows of its own: a team member that only fetches
+                    write_item(dst, ld, g_team, 0, -1, cs, ce, 0, ce * kBlock);
+                    continue;
+                }
                 const int rows = tau == tiles_r - 1 ? last_rows : full_rows;
                 const int seg_pbase = v.g.rbase[gi] + n_pc * (g * rows_per_head + tau * full_rows);
-                const int cs = 2 * pc * ps, ce = min(run, 2 * (pc + 1) * ps);
-                write_item(&items[v.g.ibase[gi] + k], ld, g, rows, u.c.moff[ld] + tau * a.mpt, cs, ce,
-                           seg_pbase + pc * rows, ce * kBlock);
+                write_item(dst, ld, g_team, rows, u.c.moff[ld] + tau * a.mpt, cs, ce, seg_pbase + pc * rows, ce * kBlock);
                 if (pc == 0) {
                     SegDesc sd;
                     sd.pbase = seg_pbase;

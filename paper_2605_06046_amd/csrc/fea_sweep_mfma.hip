@@ -1,8 +1,9 @@
 // KV sweep on the matrix cores: bf16 caches, head_dim 128, query groups of up to
 // 16 heads per KV head (any ratio: 7 as in 28/4, 5 as in 40/8, ...).
 //
-// One single-wave workgroup per SIMD; the planner has cut the stream of 32-token
-// tiles into equal shares, and wave w sweeps the consecutive work items of share w.
+// One wave per SIMD (workgroups of four waves, one workgroup per compute unit); the planner has
+// cut the stream of 32-token tiles into equal shares, and wave w sweeps the consecutive work
+// items of share w.
 // An item is a set of up to 64 query rows (one request's query group,
 // or a row tile of a prefix group: members x group heads stacked) x one KV head x
 // a range of table columns; the wave sweeps the range with an online softmax and
@@ -540,12 +541,80 @@ __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item,
     sm.q_ready = q_next;
 }
 
-__global__ __launch_bounds__(64) void sweep_mfma_kernel(SweepArgs a, int g_rcp, int xcd_aware) {
-    __shared__ __attribute__((aligned(1024))) char s_stage[kStages * kStageBytes];
-    __shared__ __attribute__((aligned(256))) int s_cols[3 * 64];
-    __shared__ __attribute__((aligned(256))) int s_desc[kDescWindow * 8];      // the next few item descriptors
-    __shared__ __attribute__((aligned(1024))) char s_q[kBlock * kD * 2];       // query rows of the next item
-    const int lane = threadIdx.x;
+// A piece of a shared run swept by a team of 2 or 4 waves of this workgroup, one row tile of up to 64
+// query rows per wave, every tile of the piece fetched once for the whole team: the hand-scheduled
+// sequences of fea_sweep_core.inc (see gen_sweep_core.py for what they do and why they are written
+// out by hand).  Same partial rows as sweep_item.  A sequence uses most of the wave's registers under
+// fixed names; the caller ends the wave right after it, so that nothing of the rest of the kernel
+// has to live across it.  `team_base`: LDS address of the team's ring (2 x team tiles of K, then of V).
+#include "fea_sweep_core.inc"
+__device__ __forceinline__ void sweep_team_core(const SweepArgs& a, const Item& item, int team, int rank, int g_rcp,
+                                                uint32_t team_base, uint32_t cols_base, int lane) {
+    // The per-lane inputs are worked out again from a copy of the lane number the compiler cannot
+    // see through: they must sit in the few registers the sequence leaves alone, and tying them to
+    // the values the rest of the kernel keeps for its whole life would push those into scratch.
+    asm volatile("" : "+v"(lane));
+    const int n = lane & 15, kg = lane >> 4;
+    const uint32_t k_off0 = (uint32_t)(n * 256 + ((kg ^ n) & 15) * 16);             // token row n, chunk kg (k-step 0)
+    const uint32_t v_off0 = (uint32_t)(4 * kg * 256 + ((n ^ (4 * kg)) & 15) * 16);  // token row 4 kg, chunk n
+    const uint32_t d_off0 = (uint32_t)(kg * 256 + ((n ^ kg) & 15) * 16);            // load 0 of a block: row kg
+    const int ntiles = (item.c1 - item.c0) >> 1;
+    const int* mlist = reinterpret_cast<const int*>(a.ws + a.lay.members) + item.mlist_off;
+    const int32_t* trow = a.bt + (size_t)item.who * a.stride;
+    // block ids of all the piece's columns (at most 128) into this wave's two column windows
+    dma4(sgpr(trow), (uint32_t)min(item.c0 + lane, item.c1 - 1) * 4u, sgpr(cols_base));
+    dma4(sgpr(trow), (uint32_t)min(item.c0 + 64 + lane, item.c1 - 1) * 4u, sgpr(cols_base + 256u));
+    // byte offset of this lane's part of query row 16 nt + n (rows past the end: the first row again)
+    uint32_t qoff[4];
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt) {
+        int row = nt * 16 + n;
+        row = row < item.nrows ? row : 0;
+        const int mem = (row * g_rcp) >> 16, hh = row - mem * a.G;
+        const int req = item.mlist_off < 0 ? item.who : mlist[mem];
+        qoff[nt] = (uint32_t)(((req * a.Hq + item.g * a.G + hh) * kD + kg * 8) * 2);
+    }
+    wait_vmcnt<0>();
+    // this wave's part of every tile: ranks of the lower half fetch K, of the upper half V; in a team of 4 one block each
+    const bool loads_v = rank >= team / 2;
+    const uint64_t own = reinterpret_cast<uint64_t>(loads_v ? a.v_cache : a.k_cache);
+    const uint32_t odd = team == 4 ? (uint32_t)(rank & 1) : 0u;
+    const uint32_t own_ring = sgpr((loads_v ? (uint32_t)(2 * team) * (2u * kBlkBytes) : 0u) + odd * kBlkBytes);
+    const uint32_t tabsel = sgpr(odd * 4u);
+    const uint64_t qbase = reinterpret_cast<uint64_t>(sgpr(a.q));
+    const uint64_t accbase = reinterpret_cast<uint64_t>(sgpr(a.ws + a.lay.acc + (size_t)item.pbase * (kD * sizeof(float))));
+    const uint64_t mlbase = reinterpret_cast<uint64_t>(sgpr(a.ws + a.lay.ml + (size_t)item.pbase * sizeof(float2)));
+    const uint32_t own_lo = sgpr((uint32_t)own), own_hi = sgpr((uint32_t)(own >> 32));
+    const uint32_t lane4 = (uint32_t)lane * 4u, dst0 = (uint32_t)n * (kD * 4u) + (uint32_t)kg * 128u;
+#define FEA_TEAM_CORE_OPERANDS                                                                                                  \
+    : [koff0] "v"(k_off0), [voff0] "v"(v_off0), [doff0] "v"(d_off0), [q0] "v"(qoff[0]), [q1] "v"(qoff[1]), [q2] "v"(qoff[2]),   \
+      [q3] "v"(qoff[3]), [lane4] "v"(lane4), [dst0] "v"(dst0), [nrow] "v"(n), [qbase] "s"(qbase), [accbase] "s"(accbase),       \
+      [mlbase] "s"(mlbase), [own_lo] "s"(own_lo), [own_hi] "s"(own_hi), [hkv] "s"(sgpr((uint32_t)a.Hkv)),                        \
+      [g] "s"(sgpr((uint32_t)item.g)), [ntiles] "s"(sgpr((uint32_t)ntiles)), [nrows] "s"(sgpr((uint32_t)item.nrows)),             \
+      [scale] "s"(__builtin_bit_cast(float, sgpr(__builtin_bit_cast(uint32_t, a.scale_log2)))), [team] "s"(sgpr(team_base)),     \
+      [tab] "s"(sgpr(cols_base)), [own_ring] "s"(own_ring), [tabsel] "s"(tabsel)                                                 \
+    : FEA_TEAM_CORE_CLOBBERS
+    if (team == 4) asm volatile(FEA_TEAM4_CORE_ASM : FEA_TEAM_CORE_OPERANDS);
+    else asm volatile(FEA_TEAM2_CORE_ASM : FEA_TEAM_CORE_OPERANDS);
+#undef FEA_TEAM_CORE_OPERANDS
+}
+
+constexpr int kWavesPerGroup = 4;   // one wave per SIMD of a compute unit: a workgroup fills the unit
+
+__global__ __launch_bounds__(64 * kWavesPerGroup) void sweep_mfma_kernel(SweepArgs a, int g_rcp, int xcd_aware) {
+    // Every wave sweeps a share of its own and owns a quarter of the workgroup's LDS; the waves of a
+    // workgroup never wait for one another on this path.  (They sit in one workgroup so that the row
+    // tiles of a shared run's piece, which read the same KV bytes, can share what is fetched.)
+    __shared__ __attribute__((aligned(1024))) char s_stage_all[kWavesPerGroup * kStages * kStageBytes];
+    __shared__ __attribute__((aligned(256))) int s_cols_all[kWavesPerGroup * 3 * 64];
+    __shared__ __attribute__((aligned(256))) int s_desc_all[kWavesPerGroup * kDescWindow * 8];     // the next few item descriptors
+    __shared__ __attribute__((aligned(1024))) char s_q_all[kWavesPerGroup * kBlock * kD * 2];      // query rows of the next item
+    const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int lane = threadIdx.x & 63;
+    char* s_stage = s_stage_all + wv * (kStages * kStageBytes);
+    int* s_cols = s_cols_all + wv * (3 * 64);
+    int* s_desc = s_desc_all + wv * (kDescWindow * 8);
+    char* s_q = s_q_all + wv * (kBlock * kD * 2);
     int* hdr = reinterpret_cast<int*>(a.ws);
     const Item* items = reinterpret_cast<const Item*>(a.ws + a.lay.items);
     const int n_items = hdr[H_ITEMS];
@@ -577,12 +646,16 @@ __global__ __launch_bounds__(64) void sweep_mfma_kernel(SweepArgs a, int g_rcp, 
         dma4(sgpr(items), (uint32_t)min(first * 8 + lane, n_items * 8 - 1) * 4u, desc_base);
         sm.seq += 1;
     };
+    int team = 0, rank = 0;   // of the descriptor read last: team size (0: a wave on its own) and rank of a shared run's piece
     auto read_desc = [&](int k) {
         const int4* p = reinterpret_cast<const int4*>(s_desc + k * 8);
         const int4 w0 = p[0], w1 = p[1];
         auto u = [](int v) { return __builtin_amdgcn_readfirstlane(v); };
         Item x;
-        x.who = u(w0.x); x.g = u(w0.y); x.nrows = u(w0.z); x.mlist_off = u(w0.w);
+        const int gt = u(w0.y);
+        team = (gt >> 16) & 15;
+        rank = (gt >> 20) & 15;
+        x.who = u(w0.x); x.g = gt & 0xFFFF; x.nrows = u(w0.z); x.mlist_off = u(w0.w);
         x.c0 = u(w1.x); x.c1 = u(w1.y); x.pbase = u(w1.z); x.tok_end = u(w1.w);
         return x;
     };
@@ -592,14 +665,16 @@ __global__ __launch_bounds__(64) void sweep_mfma_kernel(SweepArgs a, int g_rcp, 
     // consecutive shares of a shared run are its row tiles over the same KV bytes.
     // Put every 8 consecutive shares on one XCD so that those bytes are fetched into
     // one L2 once.  (Pure performance: any permutation is correct.)
-    int share = blockIdx.x;
-    if (xcd_aware && (gridDim.x & 63) == 0) {
+    int group = blockIdx.x;
+    if (xcd_aware && (gridDim.x & 15) == 0) {
         const int x = blockIdx.x & 7, k = blockIdx.x >> 3;
-        share = 8 * ((k >> 3) * 8 + x) + (k & 7);
+        group = 2 * ((k >> 1) * 8 + x) + (k & 1);
     }
+    int share = kWavesPerGroup * group + wv;
+    const int n_waves = kWavesPerGroup * (int)gridDim.x;
     const int n_shares = hdr[H_WAVES];
     const int* wave_first = reinterpret_cast<const int*>(a.ws + a.lay.wave_first);
-    for (; share < n_shares; share += gridDim.x) {
+    for (; share < n_shares; share += n_waves) {
         int it = __builtin_amdgcn_readfirstlane(wave_first[share]);
         const int it_end = min(n_items, __builtin_amdgcn_readfirstlane(wave_first[share + 1]));
         if (it >= it_end) continue;
@@ -617,6 +692,19 @@ __global__ __launch_bounds__(64) void sweep_mfma_kernel(SweepArgs a, int g_rcp, 
         fetch_desc(win_first, sm);
         wait_all(sm);
         Item item = read_desc(0);
+        // A piece of a shared run as this wave's only work, its row tiles on the neighbouring waves of this
+        // workgroup: the team sweeps it together if it qualifies (every member sees the same columns, so
+        // they all decide alike).  Members without rows of their own only take part in that.
+        if (a.fast_shared && team >= 2 && it + 1 == it_end && share + n_waves >= n_shares &&
+            ((item.c1 - item.c0) & 1) == 0 && item.c1 - item.c0 >= 8 && item.c1 - item.c0 <= 128 &&
+            item.tok_end == item.c1 * kBlock && (wv & (team - 1)) == rank) {
+            wait_lgkmcnt0();
+            const uint32_t ring = sgpr((uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)s_stage_all) +
+                                  (team == 2 ? (uint32_t)(wv >> 1) * (2u * kStages * kStageBytes) : 0u);
+            sweep_team_core(a, item, team, rank, g_rcp, ring, cols_base, lane);
+            __builtin_amdgcn_endpgm();   // (not `return`: control must not rejoin the loop, or the loop's values live across the sequence)
+        }
+        if (item.nrows == 0 && it + 1 == it_end) continue;   // a slot that only exists for a team (or a filler)
         for (;;) {
             const bool has_next = it + 1 < it_end;
             if (has_next && it + 1 - win_first == kDescWindow) {   // window used up: fetch the next one (drains the stream once)
@@ -639,7 +727,7 @@ __global__ __launch_bounds__(64) void sweep_mfma_kernel(SweepArgs a, int g_rcp, 
 void launch_sweep_mfma(const SweepArgs& a, int grid, const Launch& L) {
     const int g_rcp = (65536 + a.G - 1) / a.G;   // (row * g_rcp) >> 16 == row / G for the 64 rows of an item
     static const int xcd_aware = [] { const char* v = std::getenv("FEA_XCD_AWARE"); return v && *v ? std::atoi(v) : 1; }();
-    hipExtLaunchKernelGGL(sweep_mfma_kernel, dim3(grid), dim3(64), 0, static_cast<hipStream_t>(L.stream),
+    hipExtLaunchKernelGGL(sweep_mfma_kernel, dim3(grid / kWavesPerGroup), dim3(64 * kWavesPerGroup), 0, static_cast<hipStream_t>(L.stream),
                           static_cast<hipEvent_t>(L.ev_start), static_cast<hipEvent_t>(L.ev_stop), 0, a, g_rcp, xcd_aware);
 }
 

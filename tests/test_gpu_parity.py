@@ -560,3 +560,36 @@ def test_random_prefix_trees(seed):
     assert_close(out, want, dtype, what=f"tree {seed}")
     out2, _, _, info2 = run_workload(wl, run_kernel_min=-1)
     assert info2 == info and np.array_equal(out, out2)
+
+
+@pytest.mark.parametrize("B,Hq,Hkv", [(24, 32, 8), (32, 32, 8), (48, 32, 8), (64, 32, 8), (80, 32, 8), (20, 28, 4), (9, 64, 8)])
+@pytest.mark.parametrize("scores", ["plain", "rising", "falling"])
+def test_shared_runs_swept_by_teams_of_waves(B, Hq, Hkv, scores):
+    """Prefix groups of 2, 3, 4 and 5 row tiles of 64 query rows (a last row tile that is not full, teams with
+    a member that only fetches), whose shared run is swept by teams of waves, against the oracle - also with
+    keys arranged so that the scores rise steeply along the shared prefix (every tile outgrows the reference
+    exponent of its rows, which must then be raised and the sums rescaled) or fall (everything after the first
+    tiles underflows)."""
+    prefix = 2048
+    spec = W.Spec("teams", 61, "bf16", Hq, Hkv, 128, ((B, prefix),), (1, 90))
+    wl = W.generate(spec)
+    bt, lens = library_tables(wl)
+    if scores != "plain":
+        d = 128
+        k = W.bf16_bits_to_f32(wl.k_cache)
+        t = np.arange(prefix, dtype=np.float32)
+        ramp = (t if scores == "rising" else (prefix - 1 - t)) * np.float32(0.87) / np.float32(np.sqrt(d))
+        shared = bt[0, :prefix // 16]                                   # the prefix blocks, in token order
+        k[shared] = (k[shared].reshape(prefix // 16, Hkv, 16, d) * np.float32(0.05)
+                     + ramp.reshape(prefix // 16, 1, 16, 1))
+        wl.k_cache[:] = W.f32_to_bf16_bits(k)
+        q = W.bf16_bits_to_f32(wl.q) * np.float32(0.1) + np.float32(1.0)    # every query points along the ramp
+        wl.q[:] = W.f32_to_bf16_bits(q)
+    W.poison_dead_slots(wl, bt, lens)
+    s = wl.spec
+    out, info = run_hip(wl.q, wl.k_cache, wl.v_cache, bt, lens, s.num_q_heads, s.num_kv_heads, s.head_dim, s.dtype)
+    assert info["groups"] == 1 and info["grouped_requests"] == B and info["overflow"] == 0
+    want = oracle_for(wl, bt, lens)
+    assert_close(out, want, "bf16", what=f"teams B={B} {Hq}/{Hkv} {scores}")
+    if scores == "rising":
+        assert np.abs(want).max() > 0.5          # the softmax sits on the last prefix tokens: outputs are O(1)
