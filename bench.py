@@ -439,9 +439,12 @@ def main():
 
     if args.decode_loop > 0:
         os.makedirs(OUT_DIR, exist_ok=True)
-        res = decode_loop(args.decode_loop)
-        open(os.path.join(OUT_DIR, "decode_loop.json"), "w").write(json.dumps(res) + "\n")
-        log(json.dumps(res))
+        with open(os.path.join(OUT_DIR, "decode_loop.jsonl"), "w") as f:
+            for layers, every in ((None, 1), (None, 32), (1, 1), (1, 32)):
+                res = decode_loop(args.decode_loop, layers, every)
+                f.write(json.dumps(res) + "\n")
+                log(json.dumps(res))
+                torch.cuda.empty_cache()
     if args.scheduler and not args.suite:
         os.makedirs(OUT_DIR, exist_ok=True)
         with open(os.path.join(OUT_DIR, "scheduler.jsonl"), "w") as f:
@@ -558,10 +561,12 @@ def device_hashing(reps=50):
                "host_tokens_per_s": len(wl.tokens) / (host_us * 1e-6), "equal_to_host": same}
 
 
-def decode_loop(n_steps, layers=None):
+def decode_loop(n_steps, layers=None, replan_every=1):
     """A run of decode steps on the c2 batch: per step the host extends tables and lengths by one
     token, and every layer (a replica of the KV pool stands for a layer's cache) appends its new K/V
-    rows and attends; alias detection runs once per step and is shared by the layers."""
+    rows and attends; the plan of a step is shared by its layers, and made anew (alias detection and
+    work split) only every replan_every-th step: in between the first layer stretches the plan at hand
+    to the lengths of now."""
     import torch
     import paper_2605_06046_amd as fea
     spec = W.CONFIGS["c2"]
@@ -569,6 +574,7 @@ def decode_loop(n_steps, layers=None):
     L = c.R if layers is None else min(layers, c.R)
     p_plan = c.params
     p_reuse = fea.AttnParams(spec.num_q_heads, spec.num_kv_heads, spec.head_dim, p_plan.dtype, flags=fea.FEA_FLAG_REUSE_PLAN)
+    p_refresh = fea.AttnParams(spec.num_q_heads, spec.num_kv_heads, spec.head_dim, p_plan.dtype, flags=fea.FEA_FLAG_REFRESH_PLAN)
     g = torch.Generator(device="cuda"); g.manual_seed(5)
     shape_new = (c.B, spec.num_kv_heads, spec.head_dim)
     k_new = torch.randn(shape_new, generator=g, device="cuda").to(c.k.dtype)
@@ -591,6 +597,7 @@ def decode_loop(n_steps, layers=None):
     app_args = [(C.byref(p_plan), vp(k_new.data_ptr()), vp(v_new.data_ptr()), vp(c.k[l].data_ptr()), vp(c.v[l].data_ptr()),
                  vp(c.dbt.data_ptr()), bt.shape[1], vp(c.dl.data_ptr()), c.B, sp) for l in range(L)]
     att_args = [(C.byref(p_plan if l == 0 else p_reuse),) + c._args[l][1:] + (sp,) for l in range(L)]
+    att_refresh = (C.byref(p_refresh),) + c._args[0][1:] + (sp,)
     t_lens, t_bt = torch.from_numpy(lens), torch.from_numpy(bt)      # views of the host arrays the library updates
 
     def check(rc):
@@ -606,7 +613,7 @@ def decode_loop(n_steps, layers=None):
         pin_l[j].copy_(t_lens); c.dl.copy_(pin_l[j], non_blocking=True)
         for l in range(L):
             check(lib.fea_kv_append(*app_args[l]))
-            check(lib.fea_decode_attention(*att_args[l]))
+            check(lib.fea_decode_attention(*(att_refresh if l == 0 and j % replan_every else att_args[l])))
 
     for _ in range(5):
         step()
@@ -621,7 +628,7 @@ def decode_loop(n_steps, layers=None):
     wall = time.perf_counter() - t0
     ms = e0.elapsed_time(e1) / n_steps
     return {"workload": f"decode_loop_c2_{L}_layers", "B": c.B, "decode_steps": n_steps, "layers": L,
-            "ms_per_decode_step": ms, "us_per_layer": ms * 1e3 / L, "tokens_per_s_per_layer_call": c.B / (ms * 1e-3 / L),
+            "new_plan_every": replan_every, "ms_per_decode_step": ms, "us_per_layer": ms * 1e3 / L, "tokens_per_s_per_layer_call": c.B / (ms * 1e-3 / L),
             "tokens_per_s_model_of_these_layers": c.B / (ms * 1e-3), "host_wall_ms_per_step": wall * 1e3 / n_steps,
             "final_len_mean": float(lens.mean())}
 

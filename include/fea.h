@@ -53,6 +53,20 @@ extern "C" {
                                   step can be made on another stream while this step's
                                   attention runs (q, caches and out may be NULL)         */
 
+#define FEA_FLAG_REFRESH_PLAN 4 /* the workspace holds the plan of an earlier call on this batch
+                                  and since then the requests have only grown: lengths went
+                                  up (decode steps), table rows got new columns at their
+                                  ends, everything else is unchanged.  Alias detection is
+                                  skipped; the split of the work is kept and every request's
+                                  last piece is stretched to its length now (a few
+                                  microseconds instead of a new plan).  The balance of the
+                                  split drifts as the requests grow apart: plan anew every
+                                  few dozen steps.  A request that had no blocks of its own
+                                  when the plan was made (empty, or every block shared) and
+                                  has grown since has no piece to stretch: the call then
+                                  fills every output row with NaN and
+                                  fea_decode_plan_info reports overflow flag 2            */
+
 typedef struct fea_kv_pool fea_kv_pool;
 
 /* Shape of one attention call.  Query head h reads KV head h / (num_q_heads /
@@ -270,8 +284,8 @@ int32_t fea_decode_attention(const fea_attn_params* p,
  * (nothing in it has to start at zero - every call writes its plan before reading
  * it), and calls that overlap in time on one GPU - different streams, different
  * threads - race on it and give undefined results; order them on one stream.
- * FEA_FLAG_REUSE_PLAN and FEA_FLAG_PLAN_ONLY are refused (FEA_EINVAL): another
- * caller may have used the buffer in between.  Other errors as fea_decode_attention. */
+ * FEA_FLAG_REUSE_PLAN, FEA_FLAG_PLAN_ONLY and FEA_FLAG_REFRESH_PLAN are refused
+ * (FEA_EINVAL): another caller may have used the buffer in between.  Other errors as fea_decode_attention. */
 #define FEA_STATIC_WORKSPACE_BYTES (48u << 20)
 int32_t fea_decode_attention_static(const fea_attn_params* p,
                                     const void* q, const void* k_cache, const void* v_cache,
@@ -283,7 +297,8 @@ int32_t fea_decode_attention_static(const fea_attn_params* p,
  * (synchronises hip_stream; for tests, tuning and the benchmark's reporting).
  * info: HOST int32[8] = { work items, prefix groups, requests in groups,
  * blocks per work item, partial rows, shared-run blocks (sum over groups),
- * kernel variant (0 generic, 1 MFMA), overflow flag }. */
+ * kernel variant (0 generic, 1 MFMA), overflow flag (1: the plan did not fit
+ * its buffers, 2: FEA_FLAG_REFRESH_PLAN met a request it cannot stretch) }. */
 int32_t fea_decode_plan_info(const void* workspace /* DEVICE */, void* hip_stream,
                              int32_t* info /* HOST [8] */);
 

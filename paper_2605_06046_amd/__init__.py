@@ -6,7 +6,7 @@ merge - runs inside the library; this package only marshals arguments.  There is
 no fallback: if the library is not built, importing the binding functions fails.
 """
 from .fea import (  # noqa: F401
-    FEA_DTYPE_BF16, FEA_DTYPE_F32, FEA_FLAG_REUSE_PLAN, FEA_FLAG_PLAN_ONLY, FeaError, KVPool, AttnParams,
+    FEA_DTYPE_BF16, FEA_DTYPE_F32, FEA_FLAG_REUSE_PLAN, FEA_FLAG_PLAN_ONLY, FEA_FLAG_REFRESH_PLAN, FeaError, KVPool, AttnParams,
     fea_build_block_tables, fea_chunk_hashes, fea_decode_attention, fea_decode_plan_info,
     fea_decode_workspace_bytes, fea_kv_alloc, fea_kv_free, fea_kv_stats, fea_release,
     fea_validate_block_tables, fea_profile_enable, fea_profile_read, library_path, load_library,

@@ -76,9 +76,11 @@ static int32_t check_params(const fea_attn_params* p, const char* who) {
     if (!d_ok) return fail(FEA_EINVAL, "%s: head_dim=%d not supported for this dtype", who, d);
     if (!(p->scale >= 0.f) || !std::isfinite(p->scale)) return fail(FEA_EINVAL, "%s: scale must be finite and >= 0", who);
     if (p->split_blocks < 0 || p->max_group < 0) return fail(FEA_EINVAL, "%s: split_blocks and max_group must be >= 0", who);
-    if (p->flags & ~(FEA_FLAG_REUSE_PLAN | FEA_FLAG_PLAN_ONLY)) return fail(FEA_EINVAL, "%s: unknown flag bits 0x%x", who, p->flags);
-    if ((p->flags & FEA_FLAG_REUSE_PLAN) && (p->flags & FEA_FLAG_PLAN_ONLY))
-        return fail(FEA_EINVAL, "%s: FEA_FLAG_REUSE_PLAN and FEA_FLAG_PLAN_ONLY exclude each other", who);
+    if (p->flags & ~(FEA_FLAG_REUSE_PLAN | FEA_FLAG_PLAN_ONLY | FEA_FLAG_REFRESH_PLAN))
+        return fail(FEA_EINVAL, "%s: unknown flag bits 0x%x", who, p->flags);
+    const int plan_flags = p->flags & (FEA_FLAG_REUSE_PLAN | FEA_FLAG_PLAN_ONLY | FEA_FLAG_REFRESH_PLAN);
+    if (plan_flags & (plan_flags - 1))
+        return fail(FEA_EINVAL, "%s: FEA_FLAG_REUSE_PLAN, FEA_FLAG_PLAN_ONLY and FEA_FLAG_REFRESH_PLAN exclude one another", who);
     if (p->reserved) return fail(FEA_EINVAL, "%s: the reserved field must be 0", who);
     return FEA_OK;
 }
@@ -211,7 +213,7 @@ int32_t decode_impl(const fea_attn_params* p, const void* q, const void* k_cache
         g_prof_mask[slot] = mask;
         ++g_prof_calls;
     }
-    if (!(p->flags & FEA_FLAG_REUSE_PLAN)) {
+    if (!(p->flags & FEA_FLAG_REUSE_PLAN)) {   // a new plan, or the one in the workspace stretched to the lengths of now
         PlanArgs pa;
         std::memset(&pa, 0, sizeof pa);
         pa.bt = block_tables;
@@ -230,7 +232,8 @@ int32_t decode_impl(const fea_attn_params* p, const void* q, const void* k_cache
         pa.variant = r.variant;
         pa.pre = r.pre;
         pa.pre_grid = r.pre_grid;
-        launch_plan(pa, where[0]);
+        if (p->flags & FEA_FLAG_REFRESH_PLAN) launch_refresh(pa, where[0]);
+        else launch_plan(pa, where[0]);
     }
     if (plan_only) {
         const hipError_t e = hipGetLastError();

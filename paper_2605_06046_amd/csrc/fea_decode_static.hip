@@ -52,8 +52,8 @@ extern "C" int32_t fea_decode_attention_static(const fea_attn_params* p, const v
     size_t need = 0;
     const int32_t rc = decode_workspace_bytes(p, B, table_stride, &need, "fea_decode_attention_static");
     if (rc != FEA_OK) return rc;
-    if (p->flags & (FEA_FLAG_REUSE_PLAN | FEA_FLAG_PLAN_ONLY))
-        return fail(FEA_EINVAL, "fea_decode_attention_static: FEA_FLAG_REUSE_PLAN and FEA_FLAG_PLAN_ONLY need a workspace of the caller's "
+    if (p->flags & (FEA_FLAG_REUSE_PLAN | FEA_FLAG_PLAN_ONLY | FEA_FLAG_REFRESH_PLAN))
+        return fail(FEA_EINVAL, "fea_decode_attention_static: FEA_FLAG_REUSE_PLAN, FEA_FLAG_PLAN_ONLY and FEA_FLAG_REFRESH_PLAN need a workspace of the caller's "
                                 "(the built-in one is shared by every call on the GPU)");
     if (need > (size_t)FEA_STATIC_WORKSPACE_BYTES)
         return fail(FEA_ERANGE, "fea_decode_attention_static: this batch needs a workspace of %zu bytes, the built-in one has %zu; "

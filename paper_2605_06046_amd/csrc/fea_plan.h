@@ -13,6 +13,7 @@ constexpr int kPlanThreads = 1024;    // the planner is one workgroup
 constexpr int kGroupReqMax = 2048;    // requests with index >= this are never grouped
 constexpr int kHashSlots = 4096;      // LDS hash slots for leader finding (2x kGroupReqMax)
 constexpr int kTileRows = 64;         // query rows one MFMA work item carries at most
+constexpr int kOpenEnded = -2;        // Item::mlist_off of a request's last piece of its own columns
 
 // header words (int32) at the start of the workspace
 enum Hdr {
@@ -63,7 +64,8 @@ struct Item {          // one KV sweep: a row set x one KV head x a column range
     int32_t who;       // request whose table row is read (the group's leader for a shared run)
     int32_t g;         // KV head (bits 0-15); pieces of shared runs swept by a team of waves: team size (bits 16-19), rank (bits 20-23)
     int32_t nrows;     // query rows: (requests in the row set) x (group heads)
-    int32_t mlist_off; // the row set's request ids start at members[mlist_off]; -1: just `who`
+    int32_t mlist_off; // the row set's request ids start at members[mlist_off]; negative: just `who` (kOpenEnded: and
+                       // the piece ends where the request's history ends)
     int32_t c0, c1;    // table columns [c0, c1) of `who`'s row
     int32_t pbase;     // partial row of the item's first query row
     int32_t tok_end;   // tokens at positions >= tok_end are not attended to
@@ -130,6 +132,7 @@ struct Launch {
 };
 
 void launch_plan(const PlanArgs& a, const Launch& L);
+void launch_refresh(const PlanArgs& a, const Launch& L);
 void launch_sweep_generic(const SweepArgs& a, int dtype, int head_dim, int grid, const Launch& L);
 void launch_sweep_mfma(const SweepArgs& a, int grid, const Launch& L);
 void launch_merge(const SweepArgs& a, int dtype, int head_dim, bool by_rows, const Launch& L);

@@ -785,7 +785,8 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
             if (!overflow) {
                 for_pieces(((nb - c0) + 1) >> 1, k, rem, [&](int jb, int je, bool starts, int kk) {
                     const int cs = c0 + 2 * jb, ce = min(nb, c0 + 2 * je);
-                    write_item(&items[idx], i, g, a.G, -1, cs, ce, rows_sh + (idx - n_sh) * a.G, min(L, ce * kBlock));
+                    // (the piece that ends at the request's last column is marked: it grows with the request, see refresh_kernel)
+                    write_item(&items[idx], i, g, a.G, ce == nb ? kOpenEnded : -1, cs, ce, rows_sh + (idx - n_sh) * a.G, min(L, ce * kBlock));
                     if (starts) wave_first[n_sh + kk] = idx;
                     ++idx;
                 });
@@ -884,6 +885,39 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
         hdr[H_OVERFLOW] = overflow ? 1 : 0;
         hdr[H_WAVES] = n_shares;
     }
+}
+
+// A plan made for shorter histories: the requests have grown since (decode steps append tokens, tables got
+// new columns at their ends), nothing else changed.  The split of the work stays; the last piece of every
+// request's own columns is stretched to the request's length now.  (Lengths that shrank would leave the plan
+// wrong - attention over rows that no longer count - but never out of bounds: a piece keeps at least one tile.)
+__global__ __launch_bounds__(256) void refresh_kernel(PlanArgs a) {
+    const int* hdr = reinterpret_cast<const int*>(a.ws);
+    Item* items = reinterpret_cast<Item*>(a.ws + a.lay.items);
+    const int n_items = min(hdr[H_ITEMS], a.lay.max_items);
+    const int maxL = a.stride * kBlock;
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n_items; i += gridDim.x * blockDim.x) {
+        const int4 w0 = reinterpret_cast<const int4*>(&items[i])[0];
+        if (w0.w != kOpenEnded) continue;
+        const int who = w0.x;
+        if (who < 0 || who >= a.B) continue;
+        int4 w1 = reinterpret_cast<const int4*>(&items[i])[1];
+        const int L = max(0, min(a.seq_lens[who], maxL));
+        w1.y = max((L + kBlock - 1) / kBlock, w1.x + 1);      // c1
+        w1.w = max(L, w1.x * kBlock + 1);                     // tok_end
+        reinterpret_cast<int4*>(&items[i])[1] = w1;
+    }
+    // a request that had no columns of its own then (empty, or every block shared) has no piece to stretch
+    const ReqDesc* req = reinterpret_cast<const ReqDesc*>(a.ws + a.lay.req);
+    const SegDesc* segs = reinterpret_cast<const SegDesc*>(a.ws + a.lay.segs);
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < a.B; i += gridDim.x * blockDim.x)
+        if (segs[(size_t)i * a.Hkv].npieces == 0 && min(a.seq_lens[i], maxL) > req[i].L)
+            atomicOr(reinterpret_cast<int*>(a.ws) + H_OVERFLOW, 2);
+}
+
+void launch_refresh(const PlanArgs& a, const Launch& L) {
+    hipExtLaunchKernelGGL(refresh_kernel, dim3(32), dim3(256), 0, static_cast<hipStream_t>(L.stream),
+                          static_cast<hipEvent_t>(L.ev_start), static_cast<hipEvent_t>(L.ev_stop), 0, a);
 }
 
 void launch_plan(const PlanArgs& a, const Launch& L) {

@@ -11,6 +11,7 @@ FEA_DTYPE_F32 = 0
 FEA_DTYPE_BF16 = 1
 FEA_FLAG_REUSE_PLAN = 1
 FEA_FLAG_PLAN_ONLY = 2
+FEA_FLAG_REFRESH_PLAN = 4
 _CODES = {-1: "FEA_EINVAL", -2: "FEA_ENOMEM", -3: "FEA_ERANGE", -4: "FEA_EHIP"}
 
 _HERE = os.path.dirname(os.path.abspath(__file__))

@@ -128,6 +128,141 @@ def test_decode_loop_on_the_device(name):
     assert np.array_equal(back_v.view(np.uint8)[live], hv.view(np.uint8)[live])
 
 
+class _Loop:
+    """Device and host state of a decode loop on one batch: step() grows every request by one token
+    (tables and lengths on the host, K/V rows through the append kernel; the oracle's caches follow)."""
+
+    def __init__(self, spec, steps, seed=11):
+        import torch
+        import paper_2605_06046_amd as fea
+        from gpu_harness import to_device
+        self.fea, self.torch, self.to_device, self.spec = fea, torch, to_device, spec
+        wl = W.generate(spec)
+        nb_total = wl.num_blocks + (steps // 16 + 2) * spec.batch
+        self.pool = fea.fea_kv_alloc(nb_total, 16, wl.perm_seed)
+        self.width = wl.max_blocks_per_seq + steps // 16 + 2
+        self.bt, self.lens, _, _ = fea.fea_build_block_tables(self.pool, wl.tokens, wl.tok_offsets, self.width)
+
+        def grow(c):
+            out = np.zeros((nb_total,) + c.shape[1:], dtype=c.dtype)
+            out[:c.shape[0]] = c
+            return out
+        self.hk, self.hv = grow(wl.k_cache), grow(wl.v_cache)
+        W.poison_dead_slots(dataclass_replace(wl, k_cache=self.hk, v_cache=self.hv, num_blocks=nb_total), self.bt, self.lens)
+        self.dk, self.dv = to_device(self.hk), to_device(self.hv)
+        self.dtype = fea.FEA_DTYPE_BF16 if spec.dtype == "bf16" else fea.FEA_DTYPE_F32
+        self.p = self.params(0)
+        self.ws = torch.zeros(fea.fea_decode_workspace_bytes(self.p, spec.batch, self.width), dtype=torch.uint8, device="cuda")
+        self.rng = np.random.default_rng(seed)
+        self.sync_tables()
+
+    def params(self, flags):
+        s = self.spec
+        return self.fea.AttnParams(s.num_q_heads, s.num_kv_heads, s.head_dim, self.dtype, flags=flags)
+
+    def sync_tables(self):
+        self.dbt, self.dl = self.torch.from_numpy(self.bt).cuda(), self.torch.from_numpy(self.lens).cuda()
+
+    def draw(self, heads):
+        x = self.rng.standard_normal((self.spec.batch, heads, self.spec.head_dim), dtype=np.float32)
+        return W.f32_to_bf16_bits(x) if self.spec.dtype == "bf16" else x
+
+    def step(self):
+        self.fea.fea_kv_extend(self.pool, self.bt, self.lens)
+        kn, vn = self.draw(self.spec.num_kv_heads), self.draw(self.spec.num_kv_heads)
+        oappend.append(self.hk, self.hv, kn, vn, self.bt, self.lens)
+        self.sync_tables()
+        self.fea.fea_kv_append(self.p, self.to_device(kn), self.to_device(vn), self.dk, self.dv, self.dbt, self.dl)
+
+    def attend(self, flags):
+        """-> (query as drawn, device output) of one attention call with the given plan flags"""
+        qn = self.draw(self.spec.num_q_heads)
+        dq = self.to_device(qn)
+        out = self.torch.full_like(dq, float("nan"))
+        self.fea.fea_decode_attention(self.params(flags), dq, self.dk, self.dv, self.dbt, self.dl, out, self.ws)
+        self.torch.cuda.synchronize()
+        return qn, out
+
+    def oracle(self, qn):
+        from gpu_harness import values
+        return decode_attention(values(qn), values(self.hk), values(self.hv), self.bt, self.lens)
+
+
+LOOP_SPECS = {
+    "c2": lambda: W.scaled(W.CONFIGS["c2"], batch_div=8, len_div=8),
+    "c3": lambda: W.scaled(W.CONFIGS["c3"], batch_div=8, len_div=8),
+    "c5": lambda: W.scaled(W.CONFIGS["c5"], batch_div=16, len_div=4),
+    # 40 requests of one 2048-token prefix (row tiles swept by teams of waves), 3 more of another, 5 on their own,
+    # suffixes of 1..40 tokens: many requests cross a block boundary on every step
+    "teams_and_singles": lambda: W.Spec("loop_mix", 77, "bf16", 32, 8, 128, ((40, 2048), (3, 160), (1, 0), (1, 0), (1, 0), (1, 0), (1, 0)), (1, 40)),
+    "f32_generic": lambda: W.Spec("loop_f32", 78, "f32", 8, 2, 64, ((6, 96), (1, 0), (1, 0)), (1, 33)),
+}
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("name", list(LOOP_SPECS))
+def test_one_plan_stretched_over_many_decode_steps(name):
+    """FEA_FLAG_REFRESH_PLAN: the plan made at one decode step serves the following ones (every request one token
+    longer per step, new table columns where a block filled up) - alias detection and work split are kept, the last
+    piece of every request follows its length.  Every step attends; every third one, and each one after a new plan,
+    is set against the oracle; the refreshed plan keeps the items of the plan it came from."""
+    import paper_2605_06046_amd as fea
+    from gpu_harness import assert_close
+    steps = 40
+    lp = _Loop(LOOP_SPECS[name](), steps)
+    items = None
+    for step in range(steps):
+        lp.step()
+        fresh = step in (0, 26)
+        qn, out = lp.attend(0 if fresh else fea.FEA_FLAG_REFRESH_PLAN)
+        info = fea.fea_decode_plan_info(lp.ws)
+        assert info["overflow"] == 0
+        if fresh:
+            items = info["items"]
+        assert info["items"] == items
+        if fresh or step % 3 == 2 or step == steps - 1:
+            assert_close(out.float().cpu().numpy().astype(np.float64), lp.oracle(qn), lp.spec.dtype, what=f"{name} step {step}")
+    # the same plan used unrefreshed on the grown batch misses the new tokens: the refresh does change the result
+    if name != "c5":
+        qn, out_stale = lp.attend(fea.FEA_FLAG_REUSE_PLAN)
+        lp.step(); lp.step()
+        q2 = lp.draw(lp.spec.num_q_heads)
+        dq = lp.to_device(q2)
+        outs = []
+        for flags in (fea.FEA_FLAG_REUSE_PLAN, fea.FEA_FLAG_REFRESH_PLAN):
+            o = lp.torch.empty_like(dq)
+            fea.fea_decode_attention(lp.params(flags), dq, lp.dk, lp.dv, lp.dbt, lp.dl, o, lp.ws)
+            outs.append(o.float().cpu().numpy().astype(np.float64))
+        assert_close(outs[1], lp.oracle(q2), lp.spec.dtype, what=f"{name} after two more steps")
+        assert not np.allclose(outs[0], outs[1], rtol=0, atol=1e-6)
+
+
+@pytest.mark.gpu
+def test_refresh_reports_a_request_it_cannot_stretch():
+    """Requests whose every block is shared have no piece of their own to stretch: once they have grown, a refreshed
+    plan says so (overflow flag 2, NaN in every row) rather than leaving the new tokens out; a new plan is right."""
+    import paper_2605_06046_amd as fea
+    from gpu_harness import assert_close
+    lp = _Loop(W.Spec("allshared", 5, "bf16", 8, 2, 128, ((4, 64),), (0, 0)), 4)
+    qn, out = lp.attend(0)
+    assert fea.fea_decode_plan_info(lp.ws)["overflow"] == 0
+    assert_close(out.float().cpu().numpy().astype(np.float64), lp.oracle(qn), "bf16", what="all shared")
+    qn, out = lp.attend(fea.FEA_FLAG_REFRESH_PLAN)          # nothing has grown: still fine
+    assert fea.fea_decode_plan_info(lp.ws)["overflow"] == 0
+    assert_close(out.float().cpu().numpy().astype(np.float64), lp.oracle(qn), "bf16", what="all shared, refreshed")
+    lp.step()
+    qn, out = lp.attend(fea.FEA_FLAG_REFRESH_PLAN)
+    assert fea.fea_decode_plan_info(lp.ws)["overflow"] == 2
+    assert lp.torch.isnan(out.float()).all()
+    qn, out = lp.attend(0)
+    assert fea.fea_decode_plan_info(lp.ws)["overflow"] == 0
+    assert_close(out.float().cpu().numpy().astype(np.float64), lp.oracle(qn), "bf16", what="all shared, planned anew")
+    lp.step()
+    qn, out = lp.attend(fea.FEA_FLAG_REFRESH_PLAN)          # now every request has a block of its own
+    assert fea.fea_decode_plan_info(lp.ws)["overflow"] == 0
+    assert_close(out.float().cpu().numpy().astype(np.float64), lp.oracle(qn), "bf16", what="all shared, grown twice")
+
+
 def dataclass_replace(obj, **kw):
     import dataclasses
     return dataclasses.replace(obj, **kw)
