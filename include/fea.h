@@ -295,12 +295,13 @@ int32_t fea_decode_attention_static(const fea_attn_params* p,
 
 /* Summary of the plan the last fea_decode_attention call left in `workspace`
  * (synchronises hip_stream; for tests, tuning and the benchmark's reporting).
- * info: HOST int32[8] = { work items, prefix groups, requests in groups,
+ * info: HOST int32[9] = { work items, prefix groups, requests in groups,
  * blocks per work item, partial rows, shared-run blocks (sum over groups),
  * kernel variant (0 generic, 1 MFMA), overflow flag (1: the plan did not fit
- * its buffers, 2: FEA_FLAG_REFRESH_PLAN met a request it cannot stretch) }. */
+ * its buffers, 2: FEA_FLAG_REFRESH_PLAN met a request it cannot stretch), sweep waves that
+ * were given a share }. */
 int32_t fea_decode_plan_info(const void* workspace /* DEVICE */, void* hip_stream,
-                             int32_t* info /* HOST [8] */);
+                             int32_t* info /* HOST [9] */);
 
 /* ------------------------------------------------------------------------
  * One decode step's growth of the KV history (Section 2.1: every decode step

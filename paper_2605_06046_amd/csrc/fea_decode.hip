@@ -27,12 +27,13 @@ static int env_int(const char* name, int dflt) {
 // second thread sets) cannot switch kernels or move the workspace layout between the
 // sizing call and the attention call.  What tests need to steer is in fea_attn_params.
 struct Knobs {
-    int force_generic, sweep_grid, spare_waves, min_piece, min_run, w32, w64, no_fast_shared, w_team;
+    int force_generic, sweep_grid, spare_waves, min_piece, min_run, w32, w64, no_fast_shared, w_team, w_team2;
 };
 static const Knobs& knobs() {
     static const Knobs k = {env_int("FEA_FORCE_GENERIC", 0), env_int("FEA_SWEEP_GRID", 0), env_int("FEA_SPARE_WAVES", 16),
                             env_int("FEA_MIN_PIECE", 4),     env_int("FEA_MIN_RUN", 2),    env_int("FEA_W32", 20),
-                            env_int("FEA_W64", 24), env_int("FEA_NO_FAST_SHARED", 0), env_int("FEA_WTEAM", 12)};
+                            env_int("FEA_W64", 24), env_int("FEA_NO_FAST_SHARED", 0), env_int("FEA_WTEAM", 12),
+                            env_int("FEA_WTEAM2", 12)};
     return k;
 }
 
@@ -110,7 +111,7 @@ static int32_t resolve(const fea_attn_params* p, int32_t B, int32_t stride, Reso
     r.tune.min_piece = std::max(1, kn.min_piece);
     r.tune.min_run = std::max(1, kn.min_run);
     r.tune.weights = std::min(255, std::max(16, kn.w32)) | (std::min(255, std::max(16, kn.w64)) << 8) |
-                     (std::min(255, std::max(1, kn.w_team)) << 16);
+                     (std::min(255, std::max(1, kn.w_team)) << 16) | (std::min(127, std::max(1, kn.w_team2)) << 24);
     // Large tables: the rows are compared on many workgroups before the planner's one workgroup
     // takes over (a second launch, so only where the rows are long or many enough to pay for it).
     const int64_t groupable = std::min(B, kGroupReqMax);
@@ -338,6 +339,7 @@ int32_t fea_decode_plan_info(const void* workspace, void* hip_stream, int32_t* i
     info[5] = hdr[H_SHARED_BLOCKS];
     info[6] = hdr[H_VARIANT];
     info[7] = hdr[H_OVERFLOW];
+    info[8] = hdr[H_WAVES];
     return FEA_OK;
 }
 

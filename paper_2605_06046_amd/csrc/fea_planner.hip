@@ -391,8 +391,12 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
     // cost of one 32-token tile of a shared run per wave that sweeps it, for a group of cnt members: a team
     // fetches the tile once for all its row tiles and overlaps the two products, which makes the tile far
     // cheaper for a wave than a tile it streams and sweeps alone
-    const int w_team = (a.tune.weights >> 16) & 255;
-    auto group_weight = [&](int cnt) { return (teams && by_mpt.cdiv(cnt) >= 2) ? w_team : tile_weight(min(a.mpt, cnt) * a.G); };
+    // (a team of 2 fetches half of every tile per wave, a team of 4 a quarter: the tile costs the former more)
+    const int w_team = (a.tune.weights >> 16) & 255, w_team2 = (a.tune.weights >> 24) & 127;
+    auto group_weight = [&](int cnt) {
+        const int tiles_r = by_mpt.cdiv(cnt);
+        return (teams && tiles_r >= 2) ? (tiles_r == 2 ? w_team2 : w_team) : tile_weight(min(a.mpt, cnt) * a.G);
+    };
 
     // ---- nested prefixes.  Members of a group may go on sharing blocks past the group's
     // run (a common system prompt, then a few conversations: the radix patterns of
@@ -661,27 +665,68 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
         }
         const long long U = wsum(u_loc) + 16ll * T_pr, total_tiles = wsum(t_loc) + T_pr;
         const int n_act = (int)max(1ll, min((long long)a.tune.n_waves, ddiv(total_tiles, max(a.tune.min_piece, 1))));
-        // Cost per share: start from an even split and grow it until shared pieces plus
-        // private shares fit the waves (rounding pieces up to whole tiles and whole
-        // segments can push the count over; a wave with two shares would be the tail).
-        int Q = (int)min(1ll << 25, max(16ll, ddiv(U + n_act - 1, n_act)));
+        // Pieces of a group's run of T_seg tiles when a share may cost Q; a team's piece has at most 64 tiles
+        // (the team's window of block ids holds 128 columns).
+        auto pieces = [&](int cnt, int T_seg, int Q) {
+            int want = fixed_tiles > 0 ? fixed_tiles : max(1, idiv(Q, group_weight(cnt)));
+            if (teams && by_mpt.cdiv(cnt) >= 2) want = min(want, 64);
+            return idiv(T_seg + want - 1, want);
+        };
+        // shares of the private stream at cost Q per share, and their tiles
+        auto own_shares = [&](int Q, int& q) {
+            const int n_pr = max(1, (int)ddiv(16ll * T_pr + Q - 1, Q));
+            q = max(1, idiv(T_pr + n_pr - 1, n_pr));
+            return idiv(T_pr + q - 1, q);
+        };
+        int Q = (int)min(1ll << 25, max(16ll, ddiv(U + n_act - 1, n_act)));   // the even split
         int q = 1, n_sh = 0;
+        bool searched = false;
+        if (fixed_tiles == 0 && n_groups > 0 && n_groups <= 32) {
+            // Shares are whole tiles and pieces whole fractions of a run, so the even split rarely fits the waves,
+            // and which cost near it does is a matter of rounding.  Every lane tries one cost for the shared
+            // pieces, from 3/4 of the even split to 7/4 of it; the waves the pieces leave over share the private
+            // stream; the lane whose longest share (shared piece or private share) costs least wins.
+            const int Qc = Q - (Q >> 2) + (int)(((long long)Q * lane) >> 6);
+            int slots = 0, longest = 0;
+            for (int gi = 0; gi < n_groups; ++gi) {
+                const int ld = w.glist[gi], cnt = u.c.cnt[ld], T_seg = (u.c.run[ld] + 1) >> 1;
+                const int n_pc = pieces(cnt, T_seg, Qc);
+                slots += items_padded(Hkv * tiles_padded(by_mpt.cdiv(cnt)) * n_pc);
+                longest = max(longest, ((T_seg + n_pc - 1) / n_pc) * group_weight(cnt));
+            }
+            int qq = 0;
+            if (T_pr > 0) {
+                const int n_own = min(n_act - slots, (T_pr + a.tune.min_piece - 1) / max(a.tune.min_piece, 1));
+                qq = n_own >= 1 ? (T_pr + n_own - 1) / n_own : -1;
+                if (qq > (1 << 26)) qq = -1;
+            }
+            const bool fits = slots <= n_act && qq >= 0;
+            int cost = fits ? max(longest, 16 * qq) : 0x7FFFFFFF;
+            int who = lane;
+            for (int o = 1; o < 64; o <<= 1) {     // least cost; among equals the largest Qc (fewest pieces)
+                const int c2 = __shfl_xor(cost, o), w2 = __shfl_xor(who, o);
+                if (c2 < cost || (c2 == cost && w2 > who)) { cost = c2; who = w2; }
+            }
+            if (cost != 0x7FFFFFFF) {
+                Q = __shfl(Qc, who);
+                q = max(1, __shfl(qq, who));
+                searched = true;
+            }
+        }
+        // Otherwise (very many groups, or nothing fitted): start from the even split and grow the cost until
+        // shared pieces plus private shares fit the waves (a wave with two shares would be the tail).
         for (int round = 0; round < 4; ++round) {
             int loc = 0;
             for (int gi = lane; gi < n_groups; gi += 64) {
                 int ld, cnt, run;
                 group(gi, ld, cnt, run);
-                const int T_seg = (run + 1) >> 1;
-                const int want = fixed_tiles > 0 ? fixed_tiles : max(1, idiv(Q, group_weight(cnt)));
-                const int n_pc = idiv(T_seg + want - 1, want);
+                const int n_pc = pieces(cnt, (run + 1) >> 1, Q);
                 v.g.npc[gi] = n_pc;
                 loc += items_padded(Hkv * tiles_padded(by_mpt.cdiv(cnt)) * n_pc);
             }
             n_sh = (int)wsum(loc);
-            if (fixed_tiles > 0) break;
-            const int n_pr = max(1, (int)ddiv(16ll * T_pr + Q - 1, Q));
-            q = max(1, idiv(T_pr + n_pr - 1, n_pr));
-            const int shares = n_sh + idiv(T_pr + q - 1, q);
+            if (fixed_tiles > 0 || searched) break;
+            const int shares = n_sh + own_shares(Q, q);
             if (shares <= n_act) break;
             Q = (int)min(1ll << 25, ddiv((long long)Q * shares + n_act - 1, n_act) + 1);
         }

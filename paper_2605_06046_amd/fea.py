@@ -292,10 +292,10 @@ def fea_chunk_hashes_device(tokens, tok_offsets, hash_offsets, hashes, stream=No
 def fea_decode_plan_info(workspace, stream=None) -> dict:
     import torch
     st = stream if stream is not None else torch.cuda.current_stream()
-    info = np.zeros(8, dtype=np.int32)
+    info = np.zeros(9, dtype=np.int32)
     _check(load_library().fea_decode_plan_info(_dev_ptr(workspace), C.c_void_p(st.cuda_stream), _np_ptr(info)))
     keys = ("items", "groups", "grouped_requests", "split_blocks", "partial_rows", "shared_blocks",
-            "variant", "overflow")
+            "variant", "overflow", "shares")
     return dict(zip(keys, (int(x) for x in info)))
 
 
