@@ -34,11 +34,11 @@ GIB_KIB = 1 << 20   # a 1 GiB copy moves this many KiB each way
 
 
 def kernel_rev(root: str) -> str:
-    """Identifies the sweep kernel's code: its source file.  The counters of a summary stay valid for
+    """Identifies the sweep kernel's code: its source files.  The counters of a summary stay valid for
     a build whose sweep source is the same and whose plan for the workload (stored next to them) is the
     same, since the kernel then does the same loads and stores."""
     h = hashlib.sha256()
-    for name in ("fea_sweep_mfma.hip", "fea_plan.h"):
+    for name in ("fea_sweep_mfma.hip", "fea_sweep_core.inc", "fea_plan.h"):
         h.update(open(os.path.join(root, "paper_2605_06046_amd", "csrc", name), "rb").read())
     return h.hexdigest()[:12]
 
