@@ -233,7 +233,9 @@ __global__ __launch_bounds__(256) void merge_kernel(SweepArgs a) {
     if (rowid >= a.B * a.Hq) return;
     const int i = rowid / a.Hq, h = rowid - i * a.Hq;
     const int g = h / a.G, hh = h - g * a.G;
-    const ReqDesc rd = reinterpret_cast<const ReqDesc*>(a.ws + a.lay.req)[i];
+    // (the first four words of the request's descriptor, taken as values: a reference to the whole struct would put it on the stack)
+    const int4 rd4 = *reinterpret_cast<const int4*>(a.ws + a.lay.req + (size_t)i * sizeof(ReqDesc));
+    const int rd_ns_sh = rd4.x, rd_sh_base0 = rd4.y, rd_sh_gstride = rd4.z, rd_sh_pstride = rd4.w;
     const SegDesc pd = reinterpret_cast<const SegDesc*>(a.ws + a.lay.segs)[(size_t)i * a.Hkv + g];
     const float2* ml = reinterpret_cast<const float2*>(a.ws + a.lay.ml);
     const float* pacc = reinterpret_cast<const float*>(a.ws + a.lay.acc);
@@ -244,9 +246,9 @@ __global__ __launch_bounds__(256) void merge_kernel(SweepArgs a) {
         for (int e = lane; e < D; e += 64) Elem<T>::store(out + e, __uint_as_float(0x7FC00000u));
         return;
     }
-    const int ns_sh = rd.ns_sh, ns = ns_sh + pd.npieces;
-    const int sh_base = rd.sh_base0 + g * rd.sh_gstride + hh, pr_base = pd.pbase + hh;
-    auto prow = [&](int s) { return s < ns_sh ? sh_base + s * rd.sh_pstride : pr_base + (s - ns_sh) * a.G; };
+    const int ns_sh = rd_ns_sh, ns = ns_sh + pd.npieces;
+    const int sh_base = rd_sh_base0 + g * rd_sh_gstride + hh, pr_base = pd.pbase + hh;
+    auto prow = [&](int s) { return s < ns_sh ? sh_base + s * rd_sh_pstride : pr_base + (s - ns_sh) * a.G; };
 
     // Each lane group walks its partials kInFlight at a time: their (m, l) pairs and
     // accumulator rows are requested together, so a row with up to kInFlight * SLOTS
@@ -332,7 +334,9 @@ __global__ __launch_bounds__(256) void merge_rows_kernel(SweepArgs a) {
     if (rowid >= a.B * a.Hq) return;     // nothing below crosses lane groups
     const int i = rowid / a.Hq, h = rowid - i * a.Hq;
     const int g = h / a.G, hh = h - g * a.G;
-    const ReqDesc rd = reinterpret_cast<const ReqDesc*>(a.ws + a.lay.req)[i];
+    // (the first four words of the request's descriptor, taken as values: a reference to the whole struct would put it on the stack)
+    const int4 rd4 = *reinterpret_cast<const int4*>(a.ws + a.lay.req + (size_t)i * sizeof(ReqDesc));
+    const int rd_ns_sh = rd4.x, rd_sh_base0 = rd4.y, rd_sh_gstride = rd4.z, rd_sh_pstride = rd4.w;
     const SegDesc pd = reinterpret_cast<const SegDesc*>(a.ws + a.lay.segs)[(size_t)i * a.Hkv + g];
     const float2* ml = reinterpret_cast<const float2*>(a.ws + a.lay.ml);
     const float* pacc = reinterpret_cast<const float*>(a.ws + a.lay.acc);
@@ -341,9 +345,9 @@ __global__ __launch_bounds__(256) void merge_rows_kernel(SweepArgs a) {
         for (int e = c; e < D; e += LPR) Elem<T>::store(out + e, __uint_as_float(0x7FC00000u));
         return;
     }
-    const int ns_sh = rd.ns_sh, ns = ns_sh + pd.npieces;
-    const int sh_base = rd.sh_base0 + g * rd.sh_gstride + hh, pr_base = pd.pbase + hh;
-    auto prow = [&](int s) { return s < ns_sh ? sh_base + s * rd.sh_pstride : pr_base + (s - ns_sh) * a.G; };
+    const int ns_sh = rd_ns_sh, ns = ns_sh + pd.npieces;
+    const int sh_base = rd_sh_base0 + g * rd_sh_gstride + hh, pr_base = pd.pbase + hh;
+    auto prow = [&](int s) { return s < ns_sh ? sh_base + s * rd_sh_pstride : pr_base + (s - ns_sh) * a.G; };
     constexpr int kInFlight = 4;
     float num[8];
 #pragma unroll
