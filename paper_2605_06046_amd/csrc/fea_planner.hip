@@ -665,11 +665,9 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
         }
         const long long U = wsum(u_loc) + 16ll * T_pr, total_tiles = wsum(t_loc) + T_pr;
         const int n_act = (int)max(1ll, min((long long)a.tune.n_waves, ddiv(total_tiles, max(a.tune.min_piece, 1))));
-        // Pieces of a group's run of T_seg tiles when a share may cost Q; a team's piece has at most 64 tiles
-        // (the team's window of block ids holds 128 columns).
+        // Pieces of a group's run of T_seg tiles when a share may cost Q.
         auto pieces = [&](int cnt, int T_seg, int Q) {
-            int want = fixed_tiles > 0 ? fixed_tiles : max(1, idiv(Q, group_weight(cnt)));
-            if (teams && by_mpt.cdiv(cnt) >= 2) want = min(want, 64);
+            const int want = fixed_tiles > 0 ? fixed_tiles : max(1, idiv(Q, group_weight(cnt)));
             return idiv(T_seg + want - 1, want);
         };
         // shares of the private stream at cost Q per share, and their tiles

@@ -548,8 +548,9 @@ __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item,
 // fixed names; the caller ends the wave right after it, so that nothing of the rest of the kernel
 // has to live across it.  `team_base`: LDS address of the team's ring (2 x team tiles of K, then of V).
 #include "fea_sweep_core.inc"
+constexpr int kTeamCols = 1024;   // columns of a piece a team can sweep: their block ids fill the wave's query buffer (4 KB)
 __device__ __forceinline__ void sweep_team_core(const SweepArgs& a, const Item& item, int team, int rank, int g_rcp,
-                                                uint32_t team_base, uint32_t cols_base, int lane) {
+                                                uint32_t team_base, uint32_t tab_base, int lane) {
     // The per-lane inputs are worked out again from a copy of the lane number the compiler cannot
     // see through: they must sit in the few registers the sequence leaves alone, and tying them to
     // the values the rest of the kernel keeps for its whole life would push those into scratch.
@@ -561,9 +562,10 @@ __device__ __forceinline__ void sweep_team_core(const SweepArgs& a, const Item& 
     const int ntiles = (item.c1 - item.c0) >> 1;
     const int* mlist = reinterpret_cast<const int*>(a.ws + a.lay.members) + item.mlist_off;
     const int32_t* trow = a.bt + (size_t)item.who * a.stride;
-    // block ids of all the piece's columns (at most 128) into this wave's two column windows
-    dma4(sgpr(trow), (uint32_t)min(item.c0 + lane, item.c1 - 1) * 4u, sgpr(cols_base));
-    dma4(sgpr(trow), (uint32_t)min(item.c0 + 64 + lane, item.c1 - 1) * 4u, sgpr(cols_base + 256u));
+    // block ids of all the piece's columns (at most kTeamCols), 64 per load, into this wave's query buffer
+    // (not needed here: the sequence keeps the query rows in registers)
+    for (int w = 0; w * 64 < item.c1 - item.c0; ++w)
+        dma4(sgpr(trow), (uint32_t)min(item.c0 + 64 * w + lane, item.c1 - 1) * 4u, sgpr(tab_base + 256u * (uint32_t)w));
     // byte offset of this lane's part of query row 16 nt + n (rows past the end: the first row again)
     uint32_t qoff[4];
 #pragma unroll
@@ -592,7 +594,7 @@ __device__ __forceinline__ void sweep_team_core(const SweepArgs& a, const Item& 
       [mlbase] "s"(mlbase), [own_lo] "s"(own_lo), [own_hi] "s"(own_hi), [hkv] "s"(sgpr((uint32_t)a.Hkv)),                        \
       [g] "s"(sgpr((uint32_t)item.g)), [ntiles] "s"(sgpr((uint32_t)ntiles)), [nrows] "s"(sgpr((uint32_t)item.nrows)),             \
       [scale] "s"(__builtin_bit_cast(float, sgpr(__builtin_bit_cast(uint32_t, a.scale_log2)))), [team] "s"(sgpr(team_base)),     \
-      [tab] "s"(sgpr(cols_base)), [own_ring] "s"(own_ring), [tabsel] "s"(tabsel)                                                 \
+      [tab] "s"(sgpr(tab_base)), [own_ring] "s"(own_ring), [tabsel] "s"(tabsel)                                                   \
     : FEA_TEAM_CORE_CLOBBERS
     if (team == 4) asm volatile(FEA_TEAM4_CORE_ASM : FEA_TEAM_CORE_OPERANDS);
     else asm volatile(FEA_TEAM2_CORE_ASM : FEA_TEAM_CORE_OPERANDS);
@@ -696,12 +698,12 @@ __global__ __launch_bounds__(64 * kWavesPerGroup) void sweep_mfma_kernel(SweepAr
         // workgroup: the team sweeps it together if it qualifies (every member sees the same columns, so
         // they all decide alike).  Members without rows of their own only take part in that.
         if (a.fast_shared && team >= 2 && it + 1 == it_end && share + n_waves >= n_shares &&
-            ((item.c1 - item.c0) & 1) == 0 && item.c1 - item.c0 >= 8 && item.c1 - item.c0 <= 128 &&
+            ((item.c1 - item.c0) & 1) == 0 && item.c1 - item.c0 >= 8 && item.c1 - item.c0 <= kTeamCols &&
             item.tok_end == item.c1 * kBlock && (wv & (team - 1)) == rank) {
             wait_lgkmcnt0();
             const uint32_t ring = sgpr((uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)s_stage_all) +
                                   (team == 2 ? (uint32_t)(wv >> 1) * (2u * kStages * kStageBytes) : 0u);
-            sweep_team_core(a, item, team, rank, g_rcp, ring, cols_base, lane);
+            sweep_team_core(a, item, team, rank, g_rcp, ring, q_base, lane);
             __builtin_amdgcn_endpgm();   // (not `return`: control must not rejoin the loop, or the loop's values live across the sequence)
         }
         if (item.nrows == 0 && it + 1 == it_end) continue;   // a slot that only exists for a team (or a filler)

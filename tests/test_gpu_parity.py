@@ -593,3 +593,21 @@ def test_shared_runs_swept_by_teams_of_waves(B, Hq, Hkv, scores):
     assert_close(out, want, "bf16", what=f"teams B={B} {Hq}/{Hkv} {scores}")
     if scores == "rising":
         assert np.abs(want).max() > 0.5          # the softmax sits on the last prefix tokens: outputs are O(1)
+
+
+def test_long_pieces_of_a_shared_run_swept_by_teams():
+    """200 requests on a 16 384-token prefix: 13 row tiles per KV head take most of the waves, so the run is cut
+    into few pieces of more than 128 columns each (the teams' block-id table holds up to 1024); sampled requests
+    against the oracle, all rows finite."""
+    spec = W.Spec("teams_long", 62, "bf16", 32, 8, 128, ((200, 16384),), (1, 70))
+    wl = W.generate(spec)
+    bt, lens = library_tables(wl)
+    W.poison_dead_slots(wl, bt, lens)
+    s = wl.spec
+    out, info = run_hip(wl.q, wl.k_cache, wl.v_cache, bt, lens, s.num_q_heads, s.num_kv_heads, s.head_dim, s.dtype)
+    assert info["groups"] == 1 and info["grouped_requests"] == 200 and info["overflow"] == 0
+    assert info["items"] < 16 * 8 * 8 + 200 * 8 + 64        # at most 7 pieces of the 512-tile run: more than 64 tiles each
+    assert np.isfinite(out).all()
+    sample = [0, 1, 63, 64, 127, 128, 192, 199]
+    want = oracle_for(wl, bt, lens, requests=sample)
+    assert_close(out[sample], want[sample], "bf16", what="teams, pieces of more than 128 columns")
