@@ -14,6 +14,8 @@
 #include <hip/hip_runtime.h>
 #include <hip/hip_ext.h>
 
+#include <type_traits>
+
 #include "../../include/fea.h"
 #include "fea_plan.h"
 
@@ -66,18 +68,27 @@ template <> struct Elem<bf16_t> {
 constexpr int kGenThreads = 256;
 constexpr int kGenWaves = kGenThreads / 64;
 constexpr int kPiece = 256;   // tokens whose scores are staged at once
-constexpr int kHB = 4;        // query heads handled per pass over the KV range
 
-template <typename T, int D>
+// Query rows handled per pass over an item's tokens: the item's rows are its members' query heads stacked
+// (member-major), so a pass over a shared run serves several members at once (Section 3: the run is read
+// once for all who attend to it - here once per pass, and the passes after the first hit L2).  Two
+// instantiations: 4 rows per pass (few registers, four workgroups per compute unit: what a batch that
+// fills the chip wants, being bound by memory latency) and WIDE = 16 rows (8 for 16-bit caches, fewer for
+// head_dim 256) for batches too small to fill it, where the number of passes is all that counts.
+template <typename T, int D> constexpr int gen_rows_wide() {
+    return (sizeof(T) == 4 ? 16 : 8) > 2048 / D ? 2048 / D : (sizeof(T) == 4 ? 16 : 8);
+}
+
+template <typename T, int D, int HB>
 __global__ __launch_bounds__(kGenThreads) void sweep_generic_kernel(SweepArgs a) {
     constexpr int EPL = Elem<T>::kPerLoad;
     constexpr int LPT = D / EPL;          // lanes that share one token row
     constexpr int TPW = 64 / LPT;         // token rows per wave-wide load
     static_assert(LPT >= 1 && LPT <= 64 && (LPT & (LPT - 1)) == 0, "head_dim not supported");
 
-    __shared__ float s_sc[kHB][kPiece];
-    __shared__ float s_alpha[kHB], s_m[kHB], s_l[kHB];
-    __shared__ float s_red[kGenWaves][kHB][D];
+    __shared__ float s_sc[HB][kPiece];
+    __shared__ float s_alpha[HB], s_m[HB], s_l[HB];
+    __shared__ float s_red[kGenWaves][HB][D];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int c = lane % LPT, r = lane / LPT;
@@ -94,32 +105,35 @@ __global__ __launch_bounds__(kGenThreads) void sweep_generic_kernel(SweepArgs a)
         const Item item = items[it];
         const int32_t* row = a.bt + (size_t)item.who * a.stride;
         const int t_begin = item.c0 * kBlock, t_end = item.tok_end;
-        // query rows of the item: one request, or the members of a group's row tile
-        // (the vector path simply sweeps the shared run once per member)
-        const int n_mem = item.nrows / a.G;
+        // query rows of the item: one request's query group, or those of the members of a group's row tile
         const int* mlist = reinterpret_cast<const int*>(a.ws + a.lay.members) + item.mlist_off;
-        for (int mh = 0; mh < n_mem * ((a.G + kHB - 1) / kHB); ++mh) {
-            const int mem = mh / ((a.G + kHB - 1) / kHB);
-            const int hb = (mh % ((a.G + kHB - 1) / kHB)) * kHB;
-            const int qreq = item.mlist_off < 0 ? item.who : mlist[mem];
-            const int prow0 = item.pbase + mem * a.G + hb;
-            const int nh = min(kHB, a.G - hb);
-            float qf[kHB][EPL];
+        // one pass over the item's tokens for rows row0 .. row0 + RB - 1 (RB: a compile-time bound, so that the
+        // rows' registers are arrays the compiler can keep in registers)
+        auto pass = [&](auto rb_tag, int row0) {
+            constexpr int RB = decltype(rb_tag)::value;
+            const int prow0 = item.pbase + row0;
+            const int nh = min(RB, item.nrows - row0);
+            float qf[RB][EPL];
 #pragma unroll
-            for (int j = 0; j < kHB; ++j) {
+            for (int j = 0; j < RB; ++j) {
                 if (j < nh) {
-                    Elem<T>::load(Q + ((size_t)qreq * a.Hq + item.g * a.G + hb + j) * D + c * EPL, qf[j]);
+                    const int ra = row0 + j, mem = ra / a.G, hh = ra - mem * a.G;
+                    const int qreq = item.mlist_off < 0 ? item.who : mlist[mem];
+                    Elem<T>::load(Q + ((size_t)qreq * a.Hq + item.g * a.G + hh) * D + c * EPL, qf[j]);
                 } else {
 #pragma unroll
                     for (int e = 0; e < EPL; ++e) qf[j][e] = 0.f;
                 }
             }
-            float acc[kHB][EPL];
+            float acc[RB][EPL];
 #pragma unroll
-            for (int j = 0; j < kHB; ++j)
+            for (int j = 0; j < RB; ++j)
 #pragma unroll
                 for (int e = 0; e < EPL; ++e) acc[j][e] = 0.f;
-            float m_run = -INFINITY, l_run = 0.f;   // meaningful in wave j for head j
+            constexpr int RPW = (RB + kGenWaves - 1) / kGenWaves;   // rows whose softmax state one wave keeps
+            float m_run[RPW], l_run[RPW];   // of rows wave, wave + kGenWaves, ...
+#pragma unroll
+            for (int k = 0; k < RPW; ++k) { m_run[k] = -INFINITY; l_run[k] = 0.f; }
 
             for (int p0 = t_begin; p0 < t_end; p0 += kPiece) {
                 const int np = min(kPiece, t_end - p0);
@@ -129,9 +143,9 @@ __global__ __launch_bounds__(kGenThreads) void sweep_generic_kernel(SweepArgs a)
                     const int blk = max(row[t / kBlock], 0);   // a -1 inside a request's length (the caller's error) must not become a read before the cache
                     float kf[EPL];
                     Elem<T>::load(K + (((size_t)blk * a.Hkv + item.g) * kBlock + (t % kBlock)) * D + c * EPL, kf);
-                    float dot[kHB];
+                    float dot[RB];
 #pragma unroll
-                    for (int j = 0; j < kHB; ++j) {
+                    for (int j = 0; j < RB; ++j) {
                         float s = 0.f;
 #pragma unroll
                         for (int e = 0; e < EPL; ++e) s = fmaf(qf[j][e], kf[e], s);
@@ -140,39 +154,42 @@ __global__ __launch_bounds__(kGenThreads) void sweep_generic_kernel(SweepArgs a)
 #pragma unroll
                     for (int o = LPT / 2; o >= 1; o >>= 1)
 #pragma unroll
-                        for (int j = 0; j < kHB; ++j) dot[j] += __shfl_xor(dot[j], o);
+                        for (int j = 0; j < RB; ++j) dot[j] += __shfl_xor(dot[j], o);
                     if (c == 0) {
 #pragma unroll
-                        for (int j = 0; j < kHB; ++j) s_sc[j][tt] = dot[j] * a.scale_log2;
+                        for (int j = 0; j < RB; ++j) s_sc[j][tt] = dot[j] * a.scale_log2;
                     }
                 }
                 __syncthreads();
-                // softmax bookkeeping: wave j owns head j
-                if (wave < kHB) {
-                    const int j = wave;
-                    float mx = -INFINITY;
-                    for (int tt = lane; tt < np; tt += 64) mx = fmaxf(mx, s_sc[j][tt]);
+                // softmax bookkeeping: wave w owns rows w, w + kGenWaves, ...
 #pragma unroll
-                    for (int o = 32; o >= 1; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
-                    const float m_new = fmaxf(m_run, mx);
-                    float sum = 0.f;
-                    for (int tt = lane; tt < np; tt += 64) {
-                        const float p = exp2f(s_sc[j][tt] - m_new);
-                        s_sc[j][tt] = p;
-                        sum += p;
+                for (int k = 0; k < RPW; ++k) {
+                    const int j = wave + k * kGenWaves;
+                    if (j < nh) {
+                        float mx = -INFINITY;
+                        for (int tt = lane; tt < np; tt += 64) mx = fmaxf(mx, s_sc[j][tt]);
+#pragma unroll
+                        for (int o = 32; o >= 1; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+                        const float m_new = fmaxf(m_run[k], mx);
+                        float sum = 0.f;
+                        for (int tt = lane; tt < np; tt += 64) {
+                            const float p = exp2f(s_sc[j][tt] - m_new);
+                            s_sc[j][tt] = p;
+                            sum += p;
+                        }
+#pragma unroll
+                        for (int o = 32; o >= 1; o >>= 1) sum += __shfl_xor(sum, o);
+                        const float alpha = exp2f(m_run[k] - m_new);   // 0 on the first piece
+                        l_run[k] = l_run[k] * alpha + sum;
+                        m_run[k] = m_new;
+                        if (lane == 0) { s_alpha[j] = alpha; s_m[j] = m_new; s_l[j] = l_run[k]; }
                     }
-#pragma unroll
-                    for (int o = 32; o >= 1; o >>= 1) sum += __shfl_xor(sum, o);
-                    const float alpha = exp2f(m_run - m_new);   // 0 on the first piece
-                    l_run = l_run * alpha + sum;
-                    m_run = m_new;
-                    if (lane == 0) { s_alpha[j] = alpha; s_m[j] = m_run; s_l[j] = l_run; }
                 }
                 __syncthreads();
                 // values
 #pragma unroll
-                for (int j = 0; j < kHB; ++j) {
-                    const float al = s_alpha[j];
+                for (int j = 0; j < RB; ++j) {
+                    const float al = j < nh ? s_alpha[j] : 0.f;
 #pragma unroll
                     for (int e = 0; e < EPL; ++e) acc[j][e] *= al;
                 }
@@ -182,10 +199,12 @@ __global__ __launch_bounds__(kGenThreads) void sweep_generic_kernel(SweepArgs a)
                     float vf[EPL];
                     Elem<T>::load(V + (((size_t)blk * a.Hkv + item.g) * kBlock + (t % kBlock)) * D + c * EPL, vf);
 #pragma unroll
-                    for (int j = 0; j < kHB; ++j) {
-                        const float p = s_sc[j][tt];
+                    for (int j = 0; j < RB; ++j) {
+                        if (j < nh) {
+                            const float p = s_sc[j][tt];
 #pragma unroll
-                        for (int e = 0; e < EPL; ++e) acc[j][e] = fmaf(p, vf[e], acc[j][e]);
+                            for (int e = 0; e < EPL; ++e) acc[j][e] = fmaf(p, vf[e], acc[j][e]);
+                        }
                     }
                 }
                 __syncthreads();
@@ -194,12 +213,12 @@ __global__ __launch_bounds__(kGenThreads) void sweep_generic_kernel(SweepArgs a)
 #pragma unroll
             for (int o = LPT; o < 64; o <<= 1)
 #pragma unroll
-                for (int j = 0; j < kHB; ++j)
+                for (int j = 0; j < RB; ++j)
 #pragma unroll
                     for (int e = 0; e < EPL; ++e) acc[j][e] += __shfl_xor(acc[j][e], o);
             if (r == 0) {
 #pragma unroll
-                for (int j = 0; j < kHB; ++j)
+                for (int j = 0; j < RB; ++j)
 #pragma unroll
                     for (int e = 0; e < EPL; ++e) s_red[wave][j][c * EPL + e] = acc[j][e];
             }
@@ -213,6 +232,11 @@ __global__ __launch_bounds__(kGenThreads) void sweep_generic_kernel(SweepArgs a)
             }
             if (tid < nh) ml[prow0 + tid] = make_float2(s_m[tid], s_l[tid]);
             __syncthreads();
+        };
+        if (HB > 4 && item.nrows <= 4) {
+            pass(std::integral_constant<int, 4>{}, 0);      // a request's own columns with a query group of up to 4 heads
+        } else {
+            for (int row0 = 0; row0 < item.nrows; row0 += HB) pass(std::integral_constant<int, HB>{}, row0);
         }
     }
 }
@@ -396,15 +420,24 @@ __global__ __launch_bounds__(256) void merge_rows_kernel(SweepArgs a) {
     Elem<T>::store8(out + c * 8, num);
 }
 
-template <typename T>
-static void launch_generic_t(const SweepArgs& a, int head_dim, int grid, const Launch& L) {
+template <typename T, int D>
+static void launch_generic_d(const SweepArgs& a, int grid, bool wide, const Launch& L) {
     hipStream_t st = static_cast<hipStream_t>(L.stream);
     hipEvent_t e0 = static_cast<hipEvent_t>(L.ev_start), e1 = static_cast<hipEvent_t>(L.ev_stop);
+    if (wide) hipExtLaunchKernelGGL((sweep_generic_kernel<T, D, gen_rows_wide<T, D>()>), dim3(grid), dim3(kGenThreads), 0, st, e0, e1, 0, a);
+    else hipExtLaunchKernelGGL((sweep_generic_kernel<T, D, 4>), dim3(grid), dim3(kGenThreads), 0, st, e0, e1, 0, a);
+}
+
+template <typename T>
+static void launch_generic_t(const SweepArgs& a, int head_dim, int grid, const Launch& L) {
+    // a batch whose items cannot fill the grid: fewer, wider passes (an item per (request, KV head) and per
+    // 8 columns is a generous estimate of what the planner makes)
+    const bool wide = (int64_t)a.B * a.Hkv * (1 + a.stride / 8) <= grid;
     switch (head_dim) {
-        case 32: hipExtLaunchKernelGGL((sweep_generic_kernel<T, 32>), dim3(grid), dim3(kGenThreads), 0, st, e0, e1, 0, a); break;
-        case 64: hipExtLaunchKernelGGL((sweep_generic_kernel<T, 64>), dim3(grid), dim3(kGenThreads), 0, st, e0, e1, 0, a); break;
-        case 128: hipExtLaunchKernelGGL((sweep_generic_kernel<T, 128>), dim3(grid), dim3(kGenThreads), 0, st, e0, e1, 0, a); break;
-        case 256: hipExtLaunchKernelGGL((sweep_generic_kernel<T, 256>), dim3(grid), dim3(kGenThreads), 0, st, e0, e1, 0, a); break;
+        case 32: launch_generic_d<T, 32>(a, grid, wide, L); break;
+        case 64: launch_generic_d<T, 64>(a, grid, wide, L); break;
+        case 128: launch_generic_d<T, 128>(a, grid, wide, L); break;
+        case 256: launch_generic_d<T, 256>(a, grid, wide, L); break;
         default: break;
     }
 }

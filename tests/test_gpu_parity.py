@@ -134,6 +134,20 @@ def test_other_shapes(dtype, Hq, Hkv, d):
     assert_close(out, oracle_for(wl, bt, lens), dtype, what=f"{dtype} {Hq}/{Hkv}/{d}")
 
 
+@pytest.mark.parametrize("dtype,Hq,Hkv,d", [("f32", 8, 4, 64), ("f32", 6, 2, 128), ("bf16", 14, 2, 64), ("bf16", 8, 4, 256),
+                                            ("f32", 4, 4, 32)])
+def test_vector_sweep_on_batches_that_fill_the_chip(dtype, Hq, Hkv, d):
+    """The vector sweep has two instantiations: wide passes (up to 16 stacked query rows) for batches too small to
+    fill the chip - every other small case here - and passes of 4 rows for the rest.  These batches are big enough
+    for the second: two prefix groups (one of them wider than a row tile) and requests on their own."""
+    B = 2048 // Hkv // 8 + 40
+    spec = W.Spec("vec_big", 12, dtype, Hq, Hkv, d, ((B // 2, 256), (B // 4, 96), (B - B // 2 - B // 4, 0)), (150, 800))
+    wl = W.generate(spec)
+    out, bt, lens, info = run_workload(wl)
+    assert B * Hkv * (1 + bt.shape[1] // 8) > 2048 and info["variant"] == 0 and info["groups"] == 2
+    assert_close(out, oracle_for(wl, bt, lens), dtype, what=f"vector sweep {dtype} {Hq}/{Hkv}/{d}")
+
+
 @pytest.mark.parametrize("name", ["c1", "c2"])
 def test_grouping_off_split_sizes_scale_and_determinism(name):
     spec = W.CONFIGS[name] if name == "c1" else W.scaled(W.CONFIGS[name], **SMALL[name])
