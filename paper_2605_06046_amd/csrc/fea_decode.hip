@@ -95,7 +95,7 @@ static int32_t resolve(const fea_attn_params* p, int32_t B, int32_t stride, Reso
         return fail(FEA_EINVAL, "%s: problem too large (B * num_kv_heads * table_stride / 2 exceeds 2^30 tiles)", who);
     const Knobs& kn = knobs();
     r.G = p->num_q_heads / p->num_kv_heads;
-    const bool mfma_ok = p->dtype == FEA_DTYPE_BF16 && p->head_dim == 128 && r.G <= 16;
+    const bool mfma_ok = p->dtype == FEA_DTYPE_BF16 && (p->head_dim == 128 || p->head_dim == 64) && r.G <= 16;
     r.variant = (mfma_ok && !kn.force_generic) ? 1 : 0;
     r.mpt = r.G >= kTileRows ? 1 : kTileRows / r.G;
     r.grouping = p->max_group == 1 ? 0 : 1;
@@ -231,6 +231,7 @@ int32_t decode_impl(const fea_attn_params* p, const void* q, const void* k_cache
         pa.grouping = r.grouping;
         pa.split_user = r.split_user;
         pa.variant = r.variant;
+        pa.teams = (r.variant == 1 && p->head_dim == 128 && !knobs().no_fast_shared) ? 1 : 0;
         pa.pre = r.pre;
         pa.pre_grid = r.pre_grid;
         if (p->flags & FEA_FLAG_REFRESH_PLAN) launch_refresh(pa, where[0]);
@@ -258,8 +259,8 @@ int32_t decode_impl(const fea_attn_params* p, const void* q, const void* k_cache
     sa.Hkv = p->num_kv_heads;
     sa.G = r.G;
     sa.mpt = r.mpt;
-    sa.fast_shared = ((int64_t)B * p->num_q_heads < (1 << 23) && !knobs().no_fast_shared) ? 1 : 0;
-    if (r.variant == 1) launch_sweep_mfma(sa, r.grid, where[1]);
+    sa.fast_shared = (p->head_dim == 128 && (int64_t)B * p->num_q_heads < (1 << 23) && !knobs().no_fast_shared) ? 1 : 0;
+    if (r.variant == 1) launch_sweep_mfma(sa, p->head_dim, r.grid, where[1]);
     else launch_sweep_generic(sa, p->dtype, p->head_dim, r.grid, where[1]);
     launch_merge(sa, p->dtype, p->head_dim, r.merge_by_rows != 0, where[2]);
     const hipError_t e = hipGetLastError();

@@ -98,6 +98,7 @@ struct PlanArgs {
     int32_t grouping;    // 0: every request on its own
     int32_t split_user;  // 0: choose
     int32_t variant;
+    int32_t teams;       // the sweep runs the row tiles of a shared run's piece as a team of waves (MFMA sweep, head_dim 128)
     int32_t pre;         // leaders and common runs come from run_kernel (workspace section `pre`)
     int32_t pre_grid;    // its grid
 };
@@ -135,7 +136,7 @@ struct Launch {
 void launch_plan(const PlanArgs& a, const Launch& L);
 void launch_refresh(const PlanArgs& a, const Launch& L);
 void launch_sweep_generic(const SweepArgs& a, int dtype, int head_dim, int grid, const Launch& L);
-void launch_sweep_mfma(const SweepArgs& a, int grid, const Launch& L);
+void launch_sweep_mfma(const SweepArgs& a, int head_dim, int grid, const Launch& L);
 void launch_merge(const SweepArgs& a, int dtype, int head_dim, bool by_rows, const Launch& L);
 
 }  // namespace fea

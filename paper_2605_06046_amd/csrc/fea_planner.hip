@@ -385,7 +385,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
     // runs them as a team of 2 or 4 waves of one workgroup that fetches every tile once; for that the
     // row tiles of a piece sit on neighbouring shares, in slots of 1, 2 or a multiple of 4 (the slots
     // past the last row tile hold waves that only help fetching), and every group starts on a multiple of 4.
-    const bool teams = a.variant == 1 && a.split_user == 0;   // (with a fixed split a share holds several items: no teams)
+    const bool teams = a.teams != 0 && a.split_user == 0;   // (with a fixed split a share holds several items: no teams)
     auto tiles_padded = [&](int tiles_r) { return (!teams || tiles_r <= 2) ? tiles_r : ((tiles_r + 3) & ~3); };
     auto items_padded = [&](int n) { return teams ? ((n + 3) & ~3) : n; };
     // cost of one 32-token tile of a shared run per wave that sweeps it, for a group of cnt members: a team

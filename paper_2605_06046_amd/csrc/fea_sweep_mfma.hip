@@ -1,5 +1,9 @@
-// KV sweep on the matrix cores: bf16 caches, head_dim 128, query groups of up to
-// 16 heads per KV head (any ratio: 7 as in 28/4, 5 as in 40/8, ...).
+// KV sweep on the matrix cores: bf16 caches, head_dim 128 or 64, query groups of up to
+// 16 heads per KV head (any ratio: 7 as in 28/4, 5 as in 40/8, ...).  What follows
+// describes head_dim 128; head_dim 64 is the same kernel with 2 KB blocks (two loads
+// each, 128-byte token rows of eight chunks, swizzled by the row modulo 8), two
+// k-steps in the first product and four output products per 16 rows, lanes n and n+8
+// sharing a V chunk and taking its lower and upper four dims.
 //
 // One wave per SIMD (workgroups of four waves, one workgroup per compute unit); the planner has
 // cut the stream of 32-token tiles into equal shares, and wave w sweeps the consecutive work
@@ -94,6 +98,15 @@ __device__ __forceinline__ void dma16x4(const char* base, uint32_t off0, uint32_
         :: "v"(off0), "v"(off1), "v"(off2), "v"(off3), "s"(base), "s"(lds0), "s"(lds1), "s"(lds2), "s"(lds3)
         : "memory", "m0");
 }
+// Two such loads (a 2 KB block of head_dim 64).
+__device__ __forceinline__ void dma16x2(const char* base, uint32_t off0, uint32_t off1, uint32_t lds0, uint32_t lds1) {
+    asm volatile(
+        "s_nop 4\n\t"
+        "s_mov_b32 m0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %2\n\t"
+        "s_mov_b32 m0, %4\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+        :: "v"(off0), "v"(off1), "s"(base), "s"(lds0), "s"(lds1)
+        : "memory", "m0");
+}
 // One load of 4 bytes per lane (block ids of 64 table columns), same conventions.
 __device__ __forceinline__ void dma4(const void* base, uint32_t lane_off, uint32_t lds_addr) {
     asm volatile("s_nop 4\n\ts_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
@@ -145,9 +158,11 @@ struct Lanes {
 };
 
 // Fetch blocks b0, b1 of KV head g into the stage at LDS address `stage` (16 loads).
+template <int D>
 __device__ __forceinline__ void fetch_tile(const SweepArgs& a, int g, int b0, int b1, uint32_t stage, const Lanes& L) {
-    const size_t o0 = ((size_t)b0 * a.Hkv + g) * kBlkBytes;
-    const size_t o1 = ((size_t)b1 * a.Hkv + g) * kBlkBytes;
+    constexpr int BLK = kBlock * D * 2;
+    const size_t o0 = ((size_t)b0 * a.Hkv + g) * BLK;
+    const size_t o1 = ((size_t)b1 * a.Hkv + g) * BLK;
     const char* k0 = sgpr(static_cast<const char*>(a.k_cache) + o0);
     const char* k1 = sgpr(static_cast<const char*>(a.k_cache) + o1);
     const char* v0 = sgpr(static_cast<const char*>(a.v_cache) + o0);
@@ -156,8 +171,9 @@ __device__ __forceinline__ void fetch_tile(const SweepArgs& a, int g, int b0, in
     const char* bases[4] = {k0, k1, v0, v1};
 #pragma unroll
     for (int x = 0; x < 4; ++x) {
-        const uint32_t l = stage + x * kBlkBytes;
-        dma16x4(bases[x], L.dma_off[0], L.dma_off[1], L.dma_off[2], L.dma_off[3], l, l + 1024, l + 2048, l + 3072);
+        const uint32_t l = stage + x * BLK;
+        if constexpr (D == 128) dma16x4(bases[x], L.dma_off[0], L.dma_off[1], L.dma_off[2], L.dma_off[3], l, l + 1024, l + 2048, l + 3072);
+        else dma16x2(bases[x], L.dma_off[0], L.dma_off[1], l, l + 1024);
     }
 }
 
@@ -213,10 +229,14 @@ __device__ __forceinline__ void wait_all(Stream& sm) {
     sm.done = sm.seq;
 }
 
-template <int NT>
+template <int NT, int D>
 __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item, const Item& next, bool has_next,
                                            int g_rcp, char* s_stage, const int* s_cols, const char* s_q, uint32_t lds_base,
                                            uint32_t cols_base, uint32_t q_base, const Lanes& L, int lane, Stream& sm) {
+    constexpr int BLK = kBlock * D * 2;      // bytes of one (block, KV head)
+    constexpr int STG = 4 * BLK;             // K b0 | K b1 | V b0 | V b1
+    constexpr int KS = D / 32;               // k-steps of S^T = K Q^T
+    constexpr int NI = D / 16;               // products of O^T += V^T P^T per 16 query rows
     const int n = L.n, kg = L.kg;
     const uint16_t* Q = static_cast<const uint16_t*>(a.q);
     const int* mlist = reinterpret_cast<const int*>(a.ws + a.lay.members) + item.mlist_off;
@@ -261,8 +281,8 @@ __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item,
         const int b0 = max(__builtin_amdgcn_readfirstlane(sc[0]), 0);
         const int b1 = max(__builtin_amdgcn_readfirstlane(sc[1]), 0);
         const int stg = (sm.phase + idx) & 1;
-        fetch_tile(a, g, b0, b1, lds_base + stg * kStageBytes, L);
-        sm.seq += 16;
+        fetch_tile<D>(a, g, b0, b1, lds_base + stg * STG, L);
+        sm.seq += D / 8;
         sm.tmark0 = stg == 0 ? sm.seq : sm.tmark0;
         sm.tmark1 = stg == 1 ? sm.seq : sm.tmark1;
         sm.iss = idx + 1;
@@ -282,13 +302,13 @@ __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item,
     // that is younger than that.  Otherwise (first item of a share, rows gathered
     // through a member list, more than 16 rows) they are loaded here and everything
     // in flight is drained once.
-    bf16x8 qB[NT][4];
+    bf16x8 qB[NT][KS];
     bool q_from_lds = false;
     if constexpr (NT == 1) q_from_lds = sm.q_ready;
     if (q_from_lds) {
         wait_for(sm, sm.qmark);
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) qB[0][ks] = as_bf16x8(ld16(s_q + L.k_off[ks]));
+        for (int ks = 0; ks < KS; ++ks) qB[0][ks] = as_bf16x8(ld16(s_q + L.k_off[ks]));
     } else {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
@@ -296,9 +316,9 @@ __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item,
             const bool ok = row < item.nrows;
             const int mem = (row * g_rcp) >> 16, hh = row - mem * a.G;   // row / G and row % G (rows < 64, G <= 16)
             const int req = ok ? (item.mlist_off < 0 ? item.who : mlist[mem]) : 0;
-            const uint16_t* qp = Q + ((size_t)req * a.Hq + item.g * a.G + hh) * kD + kg * 8;
+            const uint16_t* qp = Q + ((size_t)req * a.Hq + item.g * a.G + hh) * D + kg * 8;
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
+            for (int ks = 0; ks < KS; ++ks) {
                 u32x4 v = {0u, 0u, 0u, 0u};
                 if (ok) v = ld16(qp + ks * 32);
                 qB[nt][ks] = as_bf16x8(v);
@@ -310,22 +330,33 @@ __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item,
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) asm volatile("" : "+v"(qB[nt][ks]));
+            for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qB[nt][ks]));
     }
     // Bring in the next item's query rows if they are one contiguous run of at most 16.
     const bool q_next = has_next && next.nrows <= 16 && next.mlist_off < 0;
     if (q_next) {
         wait_lgkmcnt0();   // the buffer has been read out
-        const char* qn = reinterpret_cast<const char*>(Q + ((size_t)next.who * a.Hq + next.g * a.G) * kD);
-        uint32_t off[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int row = 4 * j + kg;                          // row of the buffer this lane fills in load j
-            off[j] = (uint32_t)min(row, next.nrows - 1) * 256u + (uint32_t)((n ^ row) & 15) * 16u;   // rows past the end repeat the last one
-        }
+        const char* qn = reinterpret_cast<const char*>(Q + ((size_t)next.who * a.Hq + next.g * a.G) * D);
         const uint32_t qb = sgpr(q_base);
-        dma16x4(sgpr(qn), off[0], off[1], off[2], off[3], qb, qb + 1024, qb + 2048, qb + 3072);
-        sm.seq += 4;
+        if constexpr (D == 128) {
+            uint32_t off[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int row = 4 * j + kg;                          // row of the buffer this lane fills in load j
+                off[j] = (uint32_t)min(row, next.nrows - 1) * 256u + (uint32_t)((n ^ row) & 15) * 16u;   // rows past the end repeat the last one
+            }
+            dma16x4(sgpr(qn), off[0], off[1], off[2], off[3], qb, qb + 1024, qb + 2048, qb + 3072);
+            sm.seq += 4;
+        } else {
+            uint32_t off[2];
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int row = 8 * j + (lane >> 3), pos = lane & 7;   // 128-byte rows: eight per load
+                off[j] = (uint32_t)min(row, next.nrows - 1) * 128u + (uint32_t)((pos ^ row) & 7) * 16u;
+            }
+            dma16x2(sgpr(qn), off[0], off[1], qb, qb + 1024);
+            sm.seq += 2;
+        }
         sm.qmark = sm.seq;
     }
 
@@ -334,7 +365,7 @@ __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item,
     // rounded weights as the numerator (so numerator and denominator stay consistent).
     u32x4 ones_bits = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
     const bf16x8 ones = as_bf16x8(ones_bits);
-    f32x4 oacc[NT][8];
+    f32x4 oacc[NT][NI];
     f32x4 lacc[NT];
     float m_run[NT];
 #pragma unroll
@@ -342,7 +373,7 @@ __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item,
         m_run[nt] = -INFINITY;
         lacc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int i = 0; i < 8; ++i) oacc[nt][i] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int i = 0; i < NI; ++i) oacc[nt][i] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
     // One tile in two halves.  front(t): wait for the tile, read it out of its stage
@@ -354,7 +385,7 @@ __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item,
     float tmax[NT];    // scaled maximum of those, positions past the end left out
     int tile_pos = 0;  // position of the tile's first token
     bool ragged = false;   // the tile reaches past the item's last token (wave-uniform)
-    bf16x8 vA[8];      // vA[i]: head dim 8*(lane%16) + i, k-slots = the lane group's 8 tokens
+    bf16x8 vA[NI];     // vA[i]: head dim 8*(lane%16) + i (head_dim 64: lanes n >= 8 carry dim 8*(n-8) + i + 4), k-slots = the lane group's 8 tokens
     auto scores = [&](int nt, float (&r)[8]) {   // this lane's 8 scores of row tile nt; -inf past the end
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt)
@@ -370,21 +401,21 @@ __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item,
     };
     auto front = [&](int t) {
         const int stg = (sm.phase + t) & 1;
-        const char* st = s_stage + stg * kStageBytes;
+        const char* st = s_stage + stg * STG;
         wait_for(sm, stg == 0 ? sm.tmark0 : sm.tmark1);   // tile t has landed
         // Read the tile out of its stage and hand the stage back.  With 16 or 32 query
         // rows everything is read up front so that the refill starts at once; with 64
         // rows registers are short, so V is read after the first product (that
         // instantiation computes long enough per tile for the later refill not to matter).
-        bf16x8 kA[2][4];
+        bf16x8 kA[2][KS];
         u32x4 vr[8];
 #pragma unroll
         for (int mt = 0; mt < (NT < 4 ? 2 : 1); ++mt)
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) kA[mt][ks] = as_bf16x8(ld16(st + mt * kBlkBytes + L.k_off[ks]));
+            for (int ks = 0; ks < KS; ++ks) kA[mt][ks] = as_bf16x8(ld16(st + mt * BLK + L.k_off[ks]));
         if constexpr (NT < 4) {
 #pragma unroll
-            for (int j = 0; j < 8; ++j) vr[j] = ld16(st + (2 + (j >> 2)) * kBlkBytes + L.v_off[j & 3]);
+            for (int j = 0; j < 8; ++j) vr[j] = ld16(st + (2 + (j >> 2)) * BLK + L.v_off[j & 3]);
             wait_lgkmcnt0();   // the stage is read out: refill it with stream tile t+2
             issue(t + 1);      // (only due if the look-ahead into the next item stopped short)
             issue(t + 2);
@@ -401,18 +432,18 @@ __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item,
             if constexpr (NT == 4) {
                 if (mt == 1) {
 #pragma unroll
-                    for (int ks = 0; ks < 4; ++ks) kA[1][ks] = as_bf16x8(ld16(st + kBlkBytes + L.k_off[ks]));
+                    for (int ks = 0; ks < KS; ++ks) kA[1][ks] = as_bf16x8(ld16(st + BLK + L.k_off[ks]));
                 }
             }
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks)
+            for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt)
                     sacc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kA[mt][ks], qB[nt][ks], sacc[nt][mt], 0, 0, 0);
         }
         if constexpr (NT == 4) {
 #pragma unroll
-            for (int j = 0; j < 8; ++j) vr[j] = ld16(st + (2 + (j >> 2)) * kBlkBytes + L.v_off[j & 3]);
+            for (int j = 0; j < 8; ++j) vr[j] = ld16(st + (2 + (j >> 2)) * BLK + L.v_off[j & 3]);
             wait_lgkmcnt0();
             issue(t + 1);
             issue(t + 2);
@@ -426,13 +457,31 @@ __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item,
                 if (pos >= item.tok_end) vr[j] = u32x4{0u, 0u, 0u, 0u};
             }
         }
+        if constexpr (D == 128) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
-            u32x4 o;
+            for (int i = 0; i < 8; ++i) {
+                const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
+                u32x4 o;
 #pragma unroll
-            for (int w = 0; w < 4; ++w) o[w] = __builtin_amdgcn_perm(vr[2 * w + 1][i >> 1], vr[2 * w][i >> 1], sel);
-            vA[i] = as_bf16x8(o);
+                for (int w = 0; w < 4; ++w) o[w] = __builtin_amdgcn_perm(vr[2 * w + 1][i >> 1], vr[2 * w][i >> 1], sel);
+                vA[i] = as_bf16x8(o);
+            }
+        } else {
+            // a token row has 8 chunks: lanes n and n + 8 read the same one; lane n < 8 hands elements 0..3 of it
+            // to products 0..3 (dims 8 n + i), lane n >= 8 elements 4..7 (dims 8 (n - 8) + 4 + i)
+            const int hi = n >> 3;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
+                u32x4 o;
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    const uint32_t lo1 = vr[2 * w + 1][i >> 1], lo0 = vr[2 * w][i >> 1];
+                    const uint32_t hi1 = vr[2 * w + 1][2 + (i >> 1)], hi0 = vr[2 * w][2 + (i >> 1)];
+                    o[w] = __builtin_amdgcn_perm(hi ? hi1 : lo1, hi ? hi0 : lo0, sel);
+                }
+                vA[i] = as_bf16x8(o);
+            }
         }
 
         // ---- row maxima, one query row per lane (per row tile); the scores themselves stay
@@ -464,7 +513,7 @@ __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item,
                 const float alpha = fast_exp2(m_run[nt] - m_new);
                 scale_acc(lacc[nt], alpha);
 #pragma unroll
-                for (int i = 0; i < 8; ++i) scale_acc(oacc[nt][i], alpha);
+                for (int i = 0; i < NI; ++i) scale_acc(oacc[nt][i], alpha);
                 m_run[nt] = m_new;
             }
         }
@@ -480,7 +529,7 @@ __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item,
             for (int x = 0; x < 8; ++x) pB[x] = (__bf16)fast_exp2(fmaf(r[x], a.scale_log2, neg_m));
             lacc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pB, lacc[nt], 0, 0, 0);
 #pragma unroll
-            for (int i = 0; i < 8; ++i)
+            for (int i = 0; i < NI; ++i)
                 oacc[nt][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vA[i], pB, oacc[nt][i], 0, 0, 0);
         }
     };
@@ -513,22 +562,32 @@ __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item,
 
     // ---- partial rows: lane (n, kg) holds, for row 16 nt + n, dims 8 (4 kg + jj) + i: runs of 8 floats
     const char* ml = sgpr(a.ws + a.lay.ml + (size_t)item.pbase * sizeof(float2));          // the item's first partial row
-    const char* pacc = sgpr(a.ws + a.lay.acc + (size_t)item.pbase * (kD * sizeof(float)));
+    const char* pacc = sgpr(a.ws + a.lay.acc + (size_t)item.pbase * (D * sizeof(float)));
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
         const float l = lacc[nt][0];   // every element of the column holds the row's sum
         const int row = nt * 16 + n;
         if (nt * 16 < item.nrows) {    // wave-uniform: lane 0 has a row here, so all nine stores are issued
             if (row < item.nrows) {
-                const uint32_t dst = (uint32_t)row * (kD * 4u) + (uint32_t)kg * 128u;
+                if constexpr (D == 128) {
+                    const uint32_t dst = (uint32_t)row * (D * 4u) + (uint32_t)kg * 128u;
 #pragma unroll
-                for (int jj = 0; jj < 4; ++jj) {
-                    store_f32x4(pacc, dst + jj * 32, f32x4{oacc[nt][0][jj], oacc[nt][1][jj], oacc[nt][2][jj], oacc[nt][3][jj]});
-                    store_f32x4(pacc, dst + jj * 32 + 16, f32x4{oacc[nt][4][jj], oacc[nt][5][jj], oacc[nt][6][jj], oacc[nt][7][jj]});
+                    for (int jj = 0; jj < 4; ++jj) {
+                        store_f32x4(pacc, dst + jj * 32, f32x4{oacc[nt][0][jj], oacc[nt][1][jj], oacc[nt][2][jj], oacc[nt][3][jj]});
+                        store_f32x4(pacc, dst + jj * 32 + 16, f32x4{oacc[nt][4][jj], oacc[nt][5][jj], oacc[nt][6][jj], oacc[nt][7][jj]});
+                    }
+                } else {
+                    // product i, output row m = 4 kg + jj: dim 8 m + i for m < 8, 8 (m - 8) + 4 + i for m >= 8
+#pragma unroll
+                    for (int jj = 0; jj < 4; ++jj) {
+                        const int m = 4 * kg + jj, db = m < 8 ? 8 * m : 8 * (m - 8) + 4;
+                        store_f32x4(pacc, (uint32_t)row * (D * 4u) + (uint32_t)db * 4u,
+                                    f32x4{oacc[nt][0][jj], oacc[nt][1][jj], oacc[nt][2][jj], oacc[nt][3][jj]});
+                    }
                 }
                 if (kg == 0) store_f32x2(ml, (uint32_t)row * 8u, m_run[nt], l);
             }
-            sm.seq += 9;
+            sm.seq += D == 128 ? 9 : 5;
         }
     }
     sm.phase = (sm.phase + ntiles) & 1;
@@ -603,6 +662,7 @@ __device__ __forceinline__ void sweep_team_core(const SweepArgs& a, const Item& 
 
 constexpr int kWavesPerGroup = 4;   // one wave per SIMD of a compute unit: a workgroup fills the unit
 
+template <int D>
 __global__ __launch_bounds__(64 * kWavesPerGroup) void sweep_mfma_kernel(SweepArgs a, int g_rcp, int xcd_aware) {
     // Every wave sweeps a share of its own and owns a quarter of the workgroup's LDS; the waves of a
     // workgroup never wait for one another on this path.  (They sit in one workgroup so that the row
@@ -634,11 +694,20 @@ __global__ __launch_bounds__(64 * kWavesPerGroup) void sweep_mfma_kernel(SweepAr
     L.kg = lane >> 4;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const int row = 4 * i + L.kg;                          // token row of the block this lane fetches in load i
-        L.dma_off[i] = row * 256 + ((L.n ^ row) & 15) * 16;    // LDS chunk position n receives global chunk n ^ row
-        L.k_off[i] = L.n * 256 + (((4 * i + L.kg) ^ L.n) & 15) * 16;   // token row n, chunk 4 ks + kg
-        const int vrow = 4 * L.kg + i;                         // token row of V k-slot i (and i + 4 in the second block)
-        L.v_off[i] = vrow * 256 + ((L.n ^ vrow) & 15) * 16;    // chunk n of that row
+        if constexpr (D == 128) {
+            const int row = 4 * i + L.kg;                          // token row of the block this lane fetches in load i
+            L.dma_off[i] = row * 256 + ((L.n ^ row) & 15) * 16;    // LDS chunk position n receives global chunk n ^ row
+            L.k_off[i] = L.n * 256 + (((4 * i + L.kg) ^ L.n) & 15) * 16;   // token row n, chunk 4 ks + kg
+            const int vrow = 4 * L.kg + i;                         // token row of V k-slot i (and i + 4 in the second block)
+            L.v_off[i] = vrow * 256 + ((L.n ^ vrow) & 15) * 16;    // chunk n of that row
+        } else {
+            // head_dim 64: 128-byte token rows of 8 chunks, eight rows per load; position p of row r holds chunk p ^ (r % 8)
+            const int row = 8 * (i & 1) + (lane >> 3), pos = lane & 7;
+            L.dma_off[i] = row * 128 + ((pos ^ row) & 7) * 16;     // (loads 0 and 1 only)
+            L.k_off[i] = L.n * 128 + (((4 * (i & 1) + L.kg) ^ L.n) & 7) * 16;   // token row n, chunk 4 ks + kg (k-steps 0 and 1)
+            const int vrow = 4 * L.kg + i;
+            L.v_off[i] = vrow * 128 + ((L.n ^ vrow) & 7) * 16;     // chunk n % 8 of that row
+        }
     }
 
     // Item descriptors come through LDS too, kDescWindow at a time (one load of 4
@@ -697,14 +766,16 @@ __global__ __launch_bounds__(64 * kWavesPerGroup) void sweep_mfma_kernel(SweepAr
         // A piece of a shared run as this wave's only work, its row tiles on the neighbouring waves of this
         // workgroup: the team sweeps it together if it qualifies (every member sees the same columns, so
         // they all decide alike).  Members without rows of their own only take part in that.
-        if (a.fast_shared && team >= 2 && it + 1 == it_end && share + n_waves >= n_shares &&
-            ((item.c1 - item.c0) & 1) == 0 && item.c1 - item.c0 >= 8 && item.c1 - item.c0 <= kTeamCols &&
-            item.tok_end == item.c1 * kBlock && (wv & (team - 1)) == rank) {
-            wait_lgkmcnt0();
-            const uint32_t ring = sgpr((uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)s_stage_all) +
-                                  (team == 2 ? (uint32_t)(wv >> 1) * (2u * kStages * kStageBytes) : 0u);
-            sweep_team_core(a, item, team, rank, g_rcp, ring, q_base, lane);
-            __builtin_amdgcn_endpgm();   // (not `return`: control must not rejoin the loop, or the loop's values live across the sequence)
+        if constexpr (D == 128) {   // (the team sequence is written for head_dim 128)
+            if (a.fast_shared && team >= 2 && it + 1 == it_end && share + n_waves >= n_shares &&
+                ((item.c1 - item.c0) & 1) == 0 && item.c1 - item.c0 >= 8 && item.c1 - item.c0 <= kTeamCols &&
+                item.tok_end == item.c1 * kBlock && (wv & (team - 1)) == rank) {
+                wait_lgkmcnt0();
+                const uint32_t ring = sgpr((uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)s_stage_all) +
+                                      (team == 2 ? (uint32_t)(wv >> 1) * (2u * kStages * kStageBytes) : 0u);
+                sweep_team_core(a, item, team, rank, g_rcp, ring, q_base, lane);
+                __builtin_amdgcn_endpgm();   // (not `return`: control must not rejoin the loop, or the loop's values live across the sequence)
+            }
         }
         if (item.nrows == 0 && it + 1 == it_end) continue;   // a slot that only exists for a team (or a filler)
         for (;;) {
@@ -716,9 +787,9 @@ __global__ __launch_bounds__(64 * kWavesPerGroup) void sweep_mfma_kernel(SweepAr
                 wait_all(sm);
             }
             const Item next = has_next ? read_desc(it + 1 - win_first) : item;
-            if (item.nrows <= 16) sweep_item<1>(a, item, next, has_next, g_rcp, s_stage, s_cols, s_q, lds_base, cols_base, q_base, L, lane, sm);
-            else if (item.nrows <= 32) sweep_item<2>(a, item, next, has_next, g_rcp, s_stage, s_cols, s_q, lds_base, cols_base, q_base, L, lane, sm);
-            else sweep_item<4>(a, item, next, has_next, g_rcp, s_stage, s_cols, s_q, lds_base, cols_base, q_base, L, lane, sm);
+            if (item.nrows <= 16) sweep_item<1, D>(a, item, next, has_next, g_rcp, s_stage, s_cols, s_q, lds_base, cols_base, q_base, L, lane, sm);
+            else if (item.nrows <= 32) sweep_item<2, D>(a, item, next, has_next, g_rcp, s_stage, s_cols, s_q, lds_base, cols_base, q_base, L, lane, sm);
+            else sweep_item<4, D>(a, item, next, has_next, g_rcp, s_stage, s_cols, s_q, lds_base, cols_base, q_base, L, lane, sm);
             if (!has_next) break;
             ++it;
             item = next;
@@ -726,11 +797,14 @@ __global__ __launch_bounds__(64 * kWavesPerGroup) void sweep_mfma_kernel(SweepAr
     }
 }
 
-void launch_sweep_mfma(const SweepArgs& a, int grid, const Launch& L) {
+void launch_sweep_mfma(const SweepArgs& a, int head_dim, int grid, const Launch& L) {
     const int g_rcp = (65536 + a.G - 1) / a.G;   // (row * g_rcp) >> 16 == row / G for the 64 rows of an item
     static const int xcd_aware = [] { const char* v = std::getenv("FEA_XCD_AWARE"); return v && *v ? std::atoi(v) : 1; }();
-    hipExtLaunchKernelGGL(sweep_mfma_kernel, dim3(grid / kWavesPerGroup), dim3(64 * kWavesPerGroup), 0, static_cast<hipStream_t>(L.stream),
-                          static_cast<hipEvent_t>(L.ev_start), static_cast<hipEvent_t>(L.ev_stop), 0, a, g_rcp, xcd_aware);
+    hipStream_t st = static_cast<hipStream_t>(L.stream);
+    hipEvent_t e0 = static_cast<hipEvent_t>(L.ev_start), e1 = static_cast<hipEvent_t>(L.ev_stop);
+    const dim3 g(grid / kWavesPerGroup), b(64 * kWavesPerGroup);
+    if (head_dim == 64) hipExtLaunchKernelGGL(sweep_mfma_kernel<64>, g, b, 0, st, e0, e1, 0, a, g_rcp, xcd_aware);
+    else hipExtLaunchKernelGGL(sweep_mfma_kernel<128>, g, b, 0, st, e0, e1, 0, a, g_rcp, xcd_aware);
 }
 
 }  // namespace fea

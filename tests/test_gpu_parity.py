@@ -104,7 +104,7 @@ def _random_tables(seed, B, Hkv, d, dtype, lens, num_blocks, mode):
 
 
 @pytest.mark.parametrize("mode", ["random", "same_first_then_random", "nested", "all_same_block", "identical_rows"])
-@pytest.mark.parametrize("dtype,Hq,Hkv,d", [("f32", 8, 2, 64), ("bf16", 32, 8, 128), ("bf16", 16, 2, 128)])
+@pytest.mark.parametrize("dtype,Hq,Hkv,d", [("f32", 8, 2, 64), ("bf16", 32, 8, 128), ("bf16", 16, 2, 128), ("bf16", 16, 4, 64)])
 @pytest.mark.parametrize("lens", [[0, 1, 15, 16, 17, 160, 161, 500, 512, 33, 160, 160, 700, 2, 48, 31],
                                   [0, 160, 161, 500, 512, 100, 160, 160, 700, 48, 64, 49, 1000]])
 def test_any_block_table_is_handled(mode, dtype, Hq, Hkv, d, lens):
@@ -134,7 +134,7 @@ def test_other_shapes(dtype, Hq, Hkv, d):
     assert_close(out, oracle_for(wl, bt, lens), dtype, what=f"{dtype} {Hq}/{Hkv}/{d}")
 
 
-@pytest.mark.parametrize("dtype,Hq,Hkv,d", [("f32", 8, 4, 64), ("f32", 6, 2, 128), ("bf16", 14, 2, 64), ("bf16", 8, 4, 256),
+@pytest.mark.parametrize("dtype,Hq,Hkv,d", [("f32", 8, 4, 64), ("f32", 6, 2, 128), ("bf16", 34, 2, 64), ("bf16", 8, 4, 256),
                                             ("f32", 4, 4, 32)])
 def test_vector_sweep_on_batches_that_fill_the_chip(dtype, Hq, Hkv, d):
     """The vector sweep has two instantiations: wide passes (up to 16 stacked query rows) for batches too small to
@@ -625,3 +625,36 @@ def test_long_pieces_of_a_shared_run_swept_by_teams():
     sample = [0, 1, 63, 64, 127, 128, 192, 199]
     want = oracle_for(wl, bt, lens, requests=sample)
     assert_close(out[sample], want[sample], "bf16", what="teams, pieces of more than 128 columns")
+
+
+@pytest.mark.parametrize("name", ["c2", "c3", "c4", "c5"])
+@pytest.mark.parametrize("heads", [(32, 8), (28, 4), (8, 8)])
+def test_head_dim_64_on_the_matrix_core(name, heads):
+    """bf16 caches with head_dim 64 take the matrix-core sweep too (2 KB blocks, two k-steps, four output products
+    per 16 rows; shared runs with more than 64 rows go row tile by row tile, the team sequence being written for
+    head_dim 128): the scaled batch shapes, a few query-group sizes, against the oracle."""
+    spec = dataclasses.replace(W.scaled(W.CONFIGS[name], **SMALL[name]), head_dim=64, num_q_heads=heads[0],
+                               num_kv_heads=heads[1], name=f"{name}_d64")
+    wl = W.generate(spec)
+    out, bt, lens, info = run_workload(wl)
+    assert info["variant"] == 1 and info["overflow"] == 0
+    print(name, heads, info, assert_close(out, oracle_for(wl, bt, lens), "bf16", what=f"{name} d=64 {heads}"))
+
+
+def test_head_dim_64_wide_group_and_long_rows():
+    """head_dim 64 with a prefix group of several row tiles (72 requests x 4 heads per KV head), items of 16, 32 and
+    64 rows, ragged lengths, and scores that rise along the prefix (the reference exponents get raised)."""
+    spec = W.Spec("d64_wide", 63, "bf16", 16, 4, 64, ((72, 1024), (9, 160), (3, 0)), (1, 90))
+    wl = W.generate(spec)
+    bt, lens = library_tables(wl)
+    k = W.bf16_bits_to_f32(wl.k_cache)
+    t = np.arange(1024, dtype=np.float32)
+    shared = bt[0, :64]
+    k[shared] = k[shared].reshape(64, 4, 16, 64) * np.float32(0.05) + (t * np.float32(0.9) / np.float32(8.0)).reshape(64, 1, 16, 1)
+    wl.k_cache[:] = W.f32_to_bf16_bits(k)
+    wl.q[:] = W.f32_to_bf16_bits(W.bf16_bits_to_f32(wl.q) * np.float32(0.1) + np.float32(1.0))
+    W.poison_dead_slots(wl, bt, lens)
+    s = wl.spec
+    out, info = run_hip(wl.q, wl.k_cache, wl.v_cache, bt, lens, s.num_q_heads, s.num_kv_heads, s.head_dim, s.dtype)
+    assert info["variant"] == 1 and info["groups"] == 2
+    assert_close(out, oracle_for(wl, bt, lens), "bf16", what="d=64 wide group, rising scores")
