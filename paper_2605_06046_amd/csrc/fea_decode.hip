@@ -95,14 +95,17 @@ static int32_t resolve(const fea_attn_params* p, int32_t B, int32_t stride, Reso
         return fail(FEA_EINVAL, "%s: problem too large (B * num_kv_heads * table_stride / 2 exceeds 2^30 tiles)", who);
     const Knobs& kn = knobs();
     r.G = p->num_q_heads / p->num_kv_heads;
-    const bool mfma_ok = p->dtype == FEA_DTYPE_BF16 && (p->head_dim == 128 || p->head_dim == 64) && r.G <= 16;
+    const bool mfma_ok = p->dtype == FEA_DTYPE_BF16 && (p->head_dim == 128 || p->head_dim == 64 || p->head_dim == 256) && r.G <= 16;
     r.variant = (mfma_ok && !kn.force_generic) ? 1 : 0;
-    r.mpt = r.G >= kTileRows ? 1 : kTileRows / r.G;
+    // requests per row tile of a shared run: 64 query rows per work item, 32 on the matrix-core path at head_dim 256
+    // (a wave's accumulation registers hold O for 32 rows of 256 dims)
+    const int tile_rows = (r.variant == 1 && p->head_dim == 256) ? 32 : kTileRows;
+    r.mpt = r.G >= tile_rows ? 1 : tile_rows / r.G;
     r.grouping = p->max_group == 1 ? 0 : 1;
     r.split_user = p->split_blocks > 0 ? ((p->split_blocks + 1) & ~1) : 0;
     // the sweep grid the plan is cut for: one single-wave workgroup per SIMD on the
     // matrix-core path, a few workgroups per CU on the generic path
-    r.grid = kn.sweep_grid > 0 ? std::max(4, kn.sweep_grid & ~3) : (r.variant == 1 ? 4 : 8) * cu_count();   // waves; four to a workgroup on the matrix-core path
+    r.grid = kn.sweep_grid > 0 ? std::max(4, kn.sweep_grid & ~3) : (r.variant == 1 ? (p->head_dim == 256 ? 2 : 4) : 8) * cu_count();   // waves; four to a workgroup on the matrix-core path (two at head_dim 256)
     // The plan is cut for a few waves fewer than the grid has.  With every one of the
     // 4 x CUs single-wave workgroups busy from start to end, a handful of them (the first
     // ones dispatched) were measured to run about 1.5x longer than the rest, whatever

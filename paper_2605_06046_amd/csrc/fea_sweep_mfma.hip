@@ -1,9 +1,13 @@
-// KV sweep on the matrix cores: bf16 caches, head_dim 128 or 64, query groups of up to
-// 16 heads per KV head (any ratio: 7 as in 28/4, 5 as in 40/8, ...).  What follows
-// describes head_dim 128; head_dim 64 is the same kernel with 2 KB blocks (two loads
-// each, 128-byte token rows of eight chunks, swizzled by the row modulo 8), two
+// KV sweep on the matrix cores: bf16 caches, head_dim 128, 64 or 256, query groups of
+// up to 16 heads per KV head (any ratio: 7 as in 28/4, 5 as in 40/8, ...).  What
+// follows describes head_dim 128.  Head_dim 64 is the same kernel with 2 KB blocks (two
+// loads each, 128-byte token rows of eight chunks, swizzled by the row modulo 8), two
 // k-steps in the first product and four output products per 16 rows, lanes n and n+8
-// sharing a V chunk and taking its lower and upper four dims.
+// sharing a V chunk and taking its lower and upper four dims.  Head_dim 256: 8 KB
+// blocks (eight loads, 512-byte rows whose halves are swizzled like 256-byte rows),
+// eight k-steps, sixteen output products per 16 rows (lane n takes V chunks n and
+// n+16), work items of at most 32 rows (O for 32 rows fills half the accumulation
+// registers), and two waves per workgroup, whose two 32 KB stages each fill the LDS.
 //
 // One wave per SIMD (workgroups of four waves, one workgroup per compute unit); the planner has
 // cut the stream of 32-token tiles into equal shares, and wave w sweeps the consecutive work
@@ -152,8 +156,8 @@ __device__ __forceinline__ void wait_lgkmcnt0() { asm volatile("s_waitcnt lgkmcn
 struct Lanes {
     int n;                 // lane % 16: query row of a 16-row tile / token of a block / 16-byte chunk
     int kg;                // lane / 16: k-slot group of the MFMA operands
-    uint32_t dma_off[4];   // global byte offset inside a block for load i (rows 4i + kg, swizzled chunk)
-    uint32_t k_off[4];     // LDS byte offset inside a K block of the A operand for k-step ks
+    uint32_t dma_off[8];   // global byte offset inside a block for load i (rows 4i + kg, swizzled chunk)
+    uint32_t k_off[8];     // LDS byte offset inside a K block of the A operand for k-step ks
     uint32_t v_off[4];     // LDS byte offset inside a V block of token row 4 kg + j
 };
 
@@ -172,8 +176,9 @@ __device__ __forceinline__ void fetch_tile(const SweepArgs& a, int g, int b0, in
 #pragma unroll
     for (int x = 0; x < 4; ++x) {
         const uint32_t l = stage + x * BLK;
-        if constexpr (D == 128) dma16x4(bases[x], L.dma_off[0], L.dma_off[1], L.dma_off[2], L.dma_off[3], l, l + 1024, l + 2048, l + 3072);
-        else dma16x2(bases[x], L.dma_off[0], L.dma_off[1], l, l + 1024);
+        if constexpr (D == 64) dma16x2(bases[x], L.dma_off[0], L.dma_off[1], l, l + 1024);
+        else dma16x4(bases[x], L.dma_off[0], L.dma_off[1], L.dma_off[2], L.dma_off[3], l, l + 1024, l + 2048, l + 3072);
+        if constexpr (D == 256) dma16x4(bases[x], L.dma_off[4], L.dma_off[5], L.dma_off[6], L.dma_off[7], l + 4096, l + 5120, l + 6144, l + 7168);
     }
 }
 
@@ -347,7 +352,7 @@ __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item,
             }
             dma16x4(sgpr(qn), off[0], off[1], off[2], off[3], qb, qb + 1024, qb + 2048, qb + 3072);
             sm.seq += 4;
-        } else {
+        } else if constexpr (D == 64) {
             uint32_t off[2];
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
@@ -356,6 +361,16 @@ __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item,
             }
             dma16x2(sgpr(qn), off[0], off[1], qb, qb + 1024);
             sm.seq += 2;
+        } else {
+            uint32_t off[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int row = 2 * j + (lane >> 5), pos = lane & 31;  // 512-byte rows: two per load
+                off[j] = (uint32_t)min(row, next.nrows - 1) * 512u + (uint32_t)((pos & 16) | ((pos ^ row) & 15)) * 16u;
+            }
+            dma16x4(sgpr(qn), off[0], off[1], off[2], off[3], qb, qb + 1024, qb + 2048, qb + 3072);
+            dma16x4(sgpr(qn), off[4], off[5], off[6], off[7], qb + 4096, qb + 5120, qb + 6144, qb + 7168);
+            sm.seq += 8;
         }
         sm.qmark = sm.seq;
     }
@@ -407,13 +422,15 @@ __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item,
         // rows everything is read up front so that the refill starts at once; with 64
         // rows registers are short, so V is read after the first product (that
         // instantiation computes long enough per tile for the later refill not to matter).
-        bf16x8 kA[2][KS];
-        u32x4 vr[8];
+        constexpr bool kLate = NT == 4 || D == 256;   // registers are short: K of the second block and V are read after the first product
+        constexpr int VH = D == 256 ? 2 : 1;          // a V row has 32 chunks at head_dim 256: lane n takes chunks n and n + 16
+        bf16x8 kA[kLate ? 1 : 2][KS];
+        u32x4 vr[8 * VH];
 #pragma unroll
-        for (int mt = 0; mt < (NT < 4 ? 2 : 1); ++mt)
+        for (int mt = 0; mt < (kLate ? 1 : 2); ++mt)
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) kA[mt][ks] = as_bf16x8(ld16(st + mt * BLK + L.k_off[ks]));
-        if constexpr (NT < 4) {
+        if constexpr (!kLate) {
 #pragma unroll
             for (int j = 0; j < 8; ++j) vr[j] = ld16(st + (2 + (j >> 2)) * BLK + L.v_off[j & 3]);
             wait_lgkmcnt0();   // the stage is read out: refill it with stream tile t+2
@@ -429,21 +446,23 @@ __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item,
         for (int nt = 0; nt < NT; ++nt) sacc[nt][0] = sacc[nt][1] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt) {
-            if constexpr (NT == 4) {
+            if constexpr (kLate) {
                 if (mt == 1) {
 #pragma unroll
-                    for (int ks = 0; ks < KS; ++ks) kA[1][ks] = as_bf16x8(ld16(st + BLK + L.k_off[ks]));
+                    for (int ks = 0; ks < KS; ++ks) kA[0][ks] = as_bf16x8(ld16(st + BLK + L.k_off[ks]));
                 }
             }
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt)
-                    sacc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kA[mt][ks], qB[nt][ks], sacc[nt][mt], 0, 0, 0);
+                    sacc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kA[kLate ? 0 : mt][ks], qB[nt][ks], sacc[nt][mt], 0, 0, 0);
         }
-        if constexpr (NT == 4) {
+        if constexpr (kLate) {
 #pragma unroll
-            for (int j = 0; j < 8; ++j) vr[j] = ld16(st + (2 + (j >> 2)) * BLK + L.v_off[j & 3]);
+            for (int h = 0; h < VH; ++h)
+#pragma unroll
+                for (int j = 0; j < 8; ++j) vr[8 * h + j] = ld16(st + (2 + (j >> 2)) * BLK + L.v_off[j & 3] + h * 256);
             wait_lgkmcnt0();
             issue(t + 1);
             issue(t + 2);
@@ -454,18 +473,23 @@ __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item,
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const int pos = tile_pos + (j >> 2) * 16 + kg * 4 + (j & 3);
-                if (pos >= item.tok_end) vr[j] = u32x4{0u, 0u, 0u, 0u};
+                if (pos >= item.tok_end) {
+#pragma unroll
+                    for (int h = 0; h < VH; ++h) vr[8 * h + j] = u32x4{0u, 0u, 0u, 0u};
+                }
             }
         }
-        if constexpr (D == 128) {
+        if constexpr (D >= 128) {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
-                u32x4 o;
+            for (int h = 0; h < VH; ++h)
 #pragma unroll
-                for (int w = 0; w < 4; ++w) o[w] = __builtin_amdgcn_perm(vr[2 * w + 1][i >> 1], vr[2 * w][i >> 1], sel);
-                vA[i] = as_bf16x8(o);
-            }
+                for (int i = 0; i < 8; ++i) {
+                    const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
+                    u32x4 o;
+#pragma unroll
+                    for (int w = 0; w < 4; ++w) o[w] = __builtin_amdgcn_perm(vr[8 * h + 2 * w + 1][i >> 1], vr[8 * h + 2 * w][i >> 1], sel);
+                    vA[8 * h + i] = as_bf16x8(o);     // (head_dim 256: products 8.. carry dims 128 + 8 n + i)
+                }
         } else {
             // a token row has 8 chunks: lanes n and n + 8 read the same one; lane n < 8 hands elements 0..3 of it
             // to products 0..3 (dims 8 n + i), lane n >= 8 elements 4..7 (dims 8 (n - 8) + 4 + i)
@@ -569,12 +593,15 @@ __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item,
         const int row = nt * 16 + n;
         if (nt * 16 < item.nrows) {    // wave-uniform: lane 0 has a row here, so all nine stores are issued
             if (row < item.nrows) {
-                if constexpr (D == 128) {
-                    const uint32_t dst = (uint32_t)row * (D * 4u) + (uint32_t)kg * 128u;
+                if constexpr (D >= 128) {
 #pragma unroll
-                    for (int jj = 0; jj < 4; ++jj) {
-                        store_f32x4(pacc, dst + jj * 32, f32x4{oacc[nt][0][jj], oacc[nt][1][jj], oacc[nt][2][jj], oacc[nt][3][jj]});
-                        store_f32x4(pacc, dst + jj * 32 + 16, f32x4{oacc[nt][4][jj], oacc[nt][5][jj], oacc[nt][6][jj], oacc[nt][7][jj]});
+                    for (int h = 0; h < D / 128; ++h) {
+                        const uint32_t dst = (uint32_t)row * (D * 4u) + (uint32_t)kg * 128u + (uint32_t)h * 512u;
+#pragma unroll
+                        for (int jj = 0; jj < 4; ++jj) {
+                            store_f32x4(pacc, dst + jj * 32, f32x4{oacc[nt][8 * h + 0][jj], oacc[nt][8 * h + 1][jj], oacc[nt][8 * h + 2][jj], oacc[nt][8 * h + 3][jj]});
+                            store_f32x4(pacc, dst + jj * 32 + 16, f32x4{oacc[nt][8 * h + 4][jj], oacc[nt][8 * h + 5][jj], oacc[nt][8 * h + 6][jj], oacc[nt][8 * h + 7][jj]});
+                        }
                     }
                 } else {
                     // product i, output row m = 4 kg + jj: dim 8 m + i for m < 8, 8 (m - 8) + 4 + i for m >= 8
@@ -587,7 +614,7 @@ __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item,
                 }
                 if (kg == 0) store_f32x2(ml, (uint32_t)row * 8u, m_run[nt], l);
             }
-            sm.seq += D == 128 ? 9 : 5;
+            sm.seq += D / 16 + 1;
         }
     }
     sm.phase = (sm.phase + ntiles) & 1;
@@ -662,21 +689,26 @@ __device__ __forceinline__ void sweep_team_core(const SweepArgs& a, const Item& 
 
 constexpr int kWavesPerGroup = 4;   // one wave per SIMD of a compute unit: a workgroup fills the unit
 
+// Waves per workgroup: four (one per SIMD) - at head_dim 256 two, whose tile stages (2 x 32 KB each) fill the LDS.
+template <int D> constexpr int waves_per_group() { return D == 256 ? 2 : kWavesPerGroup; }
+
 template <int D>
-__global__ __launch_bounds__(64 * kWavesPerGroup) void sweep_mfma_kernel(SweepArgs a, int g_rcp, int xcd_aware) {
+__global__ __launch_bounds__(64 * waves_per_group<D>()) void sweep_mfma_kernel(SweepArgs a, int g_rcp, int xcd_aware) {
+    constexpr int WPG = waves_per_group<D>();
+    constexpr int STG = 4 * kBlock * D * 2;          // bytes of a tile stage: K b0 | K b1 | V b0 | V b1
     // Every wave sweeps a share of its own and owns a quarter of the workgroup's LDS; the waves of a
     // workgroup never wait for one another on this path.  (They sit in one workgroup so that the row
     // tiles of a shared run's piece, which read the same KV bytes, can share what is fetched.)
-    __shared__ __attribute__((aligned(1024))) char s_stage_all[kWavesPerGroup * kStages * kStageBytes];
-    __shared__ __attribute__((aligned(256))) int s_cols_all[kWavesPerGroup * 3 * 64];
-    __shared__ __attribute__((aligned(256))) int s_desc_all[kWavesPerGroup * kDescWindow * 8];     // the next few item descriptors
-    __shared__ __attribute__((aligned(1024))) char s_q_all[kWavesPerGroup * kBlock * kD * 2];      // query rows of the next item
+    __shared__ __attribute__((aligned(1024))) char s_stage_all[WPG * kStages * STG];
+    __shared__ __attribute__((aligned(256))) int s_cols_all[WPG * 3 * 64];
+    __shared__ __attribute__((aligned(256))) int s_desc_all[WPG * kDescWindow * 8];     // the next few item descriptors
+    __shared__ __attribute__((aligned(1024))) char s_q_all[WPG * kBlock * (D < 128 ? 128 : D) * 2];   // query rows of the next item (at least 4 KB per wave: a team keeps its block ids there)
     const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = threadIdx.x & 63;
-    char* s_stage = s_stage_all + wv * (kStages * kStageBytes);
+    char* s_stage = s_stage_all + wv * (kStages * STG);
     int* s_cols = s_cols_all + wv * (3 * 64);
     int* s_desc = s_desc_all + wv * (kDescWindow * 8);
-    char* s_q = s_q_all + wv * (kBlock * kD * 2);
+    char* s_q = s_q_all + wv * (kBlock * (D < 128 ? 128 : D) * 2);
     int* hdr = reinterpret_cast<int*>(a.ws);
     const Item* items = reinterpret_cast<const Item*>(a.ws + a.lay.items);
     const int n_items = hdr[H_ITEMS];
@@ -700,13 +732,27 @@ __global__ __launch_bounds__(64 * kWavesPerGroup) void sweep_mfma_kernel(SweepAr
             L.k_off[i] = L.n * 256 + (((4 * i + L.kg) ^ L.n) & 15) * 16;   // token row n, chunk 4 ks + kg
             const int vrow = 4 * L.kg + i;                         // token row of V k-slot i (and i + 4 in the second block)
             L.v_off[i] = vrow * 256 + ((L.n ^ vrow) & 15) * 16;    // chunk n of that row
-        } else {
+        } else if constexpr (D == 64) {
             // head_dim 64: 128-byte token rows of 8 chunks, eight rows per load; position p of row r holds chunk p ^ (r % 8)
             const int row = 8 * (i & 1) + (lane >> 3), pos = lane & 7;
             L.dma_off[i] = row * 128 + ((pos ^ row) & 7) * 16;     // (loads 0 and 1 only)
             L.k_off[i] = L.n * 128 + (((4 * (i & 1) + L.kg) ^ L.n) & 7) * 16;   // token row n, chunk 4 ks + kg (k-steps 0 and 1)
             const int vrow = 4 * L.kg + i;
             L.v_off[i] = vrow * 128 + ((L.n ^ vrow) & 7) * 16;     // chunk n % 8 of that row
+        } else {
+            // head_dim 256: 512-byte token rows of 32 chunks, two rows per load; each half of a row is swizzled like a
+            // 256-byte row (position p of row r holds chunk (p & 16) | ((p ^ r) & 15)); V chunk n + 16 sits 256 bytes on
+            const int vrow = 4 * L.kg + i;
+            L.v_off[i] = vrow * 512 + ((L.n ^ vrow) & 15) * 16;
+        }
+    }
+    if constexpr (D == 256) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int row = 2 * i + (lane >> 5), pos = lane & 31;
+            L.dma_off[i] = row * 512 + ((pos & 16) | ((pos ^ row) & 15)) * 16;
+            const int c = 4 * i + L.kg;                                          // chunk of k-step i
+            L.k_off[i] = L.n * 512 + ((c & 16) | ((c ^ L.n) & 15)) * 16;
         }
     }
 
@@ -741,8 +787,8 @@ __global__ __launch_bounds__(64 * kWavesPerGroup) void sweep_mfma_kernel(SweepAr
         const int x = blockIdx.x & 7, k = blockIdx.x >> 3;
         group = 2 * ((k >> 1) * 8 + x) + (k & 1);
     }
-    int share = kWavesPerGroup * group + wv;
-    const int n_waves = kWavesPerGroup * (int)gridDim.x;
+    int share = WPG * group + wv;
+    const int n_waves = WPG * (int)gridDim.x;
     const int n_shares = hdr[H_WAVES];
     const int* wave_first = reinterpret_cast<const int*>(a.ws + a.lay.wave_first);
     for (; share < n_shares; share += n_waves) {
@@ -788,8 +834,8 @@ __global__ __launch_bounds__(64 * kWavesPerGroup) void sweep_mfma_kernel(SweepAr
             }
             const Item next = has_next ? read_desc(it + 1 - win_first) : item;
             if (item.nrows <= 16) sweep_item<1, D>(a, item, next, has_next, g_rcp, s_stage, s_cols, s_q, lds_base, cols_base, q_base, L, lane, sm);
-            else if (item.nrows <= 32) sweep_item<2, D>(a, item, next, has_next, g_rcp, s_stage, s_cols, s_q, lds_base, cols_base, q_base, L, lane, sm);
-            else sweep_item<4, D>(a, item, next, has_next, g_rcp, s_stage, s_cols, s_q, lds_base, cols_base, q_base, L, lane, sm);
+            else if (D == 256 || item.nrows <= 32) sweep_item<2, D>(a, item, next, has_next, g_rcp, s_stage, s_cols, s_q, lds_base, cols_base, q_base, L, lane, sm);   // (head_dim 256: the planner makes no item of more than 32 rows)
+            else sweep_item<(D == 256 ? 2 : 4), D>(a, item, next, has_next, g_rcp, s_stage, s_cols, s_q, lds_base, cols_base, q_base, L, lane, sm);
             if (!has_next) break;
             ++it;
             item = next;
@@ -802,9 +848,9 @@ void launch_sweep_mfma(const SweepArgs& a, int head_dim, int grid, const Launch&
     static const int xcd_aware = [] { const char* v = std::getenv("FEA_XCD_AWARE"); return v && *v ? std::atoi(v) : 1; }();
     hipStream_t st = static_cast<hipStream_t>(L.stream);
     hipEvent_t e0 = static_cast<hipEvent_t>(L.ev_start), e1 = static_cast<hipEvent_t>(L.ev_stop);
-    const dim3 g(grid / kWavesPerGroup), b(64 * kWavesPerGroup);
-    if (head_dim == 64) hipExtLaunchKernelGGL(sweep_mfma_kernel<64>, g, b, 0, st, e0, e1, 0, a, g_rcp, xcd_aware);
-    else hipExtLaunchKernelGGL(sweep_mfma_kernel<128>, g, b, 0, st, e0, e1, 0, a, g_rcp, xcd_aware);
+    if (head_dim == 64) hipExtLaunchKernelGGL(sweep_mfma_kernel<64>, dim3(grid / 4), dim3(256), 0, st, e0, e1, 0, a, g_rcp, xcd_aware);
+    else if (head_dim == 256) hipExtLaunchKernelGGL(sweep_mfma_kernel<256>, dim3(grid / 2), dim3(128), 0, st, e0, e1, 0, a, g_rcp, xcd_aware);
+    else hipExtLaunchKernelGGL(sweep_mfma_kernel<128>, dim3(grid / 4), dim3(256), 0, st, e0, e1, 0, a, g_rcp, xcd_aware);
 }
 
 }  // namespace fea

@@ -104,7 +104,7 @@ def _random_tables(seed, B, Hkv, d, dtype, lens, num_blocks, mode):
 
 
 @pytest.mark.parametrize("mode", ["random", "same_first_then_random", "nested", "all_same_block", "identical_rows"])
-@pytest.mark.parametrize("dtype,Hq,Hkv,d", [("f32", 8, 2, 64), ("bf16", 32, 8, 128), ("bf16", 16, 2, 128), ("bf16", 16, 4, 64)])
+@pytest.mark.parametrize("dtype,Hq,Hkv,d", [("f32", 8, 2, 64), ("bf16", 32, 8, 128), ("bf16", 16, 2, 128), ("bf16", 16, 4, 64), ("bf16", 8, 2, 256)])
 @pytest.mark.parametrize("lens", [[0, 1, 15, 16, 17, 160, 161, 500, 512, 33, 160, 160, 700, 2, 48, 31],
                                   [0, 160, 161, 500, 512, 100, 160, 160, 700, 48, 64, 49, 1000]])
 def test_any_block_table_is_handled(mode, dtype, Hq, Hkv, d, lens):
@@ -134,7 +134,7 @@ def test_other_shapes(dtype, Hq, Hkv, d):
     assert_close(out, oracle_for(wl, bt, lens), dtype, what=f"{dtype} {Hq}/{Hkv}/{d}")
 
 
-@pytest.mark.parametrize("dtype,Hq,Hkv,d", [("f32", 8, 4, 64), ("f32", 6, 2, 128), ("bf16", 34, 2, 64), ("bf16", 8, 4, 256),
+@pytest.mark.parametrize("dtype,Hq,Hkv,d", [("f32", 8, 4, 64), ("f32", 6, 2, 128), ("bf16", 34, 2, 64), ("bf16", 36, 2, 256),
                                             ("f32", 4, 4, 32)])
 def test_vector_sweep_on_batches_that_fill_the_chip(dtype, Hq, Hkv, d):
     """The vector sweep has two instantiations: wide passes (up to 16 stacked query rows) for batches too small to
@@ -658,3 +658,33 @@ def test_head_dim_64_wide_group_and_long_rows():
     out, info = run_hip(wl.q, wl.k_cache, wl.v_cache, bt, lens, s.num_q_heads, s.num_kv_heads, s.head_dim, s.dtype)
     assert info["variant"] == 1 and info["groups"] == 2
     assert_close(out, oracle_for(wl, bt, lens), "bf16", what="d=64 wide group, rising scores")
+
+
+@pytest.mark.parametrize("name", ["c2", "c3", "c4", "c5"])
+@pytest.mark.parametrize("heads", [(16, 4), (14, 2), (4, 4)])
+def test_head_dim_256_on_the_matrix_core(name, heads):
+    """bf16 caches with head_dim 256 on the matrix-core sweep: 8 KB blocks, eight k-steps, sixteen output products
+    per 16 rows, work items of at most 32 query rows, two waves per workgroup."""
+    spec = dataclasses.replace(W.scaled(W.CONFIGS[name], **SMALL[name]), head_dim=256, num_q_heads=heads[0],
+                               num_kv_heads=heads[1], name=f"{name}_d256")
+    wl = W.generate(spec)
+    out, bt, lens, info = run_workload(wl)
+    assert info["variant"] == 1 and info["overflow"] == 0
+    print(name, heads, info, assert_close(out, oracle_for(wl, bt, lens), "bf16", what=f"{name} d=256 {heads}"))
+
+
+def test_head_dim_256_wide_group_and_rising_scores():
+    spec = W.Spec("d256_wide", 64, "bf16", 8, 2, 256, ((40, 512), (9, 160), (3, 0)), (1, 90))
+    wl = W.generate(spec)
+    bt, lens = library_tables(wl)
+    k = W.bf16_bits_to_f32(wl.k_cache)
+    t = np.arange(512, dtype=np.float32)
+    shared = bt[0, :32]
+    k[shared] = k[shared].reshape(32, 2, 16, 256) * np.float32(0.05) + (t * np.float32(0.9) / np.float32(16.0)).reshape(32, 1, 16, 1)
+    wl.k_cache[:] = W.f32_to_bf16_bits(k)
+    wl.q[:] = W.f32_to_bf16_bits(W.bf16_bits_to_f32(wl.q) * np.float32(0.1) + np.float32(1.0))
+    W.poison_dead_slots(wl, bt, lens)
+    s = wl.spec
+    out, info = run_hip(wl.q, wl.k_cache, wl.v_cache, bt, lens, s.num_q_heads, s.num_kv_heads, s.head_dim, s.dtype)
+    assert info["variant"] == 1 and info["groups"] == 2
+    assert_close(out, oracle_for(wl, bt, lens), "bf16", what="d=256 wide group, rising scores")
