@@ -95,7 +95,9 @@ static int32_t resolve(const fea_attn_params* p, int32_t B, int32_t stride, Reso
         return fail(FEA_EINVAL, "%s: problem too large (B * num_kv_heads * table_stride / 2 exceeds 2^30 tiles)", who);
     const Knobs& kn = knobs();
     r.G = p->num_q_heads / p->num_kv_heads;
-    const bool mfma_ok = p->dtype == FEA_DTYPE_BF16 && (p->head_dim == 128 || p->head_dim == 64 || p->head_dim == 256) && r.G <= 16;
+    // (a work item's query rows - a request's query group, or stacked ones - fill at most 64 matrix-core rows, 32 at head_dim 256)
+    const bool mfma_ok = p->dtype == FEA_DTYPE_BF16 && (p->head_dim == 128 || p->head_dim == 64 || p->head_dim == 256) &&
+                         r.G <= (p->head_dim == 256 ? 32 : 64);
     r.variant = (mfma_ok && !kn.force_generic) ? 1 : 0;
     // requests per row tile of a shared run: 64 query rows per work item, 32 on the matrix-core path at head_dim 256
     // (a wave's accumulation registers hold O for 32 rows of 256 dims)

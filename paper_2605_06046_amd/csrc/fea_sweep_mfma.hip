@@ -1,5 +1,5 @@
 // KV sweep on the matrix cores: bf16 caches, head_dim 128, 64 or 256, query groups of
-// up to 16 heads per KV head (any ratio: 7 as in 28/4, 5 as in 40/8, ...).  What
+// up to 64 heads per KV head (32 at head_dim 256; any ratio: 7 as in 28/4, 5 as in 40/8, ...).  What
 // follows describes head_dim 128.  Head_dim 64 is the same kernel with 2 KB blocks (two
 // loads each, 128-byte token rows of eight chunks, swizzled by the row modulo 8), two
 // k-steps in the first product and four output products per 16 rows, lanes n and n+8
@@ -319,7 +319,7 @@ __device__ __forceinline__ void sweep_item(const SweepArgs& a, const Item& item,
         for (int nt = 0; nt < NT; ++nt) {
             const int row = nt * 16 + n;
             const bool ok = row < item.nrows;
-            const int mem = (row * g_rcp) >> 16, hh = row - mem * a.G;   // row / G and row % G (rows < 64, G <= 16)
+            const int mem = (row * g_rcp) >> 16, hh = row - mem * a.G;   // row / G and row % G (rows < 64, G <= 64)
             const int req = ok ? (item.mlist_off < 0 ? item.who : mlist[mem]) : 0;
             const uint16_t* qp = Q + ((size_t)req * a.Hq + item.g * a.G + hh) * D + kg * 8;
 #pragma unroll

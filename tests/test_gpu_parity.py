@@ -134,7 +134,7 @@ def test_other_shapes(dtype, Hq, Hkv, d):
     assert_close(out, oracle_for(wl, bt, lens), dtype, what=f"{dtype} {Hq}/{Hkv}/{d}")
 
 
-@pytest.mark.parametrize("dtype,Hq,Hkv,d", [("f32", 8, 4, 64), ("f32", 6, 2, 128), ("bf16", 34, 2, 64), ("bf16", 36, 2, 256),
+@pytest.mark.parametrize("dtype,Hq,Hkv,d", [("f32", 8, 4, 64), ("f32", 6, 2, 128), ("bf16", 130, 2, 64), ("f32", 4, 2, 256),
                                             ("f32", 4, 4, 32)])
 def test_vector_sweep_on_batches_that_fill_the_chip(dtype, Hq, Hkv, d):
     """The vector sweep has two instantiations: wide passes (up to 16 stacked query rows) for batches too small to
@@ -688,3 +688,15 @@ def test_head_dim_256_wide_group_and_rising_scores():
     out, info = run_hip(wl.q, wl.k_cache, wl.v_cache, bt, lens, s.num_q_heads, s.num_kv_heads, s.head_dim, s.dtype)
     assert info["variant"] == 1 and info["groups"] == 2
     assert_close(out, oracle_for(wl, bt, lens), "bf16", what="d=256 wide group, rising scores")
+
+
+@pytest.mark.parametrize("Hq,Hkv,d", [(34, 2, 128), (32, 1, 128), (64, 1, 128), (60, 1, 64), (48, 2, 64), (20, 1, 256), (32, 1, 256),
+                                      (40, 1, 128), (64, 2, 128)])
+def test_wide_query_groups_on_the_matrix_core(Hq, Hkv, d):
+    """Multi-query shapes: a request's query group of 17..64 heads per KV head (up to 32 at head_dim 256) is one
+    work item of that many rows; prefix groups stack one or two requests per row tile, or none (64 heads)."""
+    spec = W.Spec("mqa", 65, "bf16", Hq, Hkv, d, ((6, 320), (3, 96), (2, 0)), (1, 200))
+    wl = W.generate(spec)
+    out, bt, lens, info = run_workload(wl)
+    assert info["variant"] == 1 and info["overflow"] == 0 and info["groups"] == 2
+    assert_close(out, oracle_for(wl, bt, lens), "bf16", what=f"query groups of {Hq // Hkv} heads, d={d}")
