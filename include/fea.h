@@ -251,6 +251,12 @@ int32_t fea_validate_block_tables(const int32_t* block_tables, int32_t table_str
  * FEA_GROUPABLE_REQUESTS requests of a batch take part in that detection: a
  * request with a higher index sweeps its whole history on its own (same result,
  * more KV reads); fea_decode_plan_info reports how many requests were grouped.
+ * Which kernel sweeps the KV history follows from the parameters alone (the
+ * result does not depend on it beyond rounding): bf16 caches with head_dim 64,
+ * 128 or 256 and at most 64 query heads per KV head (32 at head_dim 256) go
+ * through the matrix cores; float32 caches and wider query groups through the
+ * vector unit, several times slower (fea_decode_plan_info: kernel
+ * variant).
  *
  *   workspace     DEVICE scratch of at least fea_decode_workspace_bytes() bytes,
  *                 256-byte aligned; contents are overwritten.  Calls that share
