@@ -700,3 +700,31 @@ def test_wide_query_groups_on_the_matrix_core(Hq, Hkv, d):
     out, bt, lens, info = run_workload(wl)
     assert info["variant"] == 1 and info["overflow"] == 0 and info["groups"] == 2
     assert_close(out, oracle_for(wl, bt, lens), "bf16", what=f"query groups of {Hq // Hkv} heads, d={d}")
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_shapes_against_the_oracle(seed):
+    """Seeded random draws over everything the interface accepts at once: cache type, head dim, head counts (query
+    groups of 1 to 64 heads), prefix groups of random sizes and depths next to requests on their own, suffix
+    ranges, arrival order, pool permutation - whichever kernels the shape selects."""
+    rng = np.random.default_rng(9000 + seed)
+    dtype = "bf16" if rng.random() < 0.7 else "f32"
+    d = int(rng.choice([64, 128, 256] if dtype == "bf16" else [32, 64, 128, 256]))
+    Hkv = int(rng.choice([1, 2, 4, 8]))
+    G = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 12, 16, 24, 32] if d == 256 else [1, 2, 3, 4, 5, 7, 8, 12, 16, 24, 40, 64]))
+    if dtype == "f32":
+        G = min(G, 8)
+    groups = []
+    for _ in range(int(rng.integers(0, 4))):
+        groups.append((int(rng.integers(2, 40)), int(rng.integers(1, 30)) * 16))
+    groups += [(1, 0)] * int(rng.integers(0, 6))
+    if not groups:
+        groups = [(3, 0)]
+    lo = int(rng.integers(1, 60))
+    spec = W.Spec(f"rand{seed}", 100 + seed, dtype, G * Hkv, Hkv, d, tuple(groups), (lo, lo + int(rng.integers(0, 300))),
+                  interleave=bool(rng.integers(0, 2)), pool_factor=1.0 + float(rng.random()),
+                  perm_seed=int(rng.integers(0, 2)) * (seed + 1))
+    wl = W.generate(spec)
+    out, bt, lens, info = run_workload(wl)
+    assert info["overflow"] == 0
+    print(seed, dtype, d, G * Hkv, Hkv, groups, info, assert_close(out, oracle_for(wl, bt, lens), dtype, what=f"random shape {seed}"))
