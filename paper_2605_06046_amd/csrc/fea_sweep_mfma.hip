@@ -61,10 +61,10 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kD = 128;                 // head dim
+constexpr int kD = 128;                 // head dim of the team sequence (the sweep itself is instantiated per head dim)
 constexpr int kTileTok = 32;            // tokens per tile (two blocks)
-constexpr int kBlkBytes = kBlock * kD * 2;      // one (block, KV head): 4096 bytes
-constexpr int kStageBytes = 4 * kBlkBytes;      // K b0 | K b1 | V b0 | V b1
+constexpr int kBlkBytes = kBlock * kD * 2;      // one (block, KV head) at that head dim: 4096 bytes
+constexpr int kStageBytes = 4 * kBlkBytes;      // a tile stage at that head dim: K b0 | K b1 | V b0 | V b1
 constexpr int kStages = 2;
 constexpr int kDescWindow = 8;           // item descriptors fetched into LDS at a time
 constexpr float kSlack = 24.f;           // log2 of the largest softmax weight tolerated before the reference is raised
