@@ -397,7 +397,7 @@ def main():
         "host_table_build": {"ms": m["table_build_ms"], "tokens_per_s": m["table_build_tokens_per_s"]},
         "roofline": {"bound": "hbm", "achieved": nn(achieved), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": nn(achieved / HBM_PEAK_GBS), "traffic": traffic_from_profile(args.workload, m["plan"]),
-                     "kernel": "sweep_mfma_kernel" if m["plan"]["variant"] == 1 else "sweep_generic_kernel",
+                     "kernel": ("sweep_generic_kernel", "sweep_mfma_kernel", "decode_small_kernel")[m["plan"]["variant"]],
                      "bytes_per_launch": case.unique_bytes,
                      "achievable_gbs": None if calib is None else calib["scattered_gbs"],
                      "frac_of_achievable": None if calib is None else nn(achieved / calib["scattered_gbs"])},

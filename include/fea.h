@@ -89,7 +89,15 @@ typedef struct fea_attn_params {
     int32_t merge_rows_min; /* the merge takes several output rows per wave from this
                                many rows (B * num_q_heads) on.  0: the library's default
                                (8192); < 0: always; > 0: that many                       */
-    int32_t reserved;       /* must be 0                                                 */
+    int32_t fused_max;      /* batches too small to be worth a plan are done in ONE launch,
+                               a workgroup per (request, KV head) walking the whole
+                               history (no plan; a shared block is then read once per
+                               request, which at this size the L2 serves).  0: the library
+                               decides, from an estimate of both ways' durations (about:
+                               rows of up to 64 entries, as many (request, KV head) pairs
+                               as the GPU has compute units, 4 query heads per KV head;
+                               more for float32 caches); < 0: never; > 0: every batch
+                               whose table rows have at most this many entries          */
 } fea_attn_params;
 
 /* Message of the last failure on this thread ("" if none).  HOST string owned
@@ -256,7 +264,11 @@ int32_t fea_validate_block_tables(const int32_t* block_tables, int32_t table_str
  * 128 or 256 and at most 64 query heads per KV head (32 at head_dim 256) go
  * through the matrix cores; float32 caches and wider query groups through the
  * vector unit, several times slower (fea_decode_plan_info: kernel
- * variant).
+ * variant).  A batch within fea_attn_params.fused_max takes one launch of the
+ * vector unit and makes no plan: FEA_FLAG_REUSE_PLAN and FEA_FLAG_REFRESH_PLAN
+ * change nothing for it, FEA_FLAG_PLAN_ONLY still makes the plan (for
+ * fea_decode_plan_info), and after an attention call fea_decode_plan_info
+ * reports variant 2 and no groups.
  *
  *   workspace     DEVICE scratch of at least fea_decode_workspace_bytes() bytes,
  *                 256-byte aligned; contents are overwritten.  Calls that share
@@ -303,7 +315,7 @@ int32_t fea_decode_attention_static(const fea_attn_params* p,
  * (synchronises hip_stream; for tests, tuning and the benchmark's reporting).
  * info: HOST int32[9] = { work items, prefix groups, requests in groups,
  * blocks per work item, partial rows, shared-run blocks (sum over groups),
- * kernel variant (0 generic, 1 MFMA), overflow flag (1: the plan did not fit
+ * kernel variant (0 generic, 1 MFMA, 2 one fused launch without a plan), overflow flag (1: the plan did not fit
  * its buffers, 2: FEA_FLAG_REFRESH_PLAN met a request it cannot stretch), sweep waves that
  * were given a share }. */
 int32_t fea_decode_plan_info(const void* workspace /* DEVICE */, void* hip_stream,

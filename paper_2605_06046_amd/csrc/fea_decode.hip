@@ -1,5 +1,5 @@
 // fea_decode_attention: argument checks, workspace carving and the three launches
-// (plan, KV sweep, merge).  No device memory is allocated here and nothing
+// (plan, KV sweep, merge), or the one launch that small batches take.  No device memory is allocated here and nothing
 // synchronises except fea_decode_plan_info.
 #include <hip/hip_runtime.h>
 
@@ -39,6 +39,7 @@ static const Knobs& knobs() {
 
 struct Resolved {
     int variant;      // 0 generic, 1 MFMA
+    int fused;        // the batch is small enough for the one-launch kernel (no plan, sweep and merge)
     int G, mpt, grouping, split_user, grid;
     int pre, pre_grid;   // leaders and common runs on many workgroups first (large tables)
     int merge_by_rows;   // very many output rows: the merge takes several rows per wave
@@ -66,6 +67,24 @@ static int cu_count() {
     return n;
 }
 
+// Whether the one-launch kernel is expected to beat plan + sweep + merge.  Both sides are estimates in
+// microseconds fitted to measurements (1 to 128 requests, 128 to 2048 tokens, bf16 and float32, head dims 64 to
+// 256, query groups of 4 to 16): the one launch pays, per round of workgroups on the chip and per pass of four
+// query heads, a fixed part (the chain of dependent loads, the folds, the barrier) plus vector-unit work per token
+// row; the three launches cost their start-up and the planner's one workgroup, growing slowly with the batch -
+// and far more on the vector-unit sweep, which small batches suit badly.
+static bool fused_pays(const fea_attn_params* p, int64_t B, int64_t stride, int variant) {
+    const bool f32 = p->dtype == FEA_DTYPE_F32;
+    const int64_t rounds = (B * p->num_kv_heads + cu_count() - 1) / cu_count();
+    const int64_t passes = (p->num_q_heads / p->num_kv_heads + 3) / 4;
+    const int tokens_per_wave_load = 64 / (p->head_dim / (f32 ? 4 : 8));
+    const double steps = (double)stride * kBlock / tokens_per_wave_load;
+    const double fused_us = 2.6 + (double)(rounds * passes) * (6.7 + (f32 ? 0.054 : 0.07) * steps);
+    const double planned_us = variant == 1 ? (B < 2 ? 22.0 : B < 16 ? 27.0 : B <= 64 ? 31.0 : 35.0) + 0.04 * (double)stride
+                                           : (B < 4 ? 25.0 : B < 16 ? 40.0 : 90.0);
+    return fused_us < planned_us;
+}
+
 static int32_t check_params(const fea_attn_params* p, const char* who) {
     if (!p) return fail(FEA_EINVAL, "%s: params is NULL", who);
     if (p->num_q_heads <= 0 || p->num_kv_heads <= 0 || p->num_q_heads % p->num_kv_heads != 0)
@@ -82,7 +101,6 @@ static int32_t check_params(const fea_attn_params* p, const char* who) {
     const int plan_flags = p->flags & (FEA_FLAG_REUSE_PLAN | FEA_FLAG_PLAN_ONLY | FEA_FLAG_REFRESH_PLAN);
     if (plan_flags & (plan_flags - 1))
         return fail(FEA_EINVAL, "%s: FEA_FLAG_REUSE_PLAN, FEA_FLAG_PLAN_ONLY and FEA_FLAG_REFRESH_PLAN exclude one another", who);
-    if (p->reserved) return fail(FEA_EINVAL, "%s: the reserved field must be 0", who);
     return FEA_OK;
 }
 
@@ -99,6 +117,8 @@ static int32_t resolve(const fea_attn_params* p, int32_t B, int32_t stride, Reso
     const bool mfma_ok = p->dtype == FEA_DTYPE_BF16 && (p->head_dim == 128 || p->head_dim == 64 || p->head_dim == 256) &&
                          r.G <= (p->head_dim == 256 ? 32 : 64);
     r.variant = (mfma_ok && !kn.force_generic) ? 1 : 0;
+    // One launch instead of three where that is estimated to be faster; an explicit bound on the row length stands alone.
+    r.fused = p->fused_max < 0 ? 0 : p->fused_max > 0 ? (stride <= p->fused_max) : fused_pays(p, B, stride, r.variant);
     // requests per row tile of a shared run: 64 query rows per work item, 32 on the matrix-core path at head_dim 256
     // (a wave's accumulation registers hold O for 32 rows of 256 dims)
     const int tile_rows = (r.variant == 1 && p->head_dim == 256) ? 32 : kTileRows;
@@ -209,8 +229,9 @@ int32_t decode_impl(const fea_attn_params* p, const void* q, const void* k_cache
         unsigned char mask = 0;
         for (int k = 0; k < 3; ++k) {
             if (g_prof_which >= 0 && g_prof_which != k) continue;
-            if (k == 0 && (p->flags & FEA_FLAG_REUSE_PLAN)) continue;
+            if (k == 0 && ((p->flags & FEA_FLAG_REUSE_PLAN) || (r.fused && !plan_only))) continue;
             if (k > 0 && plan_only) continue;
+            if (k == 2 && r.fused) continue;
             where[k].ev_start = ev[2 * k];
             where[k].ev_stop = ev[2 * k + 1];
             if (k == 0) { where[0].ev_mid[0] = ev[6]; where[0].ev_mid[1] = ev[7]; }
@@ -219,7 +240,7 @@ int32_t decode_impl(const fea_attn_params* p, const void* q, const void* k_cache
         g_prof_mask[slot] = mask;
         ++g_prof_calls;
     }
-    if (!(p->flags & FEA_FLAG_REUSE_PLAN)) {   // a new plan, or the one in the workspace stretched to the lengths of now
+    if (!(p->flags & FEA_FLAG_REUSE_PLAN) && (plan_only || !r.fused)) {   // a new plan, or the one in the workspace stretched to the lengths of now
         PlanArgs pa;
         std::memset(&pa, 0, sizeof pa);
         pa.bt = block_tables;
@@ -265,9 +286,13 @@ int32_t decode_impl(const fea_attn_params* p, const void* q, const void* k_cache
     sa.G = r.G;
     sa.mpt = r.mpt;
     sa.fast_shared = (p->head_dim == 128 && (int64_t)B * p->num_q_heads < (1 << 23) && !knobs().no_fast_shared) ? 1 : 0;
-    if (r.variant == 1) launch_sweep_mfma(sa, p->head_dim, r.grid, where[1]);
-    else launch_sweep_generic(sa, p->dtype, p->head_dim, r.grid, where[1]);
-    launch_merge(sa, p->dtype, p->head_dim, r.merge_by_rows != 0, where[2]);
+    if (r.fused) {
+        launch_decode_small(sa, p->dtype, p->head_dim, where[1]);
+    } else {
+        if (r.variant == 1) launch_sweep_mfma(sa, p->head_dim, r.grid, where[1]);
+        else launch_sweep_generic(sa, p->dtype, p->head_dim, r.grid, where[1]);
+        launch_merge(sa, p->dtype, p->head_dim, r.merge_by_rows != 0, where[2]);
+    }
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(FEA_EHIP, "fea_decode_attention: launch failed: %s", hipGetErrorString(e));
     return FEA_OK;

@@ -24,7 +24,7 @@ enum Hdr {
     H_SPLIT = 4,       // KV blocks per wave (balanced mode) or per item (fixed split)
     H_ROWS = 5,        // partial rows in use
     H_SHARED_BLOCKS = 6,
-    H_VARIANT = 7,     // 0 generic, 1 MFMA
+    H_VARIANT = 7,     // 0 generic, 1 MFMA, 2 one fused launch (no plan)
     H_OVERFLOW = 8,    // planner ran out of item/partial capacity (never by construction)
     H_WAVES = 9,       // sweep waves that received work
     H_WORDS = 64
@@ -138,5 +138,6 @@ void launch_refresh(const PlanArgs& a, const Launch& L);
 void launch_sweep_generic(const SweepArgs& a, int dtype, int head_dim, int grid, const Launch& L);
 void launch_sweep_mfma(const SweepArgs& a, int head_dim, int grid, const Launch& L);
 void launch_merge(const SweepArgs& a, int dtype, int head_dim, bool by_rows, const Launch& L);
+void launch_decode_small(const SweepArgs& a, int dtype, int head_dim, const Launch& L);
 
 }  // namespace fea

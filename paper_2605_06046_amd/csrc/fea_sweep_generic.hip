@@ -24,10 +24,10 @@ namespace fea {
 template <typename T> struct Elem;
 template <> struct Elem<float> {
     static constexpr int kPerLoad = 4;   // elements in one 16-byte load
-    __device__ static void load(const float* p, float (&f)[4]) {
-        const float4 v = *reinterpret_cast<const float4*>(p);
-        f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
-    }
+    using Raw = float4;                  // the 16 bytes as loaded
+    __device__ static Raw load_raw(const float* p) { return *reinterpret_cast<const float4*>(p); }
+    __device__ static void unpack(const Raw& v, float (&f)[4]) { f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w; }
+    __device__ static void load(const float* p, float (&f)[4]) { unpack(load_raw(p), f); }
     __device__ static void store(float* p, float v) { *p = v; }
     __device__ static void store8(float* p, const float (&v)[8]) {   // p is 32-byte aligned
         reinterpret_cast<float4*>(p)[0] = make_float4(v[0], v[1], v[2], v[3]);
@@ -37,8 +37,9 @@ template <> struct Elem<float> {
 struct bf16_t { uint16_t bits; };
 template <> struct Elem<bf16_t> {
     static constexpr int kPerLoad = 8;
-    __device__ static void load(const bf16_t* p, float (&f)[8]) {
-        const uint4 v = *reinterpret_cast<const uint4*>(p);
+    using Raw = uint4;
+    __device__ static Raw load_raw(const bf16_t* p) { return *reinterpret_cast<const uint4*>(p); }
+    __device__ static void unpack(const Raw& v, float (&f)[8]) {
         const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
@@ -46,6 +47,7 @@ template <> struct Elem<bf16_t> {
             f[2 * k + 1] = __uint_as_float(w[k] & 0xFFFF0000u);
         }
     }
+    __device__ static void load(const bf16_t* p, float (&f)[8]) { unpack(load_raw(p), f); }
     __device__ static void store(bf16_t* p, float v) {   // round to nearest even
         uint32_t u = __float_as_uint(v);
         if ((u & 0x7FFFFFFFu) > 0x7F800000u) { p->bits = 0x7FC0; return; }
@@ -420,6 +422,190 @@ __global__ __launch_bounds__(256) void merge_rows_kernel(SweepArgs a) {
     Elem<T>::store8(out + c * 8, num);
 }
 
+// The whole call in one launch, for batches too small to be worth a plan, a sweep and a merge of their
+// own (a few requests with short histories, where three dependent launches and the planner's one
+// workgroup cost several times what the attention does).  One workgroup per (request, KV head) walks the
+// request's whole history: every lane group keeps the online-softmax state (m, l, acc) of the token rows it
+// visits - kSmallAhead rows in flight per lane, requested together and folded into the state with one
+// change of the reference exponent - and the states are folded over the wave's lane groups, then over
+// the waves through LDS, normalised and written as out[i, h, :] = softmax(q K^T * scale) V (Section 2.1).
+// No plan is read or made: a block that several requests alias is read once per request, out of L2
+// after the first.
+constexpr int kSmallThreads = 512;
+constexpr int kSmallWaves = kSmallThreads / 64;
+constexpr int kSmallRows = 4;      // query heads per pass over the history
+constexpr int kSmallAhead = 8;     // token rows a lane has in flight
+constexpr int kSmallCols = 512;    // table entries of the request kept in LDS (longer rows read the rest from memory)
+
+template <typename T, int D>
+__global__ __launch_bounds__(kSmallThreads) void decode_small_kernel(SweepArgs a) {
+    constexpr int EPL = Elem<T>::kPerLoad;
+    constexpr int LPT = D / EPL;          // lanes that share one token row
+    constexpr int TPW = 64 / LPT;         // token rows per wave-wide load
+    constexpr int RB = kSmallRows, U = kSmallAhead;
+    constexpr int STEP = kSmallWaves * TPW;
+    using Raw = typename Elem<T>::Raw;
+    __shared__ float s_acc[kSmallWaves][RB][D];
+    __shared__ float2 s_ml[kSmallWaves][RB];
+    __shared__ int s_row[kSmallCols];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c = lane % LPT, r = lane / LPT;
+    const int i = blockIdx.x / a.Hkv, g = blockIdx.x - i * a.Hkv;
+    if (blockIdx.x == 0 && tid < H_WORDS)   // what a later look at the workspace finds: no plan, this kernel
+        reinterpret_cast<int*>(a.ws)[tid] = tid == H_VARIANT ? 2 : tid == H_WAVES ? (int)gridDim.x * kSmallWaves : 0;
+    const int L = min(max(a.seq_lens[i], 0), a.stride * kBlock);
+    const int32_t* row = a.bt + (size_t)i * a.stride;
+    const T* Q = static_cast<const T*>(a.q) + ((size_t)i * a.Hq + g * a.G) * D;
+    const T* K = static_cast<const T*>(a.k_cache);
+    const T* V = static_cast<const T*>(a.v_cache);
+    T* out = static_cast<T*>(a.out) + ((size_t)i * a.Hq + g * a.G) * D;
+    // (a -1 inside a request's length - the caller's error - must not become a read before the cache)
+    for (int x = tid; x < min((L + kBlock - 1) / kBlock, kSmallCols); x += kSmallThreads) s_row[x] = max(row[x], 0);
+    __syncthreads();
+
+    for (int row0 = 0; row0 < a.G; row0 += RB) {
+        const int nh = min(RB, a.G - row0);
+        float qf[RB][EPL], acc[RB][EPL], m[RB], l[RB];
+#pragma unroll
+        for (int j = 0; j < RB; ++j) {
+            if (j < nh) {
+                Elem<T>::load(Q + (size_t)(row0 + j) * D + c * EPL, qf[j]);
+            } else {
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) qf[j][e] = 0.f;
+            }
+            m[j] = -INFINITY;
+            l[j] = 0.f;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) acc[j][e] = 0.f;
+        }
+        // One round: U token rows per lane.  FULL: every lane of the wave has all U (straight-line code, the loads
+        // in flight together); otherwise only the first nu rows exist for any lane and the rest is skipped.
+        auto round = [&](auto full_tag, int t0, int nu) {
+            constexpr bool FULL = decltype(full_tag)::value;
+            Raw kraw[U], vraw[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (FULL || u < nu) {
+                    const int t = min(t0 + u * STEP, L - 1);   // (a lane past the end loads the last token and gives it weight 0)
+                    const int col = t / kBlock;
+                    const int blk = col < kSmallCols ? s_row[col] : max(row[col], 0);
+                    const size_t at = (((size_t)blk * a.Hkv + g) * kBlock + (t % kBlock)) * D + c * EPL;
+                    kraw[u] = Elem<T>::load_raw(K + at);
+                    vraw[u] = Elem<T>::load_raw(V + at);
+                }
+            }
+            float sc[U][RB];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (FULL || u < nu) {
+                    float kf[EPL];
+                    Elem<T>::unpack(kraw[u], kf);
+#pragma unroll
+                    for (int j = 0; j < RB; ++j) {
+                        float s = 0.f;
+#pragma unroll
+                        for (int e = 0; e < EPL; ++e) s = fmaf(qf[j][e], kf[e], s);
+                        sc[u][j] = s;
+                    }
+#pragma unroll
+                    for (int o = LPT / 2; o >= 1; o >>= 1)
+#pragma unroll
+                        for (int j = 0; j < RB; ++j) sc[u][j] += __shfl_xor(sc[u][j], o);
+                    const bool live = t0 + u * STEP < L;
+#pragma unroll
+                    for (int j = 0; j < RB; ++j) sc[u][j] = live ? sc[u][j] * a.scale_log2 : -INFINITY;
+                } else {
+#pragma unroll
+                    for (int j = 0; j < RB; ++j) sc[u][j] = -INFINITY;
+                }
+            }
+            // one new reference exponent for the round (row 0 is live in every lane still in the loop, so it is finite)
+#pragma unroll
+            for (int j = 0; j < RB; ++j) {
+                float mn = m[j];
+#pragma unroll
+                for (int u = 0; u < U; ++u) mn = fmaxf(mn, sc[u][j]);
+                const float al = exp2f(m[j] - mn);   // 0 the first time
+                m[j] = mn;
+                l[j] *= al;
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) acc[j][e] *= al;
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (FULL || u < nu) {
+                    float vf[EPL];
+                    Elem<T>::unpack(vraw[u], vf);
+#pragma unroll
+                    for (int j = 0; j < RB; ++j) {
+                        const float p = exp2f(sc[u][j] - m[j]);
+                        l[j] += p;
+#pragma unroll
+                        for (int e = 0; e < EPL; ++e) acc[j][e] = fmaf(p, vf[e], acc[j][e]);
+                    }
+                }
+            }
+        };
+        for (int t0 = wave * TPW + r; t0 < L; t0 += U * STEP) {
+            // rows of this round that any lane of the wave has (the same in every lane: the first active lane is
+            // the one with the lowest token)
+            const int left = (L - __builtin_amdgcn_readfirstlane(t0 - r) + STEP - 1) / STEP;
+            const int last = __builtin_amdgcn_readfirstlane(t0 - r) + (TPW - 1) + (U - 1) * STEP;   // highest token of a full round
+            if (last < L) round(std::true_type{}, t0, U);
+            else round(std::false_type{}, t0, min(U, left));
+        }
+        // fold the states of the wave's lane groups (a group that saw no token has m = -inf and weight 0)
+#pragma unroll
+        for (int o = LPT; o < 64; o <<= 1) {
+#pragma unroll
+            for (int j = 0; j < RB; ++j) {
+                const float mo = __shfl_xor(m[j], o), lo = __shfl_xor(l[j], o);
+                const float mn = fmaxf(m[j], mo);
+                const float fa = m[j] == -INFINITY ? 0.f : exp2f(m[j] - mn);
+                const float fb = mo == -INFINITY ? 0.f : exp2f(mo - mn);
+                l[j] = l[j] * fa + lo * fb;
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) acc[j][e] = acc[j][e] * fa + __shfl_xor(acc[j][e], o) * fb;
+                m[j] = mn;
+            }
+        }
+        if (r == 0) {
+#pragma unroll
+            for (int j = 0; j < RB; ++j) {
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) s_acc[wave][j][c * EPL + e] = acc[j][e];
+                if (c == 0) s_ml[wave][j] = make_float2(m[j], l[j]);
+            }
+        }
+        __syncthreads();
+        // fold the waves (fixed order), normalise, write 8 elements per thread
+        if (tid < nh * (D / 8)) {
+            const int j = tid / (D / 8), c8 = tid % (D / 8);
+            float M = -INFINITY;
+#pragma unroll
+            for (int w = 0; w < kSmallWaves; ++w) M = fmaxf(M, s_ml[w][j].x);
+            float den = 0.f, num[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) num[k] = 0.f;
+#pragma unroll
+            for (int w = 0; w < kSmallWaves; ++w) {
+                const float2 v = s_ml[w][j];
+                const float f = v.x == -INFINITY ? 0.f : exp2f(v.x - M);
+                den = fmaf(f, v.y, den);
+#pragma unroll
+                for (int k = 0; k < 8; ++k) num[k] = fmaf(f, s_acc[w][j][c8 * 8 + k], num[k]);
+            }
+            const float inv = den > 0.f ? 1.f / den : 0.f;   // an empty history gives a zero row
+#pragma unroll
+            for (int k = 0; k < 8; ++k) num[k] *= inv;
+            Elem<T>::store8(out + (size_t)(row0 + j) * D + c8 * 8, num);
+        }
+        __syncthreads();
+    }
+}
+
 template <typename T, int D>
 static void launch_generic_d(const SweepArgs& a, int grid, bool wide, const Launch& L) {
     hipStream_t st = static_cast<hipStream_t>(L.stream);
@@ -477,6 +663,25 @@ static void launch_merge_t(const SweepArgs& a, int head_dim, bool by_rows, const
 void launch_merge(const SweepArgs& a, int dtype, int head_dim, bool by_rows, const Launch& L) {
     if (dtype == FEA_DTYPE_F32) launch_merge_t<float>(a, head_dim, by_rows, L);
     else launch_merge_t<bf16_t>(a, head_dim, by_rows, L);
+}
+
+template <typename T>
+static void launch_small_t(const SweepArgs& a, int head_dim, const Launch& L) {
+    hipStream_t st = static_cast<hipStream_t>(L.stream);
+    hipEvent_t e0 = static_cast<hipEvent_t>(L.ev_start), e1 = static_cast<hipEvent_t>(L.ev_stop);
+    const int grid = a.B * a.Hkv;
+    switch (head_dim) {
+        case 32: hipExtLaunchKernelGGL((decode_small_kernel<T, 32>), dim3(grid), dim3(kSmallThreads), 0, st, e0, e1, 0, a); break;
+        case 64: hipExtLaunchKernelGGL((decode_small_kernel<T, 64>), dim3(grid), dim3(kSmallThreads), 0, st, e0, e1, 0, a); break;
+        case 128: hipExtLaunchKernelGGL((decode_small_kernel<T, 128>), dim3(grid), dim3(kSmallThreads), 0, st, e0, e1, 0, a); break;
+        case 256: hipExtLaunchKernelGGL((decode_small_kernel<T, 256>), dim3(grid), dim3(kSmallThreads), 0, st, e0, e1, 0, a); break;
+        default: break;
+    }
+}
+
+void launch_decode_small(const SweepArgs& a, int dtype, int head_dim, const Launch& L) {
+    if (dtype == FEA_DTYPE_F32) launch_small_t<float>(a, head_dim, L);
+    else launch_small_t<bf16_t>(a, head_dim, L);
 }
 
 }  // namespace fea

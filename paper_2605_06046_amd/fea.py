@@ -28,12 +28,12 @@ class AttnParams(C.Structure):
     _fields_ = [("num_q_heads", C.c_int32), ("num_kv_heads", C.c_int32), ("head_dim", C.c_int32),
                 ("block_size", C.c_int32), ("dtype", C.c_int32), ("scale", C.c_float),
                 ("split_blocks", C.c_int32), ("max_group", C.c_int32), ("flags", C.c_int32),
-                ("run_kernel_min", C.c_int32), ("merge_rows_min", C.c_int32), ("reserved", C.c_int32)]
+                ("run_kernel_min", C.c_int32), ("merge_rows_min", C.c_int32), ("fused_max", C.c_int32)]
 
     def __init__(self, num_q_heads, num_kv_heads, head_dim, dtype, scale=0.0, split_blocks=0,
-                 max_group=0, flags=0, block_size=16, run_kernel_min=0, merge_rows_min=0):
+                 max_group=0, flags=0, block_size=16, run_kernel_min=0, merge_rows_min=0, fused_max=0):
         super().__init__(num_q_heads, num_kv_heads, head_dim, block_size, dtype, scale,
-                         split_blocks, max_group, flags, run_kernel_min, merge_rows_min, 0)
+                         split_blocks, max_group, flags, run_kernel_min, merge_rows_min, fused_max)
 
 
 def library_path() -> str:

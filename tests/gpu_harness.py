@@ -21,8 +21,13 @@ def values(x: np.ndarray) -> np.ndarray:
 
 
 def run_hip(q, k_cache, v_cache, bt, lens, num_q_heads, num_kv_heads, head_dim, dtype, **pkw):
-    """q/k/v: numpy (float32 or bf16 bits); bt/lens: numpy int32.  Returns (out float64, plan info)."""
+    """q/k/v: numpy (float32 or bf16 bits); bt/lens: numpy int32.  Returns (out float64, plan info).
+
+    Unless the caller says otherwise (fused_max), the call goes through plan, sweep and merge also where the
+    library would by default take a small batch in one launch: most cases here are small so that the oracle
+    finishes, and it is the planned path they are written for.  The one-launch kernel has tests of its own."""
     import torch
+    pkw.setdefault("fused_max", -1)
     params = AttnParams(num_q_heads, num_kv_heads, head_dim,
                         FEA_DTYPE_BF16 if dtype == "bf16" else FEA_DTYPE_F32, **pkw)
     B, stride = bt.shape

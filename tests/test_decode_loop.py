@@ -97,7 +97,7 @@ def test_decode_loop_on_the_device(name):
     W.poison_dead_slots(dataclass_replace(wl, k_cache=hk, v_cache=hv, num_blocks=nb_total), bt, lens)
     dk, dv = to_device(hk), to_device(hv)
     dtype = fea.FEA_DTYPE_BF16 if spec.dtype == "bf16" else fea.FEA_DTYPE_F32
-    p = fea.AttnParams(spec.num_q_heads, spec.num_kv_heads, spec.head_dim, dtype)
+    p = fea.AttnParams(spec.num_q_heads, spec.num_kv_heads, spec.head_dim, dtype, fused_max=-1)
     ws = torch.zeros(fea.fea_decode_workspace_bytes(p, spec.batch, width), dtype=torch.uint8, device="cuda")
     rng = np.random.default_rng(11)
     shape_new = (spec.batch, spec.num_kv_heads, spec.head_dim)
@@ -132,8 +132,9 @@ class _Loop:
     """Device and host state of a decode loop on one batch: step() grows every request by one token
     (tables and lengths on the host, K/V rows through the append kernel; the oracle's caches follow)."""
 
-    def __init__(self, spec, steps, seed=11):
+    def __init__(self, spec, steps, seed=11, fused_max=-1):
         import torch
+        self.fused_max = fused_max   # -1: plan, sweep and merge also where the library would take the batch in one launch
         import paper_2605_06046_amd as fea
         from gpu_harness import to_device
         self.fea, self.torch, self.to_device, self.spec = fea, torch, to_device, spec
@@ -158,7 +159,7 @@ class _Loop:
 
     def params(self, flags):
         s = self.spec
-        return self.fea.AttnParams(s.num_q_heads, s.num_kv_heads, s.head_dim, self.dtype, flags=flags)
+        return self.fea.AttnParams(s.num_q_heads, s.num_kv_heads, s.head_dim, self.dtype, flags=flags, fused_max=self.fused_max)
 
     def sync_tables(self):
         self.dbt, self.dl = self.torch.from_numpy(self.bt).cuda(), self.torch.from_numpy(self.lens).cuda()
@@ -261,6 +262,30 @@ def test_refresh_reports_a_request_it_cannot_stretch():
     qn, out = lp.attend(fea.FEA_FLAG_REFRESH_PLAN)          # now every request has a block of its own
     assert fea.fea_decode_plan_info(lp.ws)["overflow"] == 0
     assert_close(out.float().cpu().numpy().astype(np.float64), lp.oracle(qn), "bf16", what="all shared, grown twice")
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("name", ["f32_generic", "allshared", "c2_tiny"])
+def test_small_batches_in_one_launch_over_decode_steps(name):
+    """Batches within the one-launch bound need no plan: whatever plan flag the loop passes, every step is right and
+    the workspace says that no plan was used (variant 2).  FEA_FLAG_PLAN_ONLY still makes the plan."""
+    import paper_2605_06046_amd as fea
+    from gpu_harness import assert_close
+    spec = {"f32_generic": LOOP_SPECS["f32_generic"],
+            "allshared": lambda: W.Spec("allshared", 5, "bf16", 8, 2, 128, ((4, 64),), (0, 0)),
+            "c2_tiny": lambda: W.scaled(W.CONFIGS["c2"], batch_div=16, len_div=16)}[name]()
+    steps = 20
+    lp = _Loop(spec, steps, fused_max=0)
+    for step in range(steps):
+        lp.step()
+        flags = (0, fea.FEA_FLAG_REFRESH_PLAN, fea.FEA_FLAG_REUSE_PLAN)[step % 3]
+        qn, out = lp.attend(flags)
+        info = fea.fea_decode_plan_info(lp.ws)
+        assert info["variant"] == 2 and info["items"] == 0 and info["groups"] == 0 and info["overflow"] == 0
+        assert_close(out.float().cpu().numpy().astype(np.float64), lp.oracle(qn), lp.spec.dtype, what=f"{name} step {step}")
+    lp.attend(fea.FEA_FLAG_PLAN_ONLY)
+    info = fea.fea_decode_plan_info(lp.ws)
+    assert info["variant"] in (0, 1) and info["items"] > 0 and info["groups"] >= 1
 
 
 def dataclass_replace(obj, **kw):

@@ -180,13 +180,13 @@ def test_plan_reuse_flag_and_errors():
     wl = W.generate(W.scaled(W.CONFIGS["c2"], **SMALL["c2"]))
     bt, lens = library_tables(wl)
     s = wl.spec
-    p = AttnParams(s.num_q_heads, s.num_kv_heads, s.head_dim, FEA_DTYPE_BF16)
+    p = AttnParams(s.num_q_heads, s.num_kv_heads, s.head_dim, FEA_DTYPE_BF16, fused_max=-1)
     dq, dk, dv = to_device(wl.q), to_device(wl.k_cache), to_device(wl.v_cache)
     dbt, dl = torch.from_numpy(bt).cuda(), torch.from_numpy(lens).cuda()
     ws = torch.empty(fea_decode_workspace_bytes(p, s.batch, bt.shape[1]), dtype=torch.uint8, device="cuda")
     o1, o2 = torch.empty_like(dq), torch.empty_like(dq)
     fea_decode_attention(p, dq, dk, dv, dbt, dl, o1, ws)
-    p2 = AttnParams(s.num_q_heads, s.num_kv_heads, s.head_dim, FEA_DTYPE_BF16, flags=FEA_FLAG_REUSE_PLAN)
+    p2 = AttnParams(s.num_q_heads, s.num_kv_heads, s.head_dim, FEA_DTYPE_BF16, flags=FEA_FLAG_REUSE_PLAN, fused_max=-1)
     dq2 = to_device(W.f32_to_bf16_bits(W.bf16_bits_to_f32(wl.q) * np.float32(0.5)))
     fea_decode_attention(p2, dq2, dk, dv, dbt, dl, o2, ws)     # "next layer": new q, same tables
     torch.cuda.synchronize()
@@ -209,7 +209,7 @@ def test_profiling_events_bracket_each_kernel():
     wl = W.generate(W.scaled(W.CONFIGS["c2"], **SMALL["c2"]))
     bt, lens = library_tables(wl)
     s = wl.spec
-    p = AttnParams(s.num_q_heads, s.num_kv_heads, s.head_dim, FEA_DTYPE_BF16)
+    p = AttnParams(s.num_q_heads, s.num_kv_heads, s.head_dim, FEA_DTYPE_BF16, fused_max=-1)
     dq, dk, dv = to_device(wl.q), to_device(wl.k_cache), to_device(wl.v_cache)
     dbt, dl = torch.from_numpy(bt).cuda(), torch.from_numpy(lens).cuda()
     ws = torch.empty(fea_decode_workspace_bytes(p, s.batch, bt.shape[1]), dtype=torch.uint8, device="cuda")
@@ -344,7 +344,7 @@ def test_captured_graph_replays_match_eager_calls():
     wl = W.generate(W.scaled(W.CONFIGS["c3"], 4, 8, name="c3_graph"))
     bt, lens = library_tables(wl)
     s = wl.spec
-    params = AttnParams(s.num_q_heads, s.num_kv_heads, s.head_dim, FEA_DTYPE_BF16)
+    params = AttnParams(s.num_q_heads, s.num_kv_heads, s.head_dim, FEA_DTYPE_BF16, fused_max=-1)
     B, stride = bt.shape
     q, k, v = to_device(wl.q), to_device(wl.k_cache), to_device(wl.v_cache)
     dbt, dl = torch.from_numpy(bt).cuda(), torch.from_numpy(lens).cuda()
@@ -405,7 +405,7 @@ def test_plan_only_then_reuse_equals_one_call():
     wl = W.generate(W.scaled(W.CONFIGS["c2"], 2, 4, name="c2_plan_only"))
     bt, lens = library_tables(wl)
     s = wl.spec
-    mk = lambda flags: AttnParams(s.num_q_heads, s.num_kv_heads, s.head_dim, FEA_DTYPE_BF16, flags=flags)
+    mk = lambda flags: AttnParams(s.num_q_heads, s.num_kv_heads, s.head_dim, FEA_DTYPE_BF16, flags=flags, fused_max=-1)
     q, k, v = to_device(wl.q), to_device(wl.k_cache), to_device(wl.v_cache)
     dbt, dl = torch.from_numpy(bt).cuda(), torch.from_numpy(lens).cuda()
     n = fea_decode_workspace_bytes(mk(0), *bt.shape)
@@ -728,3 +728,58 @@ def test_random_shapes_against_the_oracle(seed):
     out, bt, lens, info = run_workload(wl)
     assert info["overflow"] == 0
     print(seed, dtype, d, G * Hkv, Hkv, groups, info, assert_close(out, oracle_for(wl, bt, lens), dtype, what=f"random shape {seed}"))
+
+
+# ---- batches small enough for one launch (no plan, no partial results) ----
+
+def test_c1_takes_one_launch_by_default():
+    wl = W.generate(W.CONFIGS["c1"])
+    out, bt, lens, info = run_workload(wl, fused_max=0)
+    assert info["variant"] == 2 and info["items"] == 0 and info["groups"] == 0 and info["overflow"] == 0
+    print("c1 fused", assert_close(out, oracle_for(wl, bt, lens), "f32", what="c1 in one launch"))
+    # the bound is on the row length and on the number of (request, KV head) pairs: the scaled c2 has longer rows
+    wl = W.generate(W.scaled(W.CONFIGS["c2"], **SMALL["c2"]))
+    out, bt, lens, info = run_workload(wl, fused_max=0)
+    assert bt.shape[1] <= 64 or info["variant"] == 1
+    out, bt, lens, info = run_workload(wl, fused_max=bt.shape[1])        # an explicit bound takes it
+    assert info["variant"] == 2
+    assert_close(out, oracle_for(wl, bt, lens), "bf16", what="scaled c2 in one launch")
+    out, bt, lens, info = run_workload(wl, fused_max=bt.shape[1] - 1)    # one entry short of the rows: planned
+    assert info["variant"] == 1 and info["groups"] == 1
+
+
+@pytest.mark.parametrize("mode", ["random", "same_first_then_random", "nested", "all_same_block", "identical_rows"])
+@pytest.mark.parametrize("dtype,Hq,Hkv,d", [("f32", 8, 2, 64), ("f32", 4, 4, 32), ("f32", 6, 2, 128), ("f32", 2, 1, 256),
+                                            ("bf16", 32, 8, 128), ("bf16", 10, 2, 128), ("bf16", 16, 4, 64), ("bf16", 9, 1, 256)])
+def test_any_block_table_in_one_launch(mode, dtype, Hq, Hkv, d):
+    """Empty, one-token, block-edge and ragged histories; query groups of 1 to 9 heads (up to three passes of four);
+    every cache type and head dim; tables that alias anywhere."""
+    lens = [0, 1, 15, 16, 17, 160, 161, 500, 512, 33, 160, 160, 700, 2, 48, 31]
+    B = len(lens)
+    seed = {"random": 111, "same_first_then_random": 212, "nested": 313, "all_same_block": 414, "identical_rows": 515}[mode]
+    bt, k, v = _random_tables(seed, B, Hkv, d, dtype, lens, 40, mode)
+    rng = np.random.default_rng(6)
+    q = rng.standard_normal((B, Hq, d), dtype=np.float32)
+    if dtype == "bf16":
+        q = W.f32_to_bf16_bits(q)
+    L = np.array(lens, dtype=np.int32)
+    out, info = run_hip(q, k, v, bt, L, Hq, Hkv, d, dtype, fused_max=bt.shape[1])
+    assert info["variant"] == 2
+    assert_close(out, decode_attention(values(q), values(k), values(v), bt, L), dtype, what=f"one launch, {mode}")
+    assert (out[0] == 0).all()                        # zero-length request
+    out_s, _ = run_hip(q, k, v, bt, L, Hq, Hkv, d, dtype, fused_max=bt.shape[1], scale=0.05)
+    assert_close(out_s, decode_attention(values(q), values(k), values(v), bt, L, scale=0.05), dtype, what="one launch, custom scale")
+
+
+@pytest.mark.parametrize("name", ["c2", "c3", "c4", "c5"])
+@pytest.mark.parametrize("peaked", [False, True])
+def test_scaled_configs_in_one_launch(name, peaked):
+    """The one-launch kernel forced onto the scaled configurations (rows of up to 150 table entries, 8 to 32
+    requests), with ordinary and with sharply peaked scores; twice, bit for bit."""
+    spec = W.scaled(W.CONFIGS[name], **SMALL[name])
+    wl = W.generate(dataclasses.replace(spec, q_gain=8.0) if peaked else spec)
+    out, bt, lens, info = run_workload(wl, fused_max=1 << 20)
+    assert info["variant"] == 2
+    assert_close(out, oracle_for(wl, bt, lens), "bf16", what=f"{name} in one launch")
+    again, _, _, _ = run_workload(wl, fused_max=1 << 20)
+    assert np.array_equal(out, again)

@@ -10,12 +10,12 @@ from gpu_harness import assert_close, library_tables, oracle_for, to_device
 pytestmark = pytest.mark.gpu
 
 
-def _both(wl, bt, lens):
+def _both(wl, bt, lens, fused_max=-1):
     import torch
     import paper_2605_06046_amd as fea
     s = wl.spec
     p = fea.AttnParams(s.num_q_heads, s.num_kv_heads, s.head_dim,
-                       fea.FEA_DTYPE_BF16 if s.dtype == "bf16" else fea.FEA_DTYPE_F32)
+                       fea.FEA_DTYPE_BF16 if s.dtype == "bf16" else fea.FEA_DTYPE_F32, fused_max=fused_max)
     q, k, v = to_device(wl.q), to_device(wl.k_cache), to_device(wl.v_cache)
     dbt, dl = torch.from_numpy(bt).cuda(), torch.from_numpy(lens).cuda()
     ws = torch.empty(fea.fea_decode_workspace_bytes(p, s.batch, bt.shape[1]), dtype=torch.uint8, device="cuda")
@@ -47,6 +47,10 @@ def test_static_workspace_entry_point_equals_the_workspace_one():
     ref2, got2 = _both(small, bt2, lens2)
     assert torch.equal(ref2, got2)
     assert_close(got2.float().cpu().numpy().astype(np.float64), oracle_for(small, bt2, lens2), "f32", what="static, second call")
+    # the small batch as the library takes it by default (one launch, nothing kept in the buffer but a header)
+    ref2f, got2f = _both(small, bt2, lens2, fused_max=0)
+    assert torch.equal(ref2f, got2f)
+    assert_close(got2f.float().cpu().numpy().astype(np.float64), oracle_for(small, bt2, lens2), "f32", what="static, one launch")
     # and the first batch again after the small one
     ref3, got3 = _both(big, bt, lens)
     assert torch.equal(ref3, got3) and torch.equal(ref3, ref)
