@@ -783,3 +783,15 @@ def test_scaled_configs_in_one_launch(name, peaked):
     assert_close(out, oracle_for(wl, bt, lens), "bf16", what=f"{name} in one launch")
     again, _, _, _ = run_workload(wl, fused_max=1 << 20)
     assert np.array_equal(out, again)
+
+
+@pytest.mark.parametrize("dtype,Hq,Hkv,d", [("bf16", 8, 2, 128), ("f32", 4, 1, 64), ("bf16", 64, 1, 64)])
+def test_one_launch_on_rows_longer_than_its_table_buffer(dtype, Hq, Hkv, d):
+    """The kernel keeps the first 512 entries of a request's table row in LDS and reads the rest from memory: histories
+    of 8200 to 9500 tokens next to short ones, grouping flags that mean nothing to it, query groups of up to 64 heads
+    (16 passes)."""
+    spec = W.Spec("long_rows", 21, dtype, Hq, Hkv, d, ((2, 8192), (1, 0), (1, 0)), (5, 1300))
+    wl = W.generate(spec)
+    out, bt, lens, info = run_workload(wl, fused_max=1 << 20, max_group=1, split_blocks=6)
+    assert bt.shape[1] > 512 and lens.max() > 8192 + 16 and info["variant"] == 2
+    assert_close(out, oracle_for(wl, bt, lens), dtype, what=f"one launch, long rows {dtype} {Hq}/{Hkv}/{d}")
