@@ -68,21 +68,28 @@ static int cu_count() {
 }
 
 // Whether the one-launch kernel is expected to beat plan + sweep + merge.  Both sides are estimates in
-// microseconds fitted to measurements (1 to 128 requests, 128 to 2048 tokens, bf16 and float32, head dims 64 to
-// 256, query groups of 4 to 16): the one launch pays, per round of workgroups on the chip and per pass of four
-// query heads, a fixed part (the chain of dependent loads, the folds, the barrier) plus vector-unit work per token
-// row; the three launches cost their start-up and the planner's one workgroup, growing slowly with the batch -
-// and far more on the vector-unit sweep, which small batches suit badly.
+// microseconds fitted to measurements (1 to 128 requests, 128 to 4096 tokens, bf16 and float32, head dims 64 to
+// 256, query groups of 4 to 65).  The one launch pays, per round of workgroups on the chip and per pass of four
+// query heads, a fixed part (the chain of dependent loads, the folds, the barrier) plus vector-unit work per
+// token in proportion to the head dim.  The three launches cost their start-up and the planner's one workgroup,
+// then the KV bytes of the requests' own columns on the matrix-core path; the vector-unit sweep costs far more
+// to start with, and from some hundred thousand (query row, token) pairs on in proportion to them.  The one
+// launch is taken where it wins by a tenth.
 static bool fused_pays(const fea_attn_params* p, int64_t B, int64_t stride, int variant) {
     const bool f32 = p->dtype == FEA_DTYPE_F32;
     const int64_t rounds = (B * p->num_kv_heads + cu_count() - 1) / cu_count();
     const int64_t passes = (p->num_q_heads / p->num_kv_heads + 3) / 4;
-    const int tokens_per_wave_load = 64 / (p->head_dim / (f32 ? 4 : 8));
-    const double steps = (double)stride * kBlock / tokens_per_wave_load;
-    const double fused_us = 2.6 + (double)(rounds * passes) * (6.7 + (f32 ? 0.054 : 0.07) * steps);
-    const double planned_us = variant == 1 ? (B < 2 ? 22.0 : B < 16 ? 27.0 : B <= 64 ? 31.0 : 35.0) + 0.04 * (double)stride
-                                           : (B < 4 ? 25.0 : B < 16 ? 40.0 : 90.0);
-    return fused_us < planned_us;
+    const double tokens = (double)stride * kBlock, dd = p->head_dim / 64.0;
+    const double fused_us = 2.4 + (double)(rounds * passes) * (6.0 + (f32 ? 0.0165 : 0.0096) * dd * tokens);
+    double planned_us;
+    if (variant == 1) {
+        planned_us = (B < 2 ? 22.0 : B < 16 ? 27.0 : B <= 64 ? 31.0 : 35.0) +
+                     (0.03 + 0.003 * (double)B) * (double)stride * (p->num_kv_heads * p->head_dim / 1024.0);
+    } else {
+        planned_us = (B < 4 ? 24.0 : B < 16 ? 40.0 : 94.0) * (p->head_dim >= 128 ? 1.4 : 1.0) +
+                     (f32 ? 0.027e-3 : 0.0175e-3) * std::pow(dd, 1.6) * (double)(B * p->num_q_heads) * tokens;
+    }
+    return 1.1 * fused_us < planned_us;
 }
 
 static int32_t check_params(const fea_attn_params* p, const char* who) {
