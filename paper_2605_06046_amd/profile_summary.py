@@ -12,6 +12,11 @@
     rocprofv3 --pmc WRITE_SIZE --kernel-trace -d <raw_dir>/pmc_WRITE_SIZE_W -o p --output-format csv -- \\
         python3 bench.py --workload W --no-cpu-baseline --no-configs --no-hbm-calibration --steps 40 --warmup 4 --copy-calibration
 
+optionally the L2 cache's hits and misses,
+
+    rocprofv3 --pmc TCC_HIT_sum TCC_MISS_sum --kernel-trace -d <raw_dir>/pmc_L2_W -o p --output-format csv -- \\
+        python3 bench.py --workload W --no-cpu-baseline --no-configs --no-hbm-calibration --steps 40 --warmup 4
+
 and, optionally, <raw_dir>/untraced_W.json: the output line of the first command run
 without the profiler.  Under the profiler the library's own per-dispatch events are
 off (fea_profile_enable refuses while a profiling tool is attached, and bench.py then
@@ -70,6 +75,7 @@ def main(raw: str, wl: str, out: str) -> None:
              f"  rocprofv3 --kernel-trace --stats -d <raw>/trace_{wl} -o t --output-format csv -- python3 bench.py --workload {wl} --no-cpu-baseline --no-configs --no-hbm-calibration --steps 200 --warmup 20",
              f"  rocprofv3 --pmc FETCH_SIZE --kernel-trace -d <raw>/pmc_FETCH_SIZE_{wl} -o p --output-format csv -- python3 bench.py --workload {wl} --no-cpu-baseline --no-configs --no-hbm-calibration --steps 40 --warmup 4 --copy-calibration",
              f"  rocprofv3 --pmc WRITE_SIZE --kernel-trace -d <raw>/pmc_WRITE_SIZE_{wl} -o p --output-format csv -- python3 bench.py --workload {wl} --no-cpu-baseline --no-configs --no-hbm-calibration --steps 40 --warmup 4 --copy-calibration",
+             f"  rocprofv3 --pmc TCC_HIT_sum TCC_MISS_sum --kernel-trace -d <raw>/pmc_L2_{wl} -o p --output-format csv -- python3 bench.py --workload {wl} --no-cpu-baseline --no-configs --no-hbm-calibration --steps 40 --warmup 4    (optional)",
              f"  python3 bench.py --workload {wl} --no-cpu-baseline --no-configs --no-hbm-calibration --steps 200 --warmup 20    (no profiler)",
              f"  python3 -m paper_2605_06046_amd.profile_summary <raw> {wl} profiles",
              "", "Kernel trace (library kernels only; durations in microseconds)", "",
@@ -101,6 +107,22 @@ def main(raw: str, wl: str, out: str) -> None:
     lines += [f"  total {total / 1e6:.2f} MB per launch; algorithmic (distinct live KV blocks, K and V): "
               f"{res['unique_kv_bytes'] / 1e6:.2f} MB; ratio {total / res['unique_kv_bytes']:.3f}",
               ""]
+    l2 = glob.glob(f"{raw}/pmc_L2_{wl}/**/*counter_collection.csv", recursive=True)
+    if l2:   # requests the L2 served against those it passed on, per kernel
+        acc = {}
+        for r in csv.DictReader(open(l2[0])):
+            if r["Counter_Name"] in ("TCC_HIT_sum", "TCC_MISS_sum") and r["Kernel_Name"].startswith(("fea::", "void fea::")):
+                d = acc.setdefault(r["Kernel_Name"], {"TCC_HIT_sum": 0.0, "TCC_MISS_sum": 0.0, "n": 0})
+                d[r["Counter_Name"]] += float(r["Counter_Value"])
+                d["n"] += r["Counter_Name"] == "TCC_HIT_sum"
+        lines += ["L2 cache (rocprofv3 --pmc TCC_HIT_sum TCC_MISS_sum, requests per launch):"]
+        for k, d in acc.items():
+            n = max(d["n"], 1)
+            tot = d["TCC_HIT_sum"] + d["TCC_MISS_sum"]
+            lines.append(f"  {k[:58]:58s} hits {d['TCC_HIT_sum'] / n:12.0f}  misses {d['TCC_MISS_sum'] / n:12.0f}  hit rate {d['TCC_HIT_sum'] / max(tot, 1):.3f}")
+            if "sweep" in k:
+                res["l2_hit_rate"] = d["TCC_HIT_sum"] / max(tot, 1)
+        lines.append("")
     un = f"{raw}/untraced_{wl}.json"
     if os.path.exists(un):
         b2 = json.loads(open(un).read().strip().splitlines()[-1])
