@@ -502,8 +502,9 @@ int32_t fea_cht_build_batch_learned(fea_cht* t, fea_policy* policy, int32_t max_
  * the merge; which = -1 times all three.  fea_profile_read(c, ms) waits for the c-th
  * call since enabling (0-based) and returns the durations in milliseconds (HOST
  * float[3], zero where not timed, e.g. the first under FEA_FLAG_REUSE_PLAN).
- * fea_profile_enable(0, -1) switches recording off.  Process-wide, not thread-safe;
- * leave it off in production.  Under a profiler that intercepts the launches
+ * fea_profile_enable(0, -1) switches recording off.  Process-wide (calls from several
+ * threads are recorded in the order in which they take their slot; a lock is taken only
+ * while recording is on); leave it off in production.  Under a profiler that intercepts the launches
  * (rocprofv3 and other tools loaded through ROCP_TOOL_LIBRARIES) recording is
  * refused with FEA_EINVAL: the tool times the dispatches itself, and the two ways
  * of attaching to a dispatch are not combined.

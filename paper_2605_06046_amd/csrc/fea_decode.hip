@@ -5,7 +5,9 @@
 
 #include <cmath>
 #include <cstdlib>
+#include <atomic>
 #include <cstring>
+#include <mutex>
 #include <vector>
 
 #include "../../include/fea.h"
@@ -50,7 +52,8 @@ struct Resolved {
 // Optional per-kernel timing: each launch can carry a pair of library-owned events that
 // take the start and end time of that dispatch itself (no marker packets in between).
 constexpr int kEvPerCall = 8;               // (start, stop) for plan, sweep, merge, and the inner pair of a two-dispatch plan
-static bool g_prof_on = false;
+static std::atomic<bool> g_prof_on{false};  // read without the lock on every call; everything below is under g_prof_mu
+static std::mutex g_prof_mu;
 static std::vector<hipEvent_t> g_ev_pool;   // kEvPerCall events per recorded call
 static int g_prof_calls = 0;                // calls recorded since profiling was switched on
 static int g_prof_which = -1;               // -1: all three launches; 0, 1, 2: only that one
@@ -230,7 +233,9 @@ int32_t decode_impl(const fea_attn_params* p, const void* q, const void* k_cache
 
     const float scale = p->scale > 0.f ? p->scale : 1.0f / std::sqrt((float)p->head_dim);
     Launch where[3] = {{hip_stream, nullptr, nullptr}, {hip_stream, nullptr, nullptr}, {hip_stream, nullptr, nullptr}};
-    if (g_prof_on && !g_ev_pool.empty()) {
+    std::unique_lock<std::mutex> prof_lock(g_prof_mu, std::defer_lock);
+    if (g_prof_on.load(std::memory_order_relaxed)) prof_lock.lock();   // (calls of several threads take their slots one after the other)
+    if (prof_lock.owns_lock() && g_prof_on.load() && !g_ev_pool.empty()) {
         const size_t slot = (size_t)(g_prof_calls % (int)(g_ev_pool.size() / kEvPerCall));
         hipEvent_t* ev = &g_ev_pool[kEvPerCall * slot];
         unsigned char mask = 0;
@@ -247,6 +252,7 @@ int32_t decode_impl(const fea_attn_params* p, const void* q, const void* k_cache
         g_prof_mask[slot] = mask;
         ++g_prof_calls;
     }
+    if (prof_lock.owns_lock()) prof_lock.unlock();
     if (!(p->flags & FEA_FLAG_REUSE_PLAN) && (plan_only || !r.fused)) {   // a new plan, or the one in the workspace stretched to the lengths of now
         PlanArgs pa;
         std::memset(&pa, 0, sizeof pa);
@@ -330,6 +336,7 @@ int32_t fea_profile_enable(int32_t max_calls, int32_t which) {
         return fail(FEA_EINVAL, "fea_profile_enable: a profiling tool is attached to this process (ROCP_TOOL_LIBRARIES); "
                                 "it times the dispatches itself, the library's events stay off");
     return guarded("fea_profile_enable", [&]() -> int32_t {
+    std::lock_guard<std::mutex> lock(g_prof_mu);
     g_prof_which = which;
     while ((int)g_ev_pool.size() < kEvPerCall * max_calls) {
         hipEvent_t ev;
@@ -346,6 +353,7 @@ int32_t fea_profile_enable(int32_t max_calls, int32_t which) {
 
 int32_t fea_profile_read(int32_t call, float* ms) {
     if (!ms) return fail(FEA_EINVAL, "fea_profile_read: ms is NULL");
+    std::lock_guard<std::mutex> lock(g_prof_mu);
     const int slots = (int)(g_ev_pool.size() / kEvPerCall);
     if (call < 0 || call >= g_prof_calls || g_prof_calls - call > slots)
         return fail(FEA_EINVAL, "fea_profile_read: call %d was not recorded (or its events were reused)", call);

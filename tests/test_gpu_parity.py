@@ -795,3 +795,56 @@ def test_one_launch_on_rows_longer_than_its_table_buffer(dtype, Hq, Hkv, d):
     out, bt, lens, info = run_workload(wl, fused_max=1 << 20, max_group=1, split_blocks=6)
     assert bt.shape[1] > 512 and lens.max() > 8192 + 16 and info["variant"] == 2
     assert_close(out, oracle_for(wl, bt, lens), dtype, what=f"one launch, long rows {dtype} {Hq}/{Hkv}/{d}")
+
+
+def test_calls_from_two_threads_on_streams_and_workspaces_of_their_own():
+    """Nothing in a call is shared between callers but the read-only tuning (and, while it is on, the recording of
+    kernel durations, which takes a lock): two threads, each with its stream, workspace and output, give what one does."""
+    import threading
+    import torch
+    from paper_2605_06046_amd import (AttnParams, FEA_DTYPE_BF16, fea_decode_attention, fea_decode_workspace_bytes,
+                                      fea_profile_enable, fea_profile_read)
+    from gpu_harness import to_device
+    wls = [W.generate(W.scaled(W.CONFIGS[n], **SMALL[n])) for n in ("c2", "c3")]
+    jobs = []
+    for wl in wls:
+        bt, lens = library_tables(wl)
+        s = wl.spec
+        p = AttnParams(s.num_q_heads, s.num_kv_heads, s.head_dim, FEA_DTYPE_BF16, fused_max=-1)
+        q, k, v = to_device(wl.q), to_device(wl.k_cache), to_device(wl.v_cache)
+        dbt, dl = torch.from_numpy(bt).cuda(), torch.from_numpy(lens).cuda()
+        ws = torch.empty(fea_decode_workspace_bytes(p, s.batch, bt.shape[1]), dtype=torch.uint8, device="cuda")
+        ref = torch.empty_like(q)
+        fea_decode_attention(p, q, k, v, dbt, dl, ref, ws)
+        jobs.append(dict(p=p, q=q, k=k, v=v, dbt=dbt, dl=dl, ws=ws, ref=ref, outs=[], stream=torch.cuda.Stream(), err=None))
+    torch.cuda.synchronize()
+
+    def work(j):
+        try:
+            for out in j["outs"]:
+                fea_decode_attention(j["p"], j["q"], j["k"], j["v"], j["dbt"], j["dl"], out, j["ws"], stream=j["stream"])
+            j["stream"].synchronize()
+        except Exception as e:   # surfaces in the main thread
+            j["err"] = e
+
+    for recording in (False, True):
+        if recording:
+            fea_profile_enable(64, -1)
+        try:
+            for j in jobs:      # outputs made (and poisoned) here, so that the threads only make the library's calls
+                j["outs"] = [torch.full_like(j["q"], float("nan")) for _ in range(25)]
+            torch.cuda.synchronize()
+            threads = [threading.Thread(target=work, args=(j,)) for j in jobs]
+            for t in threads:
+                t.start()
+            for t in threads:
+                t.join()
+            for j in jobs:
+                assert j["err"] is None, j["err"]
+                assert len(j["outs"]) == 25 and all(torch.equal(o, j["ref"]) for o in j["outs"])
+            if recording:
+                ms = [fea_profile_read(c) for c in range(50)]
+                assert all(m[1] > 0 for m in ms)
+        finally:
+            if recording:
+                fea_profile_enable(0, -1)
