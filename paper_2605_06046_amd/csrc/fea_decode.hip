@@ -81,15 +81,17 @@ static int cu_count() {
 static bool fused_pays(const fea_attn_params* p, int64_t B, int64_t stride, int variant) {
     const bool f32 = p->dtype == FEA_DTYPE_F32;
     const int64_t rounds = (B * p->num_kv_heads + cu_count() - 1) / cu_count();
-    const int64_t passes = (p->num_q_heads / p->num_kv_heads + 3) / 4;
+    const int per_pass = f32 && p->num_q_heads / p->num_kv_heads > 4 ? 8 : 4;   // query heads the kernel takes per pass
+    const int64_t passes = (p->num_q_heads / p->num_kv_heads + per_pass - 1) / per_pass;
     const double tokens = (double)stride * kBlock, dd = p->head_dim / 64.0;
-    const double fused_us = 2.4 + (double)(rounds * passes) * (6.0 + (f32 ? 0.0165 : 0.0096) * dd * tokens);
+    const double fused_us = 2.4 + (double)(rounds * passes) * (6.0 + (f32 ? 0.0165 : 0.0096) * (per_pass == 8 ? 1.7 : 1.0) * dd * tokens);
     double planned_us;
     if (variant == 1) {
         planned_us = (B < 2 ? 22.0 : B < 16 ? 27.0 : B <= 64 ? 31.0 : 35.0) +
                      (0.03 + 0.003 * (double)B) * (double)stride * (p->num_kv_heads * p->head_dim / 1024.0);
     } else {
-        planned_us = (B < 4 ? 24.0 : B < 16 ? 40.0 : 94.0) * (p->head_dim >= 128 ? 1.4 : 1.0) +
+        const bool wide = p->num_q_heads / p->num_kv_heads > 4;
+        planned_us = (B < 4 ? 24.0 * (wide ? 1.4 : 1.0) : B < 16 ? 40.0 * (wide ? 1.4 : 1.0) : 94.0) * (p->head_dim >= 128 ? 1.4 : 1.0) +
                      (f32 ? 0.027e-3 : 0.0175e-3) * std::pow(dd, 1.6) * (double)(B * p->num_q_heads) * tokens;
     }
     return 1.1 * fused_us < planned_us;

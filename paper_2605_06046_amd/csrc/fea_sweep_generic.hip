@@ -426,23 +426,25 @@ __global__ __launch_bounds__(256) void merge_rows_kernel(SweepArgs a) {
 // own (a few requests with short histories, where three dependent launches and the planner's one
 // workgroup cost several times what the attention does).  One workgroup per (request, KV head) walks the
 // request's whole history: every lane group keeps the online-softmax state (m, l, acc) of the token rows it
-// visits - kSmallAhead rows in flight per lane, requested together and folded into the state with one
+// visits - several rows in flight per lane, requested together and folded into the state with one
 // change of the reference exponent - and the states are folded over the wave's lane groups, then over
 // the waves through LDS, normalised and written as out[i, h, :] = softmax(q K^T * scale) V (Section 2.1).
 // No plan is read or made: a block that several requests alias is read once per request, out of L2
 // after the first.
 constexpr int kSmallThreads = 512;
 constexpr int kSmallWaves = kSmallThreads / 64;
-constexpr int kSmallRows = 4;      // query heads per pass over the history
-constexpr int kSmallAhead = 8;     // token rows a lane has in flight
+// Query heads per pass over the history and token rows a lane has in flight: 4 and 8, or - for query groups of
+// more than 4 heads over float32 caches, where the number of passes counts - 8 and 4 (the registers hold one or
+// the other; with 16-bit caches a lane carries 8 elements per head, and 8 heads do not fit).
 constexpr int kSmallCols = 512;    // table entries of the request kept in LDS (longer rows read the rest from memory)
 
-template <typename T, int D>
+template <typename T, int D, int RB>
 __global__ __launch_bounds__(kSmallThreads) void decode_small_kernel(SweepArgs a) {
     constexpr int EPL = Elem<T>::kPerLoad;
     constexpr int LPT = D / EPL;          // lanes that share one token row
     constexpr int TPW = 64 / LPT;         // token rows per wave-wide load
-    constexpr int RB = kSmallRows, U = kSmallAhead;
+    constexpr int U = RB == 4 ? 8 : 4;
+    static_assert(RB == 4 || RB == 8, "4 or 8 query heads per pass");
     constexpr int STEP = kSmallWaves * TPW;
     using Raw = typename Elem<T>::Raw;
     __shared__ float s_acc[kSmallWaves][RB][D];
@@ -665,23 +667,23 @@ void launch_merge(const SweepArgs& a, int dtype, int head_dim, bool by_rows, con
     else launch_merge_t<bf16_t>(a, head_dim, by_rows, L);
 }
 
-template <typename T>
+template <typename T, int RB>
 static void launch_small_t(const SweepArgs& a, int head_dim, const Launch& L) {
     hipStream_t st = static_cast<hipStream_t>(L.stream);
     hipEvent_t e0 = static_cast<hipEvent_t>(L.ev_start), e1 = static_cast<hipEvent_t>(L.ev_stop);
     const int grid = a.B * a.Hkv;
     switch (head_dim) {
-        case 32: hipExtLaunchKernelGGL((decode_small_kernel<T, 32>), dim3(grid), dim3(kSmallThreads), 0, st, e0, e1, 0, a); break;
-        case 64: hipExtLaunchKernelGGL((decode_small_kernel<T, 64>), dim3(grid), dim3(kSmallThreads), 0, st, e0, e1, 0, a); break;
-        case 128: hipExtLaunchKernelGGL((decode_small_kernel<T, 128>), dim3(grid), dim3(kSmallThreads), 0, st, e0, e1, 0, a); break;
-        case 256: hipExtLaunchKernelGGL((decode_small_kernel<T, 256>), dim3(grid), dim3(kSmallThreads), 0, st, e0, e1, 0, a); break;
+        case 32: hipExtLaunchKernelGGL((decode_small_kernel<T, 32, RB>), dim3(grid), dim3(kSmallThreads), 0, st, e0, e1, 0, a); break;
+        case 64: hipExtLaunchKernelGGL((decode_small_kernel<T, 64, RB>), dim3(grid), dim3(kSmallThreads), 0, st, e0, e1, 0, a); break;
+        case 128: hipExtLaunchKernelGGL((decode_small_kernel<T, 128, RB>), dim3(grid), dim3(kSmallThreads), 0, st, e0, e1, 0, a); break;
+        case 256: hipExtLaunchKernelGGL((decode_small_kernel<T, 256, RB>), dim3(grid), dim3(kSmallThreads), 0, st, e0, e1, 0, a); break;
         default: break;
     }
 }
 
 void launch_decode_small(const SweepArgs& a, int dtype, int head_dim, const Launch& L) {
-    if (dtype == FEA_DTYPE_F32) launch_small_t<float>(a, head_dim, L);
-    else launch_small_t<bf16_t>(a, head_dim, L);
+    if (dtype == FEA_DTYPE_F32) { if (a.G > 4) launch_small_t<float, 8>(a, head_dim, L); else launch_small_t<float, 4>(a, head_dim, L); }
+    else launch_small_t<bf16_t, 4>(a, head_dim, L);
 }
 
 }  // namespace fea

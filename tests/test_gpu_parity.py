@@ -750,10 +750,12 @@ def test_c1_takes_one_launch_by_default():
 
 @pytest.mark.parametrize("mode", ["random", "same_first_then_random", "nested", "all_same_block", "identical_rows"])
 @pytest.mark.parametrize("dtype,Hq,Hkv,d", [("f32", 8, 2, 64), ("f32", 4, 4, 32), ("f32", 6, 2, 128), ("f32", 2, 1, 256),
+                                            ("f32", 16, 2, 64), ("f32", 24, 2, 128), ("f32", 5, 1, 32), ("f32", 8, 1, 256),
                                             ("bf16", 32, 8, 128), ("bf16", 10, 2, 128), ("bf16", 16, 4, 64), ("bf16", 9, 1, 256)])
 def test_any_block_table_in_one_launch(mode, dtype, Hq, Hkv, d):
-    """Empty, one-token, block-edge and ragged histories; query groups of 1 to 9 heads (up to three passes of four);
-    every cache type and head dim; tables that alias anywhere."""
+    """Empty, one-token, block-edge and ragged histories; query groups of 1 to 12 heads (passes of four heads, of
+    eight for wide groups over float32 caches, the last pass ragged); every cache type and head dim; tables that
+    alias anywhere."""
     lens = [0, 1, 15, 16, 17, 160, 161, 500, 512, 33, 160, 160, 700, 2, 48, 31]
     B = len(lens)
     seed = {"random": 111, "same_first_then_random": 212, "nested": 313, "all_same_block": 414, "identical_rows": 515}[mode]
