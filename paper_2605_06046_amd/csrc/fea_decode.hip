@@ -77,24 +77,31 @@ static int cu_count() {
 // token in proportion to the head dim.  The three launches cost their start-up and the planner's one workgroup,
 // then the KV bytes of the requests' own columns on the matrix-core path; the vector-unit sweep costs far more
 // to start with, and from some hundred thousand (query row, token) pairs on in proportion to them.  The one
-// launch is taken where it wins by a tenth.
+// launch is taken where it wins by a tenth (more where its workgroups need several rounds on the chip).
 static bool fused_pays(const fea_attn_params* p, int64_t B, int64_t stride, int variant) {
     const bool f32 = p->dtype == FEA_DTYPE_F32;
     const int64_t rounds = (B * p->num_kv_heads + cu_count() - 1) / cu_count();
     const int per_pass = f32 && p->num_q_heads / p->num_kv_heads > 4 ? 8 : 4;   // query heads the kernel takes per pass
     const int64_t passes = (p->num_q_heads / p->num_kv_heads + per_pass - 1) / per_pass;
     const double tokens = (double)stride * kBlock, dd = p->head_dim / 64.0;
-    const double fused_us = 2.4 + (double)(rounds * passes) * (6.0 + (f32 ? 0.0165 : 0.0096) * (per_pass == 8 ? 1.7 : 1.0) * dd * tokens);
+    // (passes of one query group run side by side on 2, 4 or 8 sets of the workgroup's waves: their fixed part is
+    // paid once per round of passes, their work per token adds up as if they ran one after the other)
+    int64_t sets = 1;
+    while (sets < 8 && sets < passes) sets <<= 1;
+    const int64_t seq = (passes + sets - 1) / sets;
+    const double fused_us = 2.4 + (double)rounds * ((double)seq * 6.0 + (double)(seq * sets) * (f32 ? 0.0165 : 0.0096) *
+                                                                         (per_pass == 8 ? 1.7 : 1.0) * dd * tokens);
     double planned_us;
     if (variant == 1) {
-        planned_us = (B < 2 ? 22.0 : B < 16 ? 27.0 : B <= 64 ? 31.0 : 35.0) +
+        planned_us = (B < 2 ? 22.0 : B < 16 ? 27.0 : B <= 64 ? 31.0 : 35.0) + (p->head_dim == 256 ? 4.0 : 0.0) +
                      (0.03 + 0.003 * (double)B) * (double)stride * (p->num_kv_heads * p->head_dim / 1024.0);
     } else {
-        const bool wide = p->num_q_heads / p->num_kv_heads > 4;
-        planned_us = (B < 4 ? 24.0 * (wide ? 1.4 : 1.0) : B < 16 ? 40.0 * (wide ? 1.4 : 1.0) : 94.0) * (p->head_dim >= 128 ? 1.4 : 1.0) +
+        const double G = (double)(p->num_q_heads / p->num_kv_heads);   // (the vector sweep passes over its tokens once per 4 or 16 stacked rows)
+        const double base = B < 4 ? 20.0 + 1.5 * G : std::min(30.0 + 4.0 * G, 120.0);
+        planned_us = (B < 16 ? base : std::max(94.0, base)) * (p->head_dim >= 128 ? 1.4 : 1.0) +
                      (f32 ? 0.027e-3 : 0.0175e-3) * std::pow(dd, 1.6) * (double)(B * p->num_q_heads) * tokens;
     }
-    return 1.1 * fused_us < planned_us;
+    return (1.1 + 0.05 * (double)(rounds - 1)) * fused_us < planned_us;   // (several rounds of workgroups take longer than their sum)
 }
 
 static int32_t check_params(const fea_attn_params* p, const char* who) {

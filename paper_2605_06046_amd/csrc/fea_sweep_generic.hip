@@ -445,7 +445,6 @@ __global__ __launch_bounds__(kSmallThreads) void decode_small_kernel(SweepArgs a
     constexpr int TPW = 64 / LPT;         // token rows per wave-wide load
     constexpr int U = RB == 4 ? 8 : 4;
     static_assert(RB == 4 || RB == 8, "4 or 8 query heads per pass");
-    constexpr int STEP = kSmallWaves * TPW;
     using Raw = typename Elem<T>::Raw;
     __shared__ float s_acc[kSmallWaves][RB][D];
     __shared__ float2 s_ml[kSmallWaves][RB];
@@ -466,8 +465,19 @@ __global__ __launch_bounds__(kSmallThreads) void decode_small_kernel(SweepArgs a
     for (int x = tid; x < min((L + kBlock - 1) / kBlock, kSmallCols); x += kSmallThreads) s_row[x] = max(row[x], 0);
     __syncthreads();
 
-    for (int row0 = 0; row0 < a.G; row0 += RB) {
-        const int nh = min(RB, a.G - row0);
+    // A query group of more than RB heads takes several passes over the history.  They run side by side where they
+    // can: the 8 waves form 2, 4 or 8 sets, each set with a pass of its own over all tokens (the work per wave is
+    // the same as with one pass after the other on all waves, but the fixed part of a pass - the dependent loads at
+    // its start, the folds at its end - is paid once for the passes of a round).
+    const int passes = (a.G + RB - 1) / RB;
+    int nsets = 1;
+    while (nsets < kSmallWaves && nsets < passes) nsets <<= 1;
+    const int wps = kSmallWaves / nsets;                 // waves per set
+    const int set = wave / wps, wis = wave - set * wps;   // (uniform in a wave)
+    const int STEP = wps * TPW;                           // token rows a set takes per wave-wide load of its waves
+    for (int ps = 0; ps * nsets < passes; ++ps) {
+        const int row0 = (ps * nsets + set) * RB;
+        const int nh = max(0, min(RB, a.G - row0));      // 0: no pass left for this set (it still meets the barriers)
         float qf[RB][EPL], acc[RB][EPL], m[RB], l[RB];
 #pragma unroll
         for (int j = 0; j < RB; ++j) {
@@ -550,7 +560,7 @@ __global__ __launch_bounds__(kSmallThreads) void decode_small_kernel(SweepArgs a
                 }
             }
         };
-        for (int t0 = wave * TPW + r; t0 < L; t0 += U * STEP) {
+        for (int t0 = wis * TPW + r; t0 < (nh > 0 ? L : 0); t0 += U * STEP) {
             // rows of this round that any lane of the wave has (the same in every lane: the first active lane is
             // the one with the lowest token)
             const int left = (L - __builtin_amdgcn_readfirstlane(t0 - r) + STEP - 1) / STEP;
@@ -582,17 +592,19 @@ __global__ __launch_bounds__(kSmallThreads) void decode_small_kernel(SweepArgs a
             }
         }
         __syncthreads();
-        // fold the waves (fixed order), normalise, write 8 elements per thread
-        if (tid < nh * (D / 8)) {
-            const int j = tid / (D / 8), c8 = tid % (D / 8);
+        // fold the waves of every set (fixed order), normalise, write 8 elements per thread
+        for (int x = tid; x < nsets * RB * (D / 8); x += kSmallThreads) {
+            const int sf = x / (RB * (D / 8)), y = x - sf * (RB * (D / 8));
+            const int j = y / (D / 8), c8 = y % (D / 8);
+            const int head = (ps * nsets + sf) * RB + j;
+            if (head >= a.G) continue;
+            const int w0 = sf * wps, w1 = w0 + wps;
             float M = -INFINITY;
-#pragma unroll
-            for (int w = 0; w < kSmallWaves; ++w) M = fmaxf(M, s_ml[w][j].x);
+            for (int w = w0; w < w1; ++w) M = fmaxf(M, s_ml[w][j].x);
             float den = 0.f, num[8];
 #pragma unroll
             for (int k = 0; k < 8; ++k) num[k] = 0.f;
-#pragma unroll
-            for (int w = 0; w < kSmallWaves; ++w) {
+            for (int w = w0; w < w1; ++w) {
                 const float2 v = s_ml[w][j];
                 const float f = v.x == -INFINITY ? 0.f : exp2f(v.x - M);
                 den = fmaf(f, v.y, den);
@@ -602,7 +614,7 @@ __global__ __launch_bounds__(kSmallThreads) void decode_small_kernel(SweepArgs a
             const float inv = den > 0.f ? 1.f / den : 0.f;   // an empty history gives a zero row
 #pragma unroll
             for (int k = 0; k < 8; ++k) num[k] *= inv;
-            Elem<T>::store8(out + (size_t)(row0 + j) * D + c8 * 8, num);
+            Elem<T>::store8(out + (size_t)head * D + c8 * 8, num);
         }
         __syncthreads();
     }
