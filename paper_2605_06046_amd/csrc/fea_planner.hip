@@ -569,6 +569,14 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
     }
     // lcp[] and flw[] are dead from here on; run/cnt hold every group's run (the shortest
     // common run over its members) and size, my_rank the arrival at the group's counter
+    // A run swept by teams is cut to an even number of columns (tiles are two columns; a piece with a column left
+    // over is not taken by a team, and the waves that sweep it on their own hold up the team they share a
+    // workgroup with).  The members read the column left over with their own ones, out of L2 after the first.
+    if (teams) {
+        for (int i = tid; i < nG; i += kPlanThreads)
+            if (s_lead[i] == i && u.c.cnt[i] > a.mpt) u.c.run[i] &= ~1;
+        __syncthreads();
+    }
     auto viable = [&](int i) { return s_lead[i] == i && u.c.cnt[i] >= 2 && u.c.run[i] >= a.tune.min_run; };
 
     // ---- member-list offsets (exclusive scan over leaders) and the list of groups
@@ -859,7 +867,12 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
             const int cnt = u.c.cnt[ld], run = u.c.run[ld];
             const int tiles_r = by_mpt.cdiv(cnt), T_seg = (run + 1) >> 1;
             const int n_pc = v.g.npc[gi];
-            const int ps = fixed_tiles > 0 ? fixed_tiles : (T_seg + n_pc - 1) / n_pc;   // tiles per piece
+            // tiles per piece: the fixed split's, or the run's tiles dealt out evenly (the first `extra` pieces hold one
+            // more).  A short last piece would not be worth a team, and the pair of waves sweeping it on their own
+            // would sit in a workgroup with a team: its barriers wait for every wave of the workgroup that is still
+            // running, so that team would start only when those two had finished.
+            const int ps = fixed_tiles > 0 ? fixed_tiles : T_seg / n_pc;
+            const int extra = fixed_tiles > 0 ? 0 : T_seg - ps * n_pc;
             if (l0 == 0) {
                 GroupDesc gd;
                 gd.leader = ld;
@@ -886,7 +899,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
                 }
                 const int rest = by_tp.div(k), tau = k - rest * tiles_p;
                 const int g = by_pc.div(rest), pc = rest - g * n_pc;
-                const int cs = 2 * pc * ps, ce = min(run, 2 * (pc + 1) * ps);
+                const int cs = 2 * (pc * ps + min(pc, extra)), ce = min(run, cs + 2 * (ps + (pc < extra ? 1 : 0)));
                 const int g_team = g | (team << 16) | ((team ? (tau & (team - 1)) : 0) << 20);   // KV head, team size, rank in the team
                 if (tau >= tiles_r) {                  // no rows of its own: a team member that only fetches
                     write_item(dst, ld, g_team, 0, -1, cs, ce, 0, ce * kBlock);

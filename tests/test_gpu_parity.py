@@ -609,6 +609,20 @@ def test_shared_runs_swept_by_teams_of_waves(B, Hq, Hkv, scores):
         assert np.abs(want).max() > 0.5          # the softmax sits on the last prefix tokens: outputs are O(1)
 
 
+@pytest.mark.parametrize("B,prefix", [(24, 2064), (32, 1968), (64, 2096), (96, 1040), (150, 784)])
+def test_runs_of_odd_length_and_uneven_pieces_swept_by_teams(B, prefix):
+    """Shared runs of an odd number of blocks, and of lengths that no number of pieces divides: a team takes an even
+    number of columns, so the planner leaves a run's last odd column to the members' own sweeps (the plan reports
+    one shared block less) and deals the tiles out evenly over the pieces."""
+    spec = W.Spec("teams_odd", 63, "bf16", 32, 8, 128, ((B, prefix),), (1, 75))
+    wl = W.generate(spec)
+    out, bt, lens, info = run_workload(wl)
+    blocks = prefix // 16
+    assert info["groups"] == 1 and info["grouped_requests"] == B and info["overflow"] == 0
+    assert info["shared_blocks"] == blocks - (blocks & 1)
+    assert_close(out, oracle_for(wl, bt, lens), "bf16", what=f"teams on a run of {blocks} blocks, B={B}")
+
+
 def test_long_pieces_of_a_shared_run_swept_by_teams():
     """200 requests on a 16 384-token prefix: 13 row tiles per KV head take most of the waves, so the run is cut
     into few pieces of more than 128 columns each (the teams' block-id table holds up to 1024); sampled requests
