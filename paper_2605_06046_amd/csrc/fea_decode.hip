@@ -29,13 +29,13 @@ static int env_int(const char* name, int dflt) {
 // second thread sets) cannot switch kernels or move the workspace layout between the
 // sizing call and the attention call.  What tests need to steer is in fea_attn_params.
 struct Knobs {
-    int force_generic, sweep_grid, spare_waves, min_piece, min_run, w32, w64, no_fast_shared, w_team, w_team2;
+    int force_generic, sweep_grid, spare_waves, min_piece, min_run, w32, w64, no_fast_shared, w_team, w_team2, team_fixed;
 };
 static const Knobs& knobs() {
     static const Knobs k = {env_int("FEA_FORCE_GENERIC", 0), env_int("FEA_SWEEP_GRID", 0), env_int("FEA_SPARE_WAVES", 16),
                             env_int("FEA_MIN_PIECE", 4),     env_int("FEA_MIN_RUN", 2),    env_int("FEA_W32", 20),
                             env_int("FEA_W64", 24), env_int("FEA_NO_FAST_SHARED", 0), env_int("FEA_WTEAM", 12),
-                            env_int("FEA_WTEAM2", 12)};
+                            env_int("FEA_WTEAM2", 12), env_int("FEA_TEAM_FIXED", 40)};
     return k;
 }
 
@@ -154,6 +154,7 @@ static int32_t resolve(const fea_attn_params* p, int32_t B, int32_t stride, Reso
     r.tune.n_waves = std::max(1, r.grid - std::min(r.grid / 2, std::max(0, kn.spare_waves)));
     r.tune.min_piece = std::max(1, kn.min_piece);
     r.tune.min_run = std::max(1, kn.min_run);
+    r.tune.team_fixed = std::min(4096, std::max(0, kn.team_fixed));
     r.tune.weights = std::min(255, std::max(16, kn.w32)) | (std::min(255, std::max(16, kn.w64)) << 8) |
                      (std::min(255, std::max(1, kn.w_team)) << 16) | (std::min(127, std::max(1, kn.w_team2)) << 24);
     // Large tables: the rows are compared on many workgroups before the planner's one workgroup

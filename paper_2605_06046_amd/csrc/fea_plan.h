@@ -83,6 +83,7 @@ struct PlanTuning {
     int32_t n_waves;        // sweep waves the work is cut for (the sweep kernel's grid)
     int32_t min_piece;      // a wave gets at least this many 32-token tiles (fewer waves get work instead)
     int32_t min_run;        // shortest aliased run worth sweeping jointly
+    int32_t team_fixed;     // what a piece costs a wave of a team of 2 before its first tile and after its last, in the units of the tile weights
     int32_t weights;        // cost of a 32-token tile to the wave that sweeps it, in sixteenths of a 16-row tile a wave streams
                             // alone: with <= 32 query rows | with <= 64 << 8 | as one of a team of 4 waves << 16 | of 2 << 24
 };

@@ -397,6 +397,11 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
         const int tiles_r = by_mpt.cdiv(cnt);
         return (teams && tiles_r >= 2) ? (tiles_r == 2 ? w_team2 : w_team) : tile_weight(min(a.mpt, cnt) * a.G);
     };
+    // ... and what a piece costs the two waves of a small team besides its tiles: they fill the table of block ids
+    // and the ring before the first tile, and drain it after the last, with half the lanes a team of 4 has for it
+    // (measured: 32 requests on one 4096-token prefix 26.2 -> 24.6 us; with the same charge on teams of 4, whose
+    // pieces it shortens as well, the 64-request batch lost 0.5 us to the merge of the extra pieces)
+    auto group_fixed = [&](int cnt) { return (teams && by_mpt.cdiv(cnt) == 2) ? a.tune.team_fixed : 0; };
 
     // ---- nested prefixes.  Members of a group may go on sharing blocks past the group's
     // run (a common system prompt, then a few conversations: the radix patterns of
@@ -675,7 +680,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
         const int n_act = (int)max(1ll, min((long long)a.tune.n_waves, ddiv(total_tiles, max(a.tune.min_piece, 1))));
         // Pieces of a group's run of T_seg tiles when a share may cost Q.
         auto pieces = [&](int cnt, int T_seg, int Q) {
-            const int want = fixed_tiles > 0 ? fixed_tiles : max(1, idiv(Q, group_weight(cnt)));
+            const int want = fixed_tiles > 0 ? fixed_tiles : max(1, idiv(max(Q - group_fixed(cnt), 0), group_weight(cnt)));
             return idiv(T_seg + want - 1, want);
         };
         // shares of the private stream at cost Q per share, and their tiles
@@ -698,7 +703,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) {
                 const int ld = w.glist[gi], cnt = u.c.cnt[ld], T_seg = (u.c.run[ld] + 1) >> 1;
                 const int n_pc = pieces(cnt, T_seg, Qc);
                 slots += items_padded(Hkv * tiles_padded(by_mpt.cdiv(cnt)) * n_pc);
-                longest = max(longest, ((T_seg + n_pc - 1) / n_pc) * group_weight(cnt));
+                longest = max(longest, ((T_seg + n_pc - 1) / n_pc) * group_weight(cnt) + group_fixed(cnt));
             }
             int qq = 0;
             if (T_pr > 0) {
